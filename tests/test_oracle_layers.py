@@ -1,0 +1,326 @@
+"""Pins for the CPU oracle's layers: closed forms, brute-force loops, library routines
+applied to explicitly copied slices, and the invariants of weight slicing
+(masked-full == sliced, prefix nesting, additivity; Section 3.2, Eq. 7-8)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import ds_oracle as O
+
+RNG = np.random.default_rng(20260101)
+
+
+def t64(a):
+    return torch.from_numpy(np.asarray(a, np.float64))
+
+
+# ------------------------------------------------------------------ bf16 rounding
+def test_bf16_round_matches_library_conversion():
+    x = RNG.standard_normal(20000).astype(np.float32) * np.float32(3.7)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.bf16_round(x.astype(np.float64))
+    assert np.array_equal(got, want)
+
+
+def test_bf16_round_ties_to_even_and_fixed_points():
+    ulp = 2.0 ** -7                      # spacing of bf16 in [1, 2)
+    assert O.bf16_round(1.0 + ulp / 2) == 1.0              # tie -> even mantissa (1.0)
+    assert O.bf16_round(1.0 + 3 * ulp / 2) == 1.0 + 2 * ulp  # tie -> even mantissa
+    assert O.bf16_round(1.0 + ulp / 2 + 1e-9) == 1.0 + ulp
+    assert O.bf16_round(0.0) == 0.0
+    assert O.bf16_round(-2.5) == -2.5
+    v = O.bf16_round(RNG.standard_normal(100))
+    assert np.array_equal(O.bf16_round(v), v)              # idempotent
+
+
+# ------------------------------------------------------------------ sliced linear
+def test_linear_full_ratio_is_static_layer():
+    x, w, b = RNG.standard_normal((5, 12)), RNG.standard_normal((20, 12)), RNG.standard_normal(20)
+    want = F.linear(t64(x), t64(w), t64(b)).numpy()
+    np.testing.assert_allclose(O.sliced_linear(x, w, b, 20), want, rtol=1e-13, atol=1e-13)
+
+
+def test_linear_brute_force():
+    x, w, b = RNG.standard_normal((3, 7)), RNG.standard_normal((9, 11)), RNG.standard_normal(9)
+    k_in, k_out = 7, 5
+    want = np.zeros((3, k_out))
+    for m in range(3):
+        for o in range(k_out):
+            acc = b[o]
+            for i in range(k_in):
+                acc += w[o, i] * x[m, i]
+            want[m, o] = acc
+    np.testing.assert_allclose(O.sliced_linear(x, w, b, k_out), want, rtol=1e-13, atol=1e-13)
+
+
+def test_linear_masked_full_equals_sliced():
+    K, N, k_in, k_out = 16, 24, 10, 14
+    x = RNG.standard_normal((4, K))
+    w, b = RNG.standard_normal((N, K)), RNG.standard_normal(N)
+    wm = w.copy(); wm[k_out:, :] = 0; wm[:, k_in:] = 0
+    xm = x.copy(); xm[:, k_in:] = 0
+    full = F.linear(t64(xm), t64(wm), t64(b)).numpy()[:, :k_out]
+    np.testing.assert_allclose(O.sliced_linear(x[:, :k_in], w, b, k_out), full, rtol=1e-13, atol=1e-13)
+
+
+def test_linear_prefix_nesting_and_additivity():
+    K, N = 16, 24
+    x, w = RNG.standard_normal((4, K)), RNG.standard_normal((N, K))
+    y_small = O.sliced_linear(x[:, :8], w, None, 10)
+    y_big = O.sliced_linear(x[:, :8], w, None, 20)
+    assert np.array_equal(y_big[:, :10], y_small)          # output-prefix nesting
+    k1, k2 = 6, 13                                          # Eq. 8 additivity over the input slice
+    y1 = O.sliced_linear(x[:, :k1], w, None, N)
+    y2 = O.sliced_linear(x[:, :k2], w, None, N)
+    np.testing.assert_allclose(y2, y1 + x[:, k1:k2] @ w[:, k1:k2].T, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ sliced conv
+@pytest.mark.parametrize("K,stride,pad", [(3, 1, 1), (3, 2, 1), (1, 1, 0), (1, 2, 0), (7, 2, 3)])
+def test_conv_matches_library_on_copied_slice(K, stride, pad):
+    C_O, C_I, c_o, c_i, H, W = 10, 9, 6, 5, 11, 12
+    x = RNG.standard_normal((c_i, H, W))
+    w = RNG.standard_normal((C_O, C_I, K, K))
+    want = F.conv2d(t64(x)[None], t64(w[:c_o, :c_i].copy()), stride=stride, padding=pad)[0].numpy()
+    got = O.sliced_conv2d(x, w, c_o, stride, pad)
+    assert got.shape == want.shape
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_conv_brute_force_seven_loops():
+    C_O, C_I, c_o, c_i, H, W, K, s, p = 5, 6, 3, 4, 6, 7, 3, 2, 1
+    x = RNG.standard_normal((c_i, H, W))
+    w = RNG.standard_normal((C_O, C_I, K, K))
+    Ho, Wo = (H + 2 * p - K) // s + 1, (W + 2 * p - K) // s + 1
+    want = np.zeros((c_o, Ho, Wo))
+    for o in range(c_o):
+        for yy in range(Ho):
+            for xx in range(Wo):
+                for i in range(c_i):
+                    for u in range(K):
+                        for v in range(K):
+                            a, b = yy * s + u - p, xx * s + v - p
+                            if 0 <= a < H and 0 <= b < W:
+                                want[o, yy, xx] += w[o, i, u, v] * x[i, a, b]
+    np.testing.assert_allclose(O.sliced_conv2d(x, w, c_o, s, p), want, rtol=1e-12, atol=1e-12)
+
+
+def test_conv_masked_full_nesting_additivity():
+    C_O, C_I, c_o, c_i, H = 8, 8, 5, 3, 6
+    x = RNG.standard_normal((C_I, H, H))
+    w = RNG.standard_normal((C_O, C_I, 3, 3))
+    wm = w.copy(); wm[c_o:] = 0; wm[:, c_i:] = 0
+    xm = x.copy(); xm[c_i:] = 0
+    full = F.conv2d(t64(xm)[None], t64(wm), padding=1)[0].numpy()[:c_o]
+    got = O.sliced_conv2d(x[:c_i], w, c_o, 1, 1)
+    np.testing.assert_allclose(got, full, rtol=1e-12, atol=1e-12)
+    assert np.array_equal(O.sliced_conv2d(x[:c_i], w, C_O, 1, 1)[:c_o], got)
+    y1 = O.sliced_conv2d(x[:2], w, C_O, 1, 1)
+    y2 = O.sliced_conv2d(x[:6], w, C_O, 1, 1)
+    extra = F.conv2d(t64(x[2:6])[None], t64(w[:, 2:6].copy()), padding=1)[0].numpy()
+    np.testing.assert_allclose(y2, y1 + extra, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.sliced_conv2d(x, w, C_O, 1, 1),
+                               F.conv2d(t64(x)[None], t64(w), padding=1)[0].numpy(), rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ depthwise conv
+@pytest.mark.parametrize("stride", [1, 2])
+def test_dwconv_matches_library_and_brute(stride):
+    C, c, H, W = 9, 6, 8, 7
+    x = RNG.standard_normal((c, H, W))
+    w = RNG.standard_normal((C, 1, 3, 3))
+    want = F.conv2d(t64(x)[None], t64(w[:c].copy()), stride=stride, padding=1, groups=c)[0].numpy()
+    got = O.sliced_dwconv2d(x, w, stride, 1)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    ch, yy, xx = 4, 1, 2
+    acc = 0.0
+    for u in range(3):
+        for v in range(3):
+            a, b = yy * stride + u - 1, xx * stride + v - 1
+            if 0 <= a < H and 0 <= b < W:
+                acc += w[ch, 0, u, v] * x[ch, a, b]
+    assert abs(got[ch, yy, xx] - acc) < 1e-12
+    # channel c of the output depends on channel c of the input only
+    x2 = x.copy(); x2[0] += 1.0
+    assert np.array_equal(O.sliced_dwconv2d(x2, w, stride, 1)[1:], got[1:])
+
+
+# ------------------------------------------------------------------ split batch-norm
+def test_re_sbn_matches_library_eval_bn_on_slice_and_closed_form():
+    T, C, c, eps = 3, 10, 7, 1e-5
+    bn = {"gamma": RNG.uniform(0.5, 1.5, C), "beta": RNG.standard_normal(C),
+          "mean": RNG.standard_normal((T, C)), "var": RNG.uniform(0.5, 1.5, (T, C))}
+    x = RNG.standard_normal((c, 4, 5))
+    for t in range(T):
+        want = F.batch_norm(t64(x)[None], t64(bn["mean"][t, :c].copy()), t64(bn["var"][t, :c].copy()),
+                            t64(bn["gamma"][:c].copy()), t64(bn["beta"][:c].copy()), False, 0.0, eps)[0].numpy()
+        got = O.re_sbn(x, bn, t, eps)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    ch = 3
+    v = bn["gamma"][ch] * (x[ch, 1, 2] - bn["mean"][2, ch]) / math.sqrt(bn["var"][2, ch] + eps) + bn["beta"][ch]
+    assert abs(O.re_sbn(x, bn, 2, eps)[ch, 1, 2] - v) < 1e-12
+    # statistics differ per route, so outputs must differ
+    assert not np.allclose(O.re_sbn(x, bn, 0, eps), O.re_sbn(x, bn, 1, eps))
+
+
+# ------------------------------------------------------------------ gate
+def test_gate_encoder_closed_forms():
+    x = np.full((3, 4, 5), 2.5)
+    assert np.array_equal(O.gate_encoder(x), np.full(3, 2.5))
+    x = RNG.standard_normal((4, 6, 5))
+    want = F.adaptive_avg_pool2d(t64(x)[None], 1)[0, :, 0, 0].numpy()
+    np.testing.assert_allclose(O.gate_encoder(x), want, rtol=1e-13, atol=1e-13)
+    ramp = np.arange(12.0).reshape(1, 3, 4)
+    assert O.gate_encoder(ramp)[0] == 5.5
+
+
+def test_gate_logits_brute_force_with_input_slice():
+    C, c, hid, T = 8, 5, 4, 3
+    pooled = RNG.standard_normal(c)
+    w1, b1 = RNG.standard_normal((hid, C)), RNG.standard_normal(hid)
+    w2, b2 = RNG.standard_normal((T, hid)), RNG.standard_normal(T)
+    lb = RNG.standard_normal(T)
+    want = []
+    for t in range(T):
+        acc = b2[t] + lb[t]
+        for j in range(hid):
+            hj = b1[j] + sum(w1[j, i] * pooled[i] for i in range(c))
+            acc += w2[t, j] * max(hj, 0.0)
+        want.append(acc)
+    np.testing.assert_allclose(O.gate_logits(pooled, w1, b1, w2, b2, lb), want, rtol=1e-12, atol=1e-12)
+    want_t = F.linear(torch.relu(F.linear(t64(pooled), t64(w1[:, :c].copy()), t64(b1))), t64(w2), t64(b2)).numpy()
+    np.testing.assert_allclose(O.gate_logits(pooled, w1, b1, w2, b2), want_t, rtol=1e-12, atol=1e-12)
+
+
+def test_gate_route_argmax_ties_and_nan():
+    assert O.gate_route([0.1, 0.7, 0.3]) == 1
+    assert O.gate_route([0.7, 0.7, 0.3]) == 0          # tie -> lowest index
+    assert O.gate_route([0.1, 0.7, 0.7]) == 1
+    assert O.gate_route([float("nan"), 0.2, 0.1]) == 1  # NaN never selected
+    assert O.gate_route([float("nan")] * 3) == 0
+    assert O.gate_route([-1.0]) == 0
+    z = RNG.standard_normal((50, 6))
+    assert [O.gate_route(r) for r in z] == np.argmax(z, axis=1).tolist()
+    assert abs(O.gate_margin([0.1, 0.9, 0.6]) - 0.3) < 1e-12
+
+
+# ------------------------------------------------------------------ route bucket
+@pytest.mark.parametrize("B,T", [(0, 4), (1, 1), (7, 3), (64, 4), (256, 48), (256, 14)])
+def test_route_bucket_invariants(B, T):
+    route = RNG.integers(0, T, B).astype(np.int32)
+    perm, inv, off = O.route_bucket(route, T)
+    assert sorted(perm.tolist()) == list(range(B))                       # a permutation
+    assert np.array_equal(inv[perm], np.arange(B))                        # inverse restores order
+    assert np.array_equal(perm[inv], np.arange(B))
+    assert np.all(np.diff(route[perm]) >= 0)                              # bucket-major
+    assert np.array_equal(np.diff(off), np.bincount(route, minlength=T))  # histogram
+    assert off[0] == 0 and off[T] == B
+    for t in range(T):
+        seg = perm[off[t]:off[t + 1]]
+        assert np.all(np.diff(seg) > 0)                                   # stable
+    assert np.array_equal(perm, np.argsort(route, kind="stable"))         # library routine
+
+
+def test_route_bucket_rejects_bad_ids_and_handles_empty_buckets():
+    with pytest.raises(ValueError):
+        O.route_bucket([0, 4], 4)
+    with pytest.raises(ValueError):
+        O.route_bucket([-1], 4)
+    perm, inv, off = O.route_bucket([3, 3, 0], 5)
+    assert perm.tolist() == [2, 0, 1] and off.tolist() == [0, 1, 1, 1, 3, 3] and inv.tolist() == [1, 2, 0]
+
+
+# ------------------------------------------------------------------ LayerNorm / GELU / softmax / max-pool
+def test_layernorm_on_prefix_matches_library():
+    N, D, d, eps = 5, 16, 10, 1e-6
+    x = RNG.standard_normal((N, d)) * 3 + 1
+    g, b = RNG.standard_normal(D), RNG.standard_normal(D)
+    want = F.layer_norm(t64(x), (d,), t64(g[:d].copy()), t64(b[:d].copy()), eps).numpy()
+    np.testing.assert_allclose(O.layernorm_sliced(x, g, b, eps), want, rtol=1e-12, atol=1e-12)
+    plain = O.layernorm_sliced(x, np.ones(D), np.zeros(D), 0.0)
+    np.testing.assert_allclose(plain.mean(-1), 0, atol=1e-12)
+    np.testing.assert_allclose(plain.var(-1), 1, atol=1e-12)
+
+
+def test_gelu_softmax_maxpool_match_library():
+    x = RNG.standard_normal(1000) * 3
+    np.testing.assert_allclose(O.gelu(x), F.gelu(t64(x)).numpy(), rtol=1e-12, atol=1e-14)
+    assert O.gelu(np.array([0.0]))[0] == 0.0
+    assert abs(O.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-13   # Phi(1)
+    s = RNG.standard_normal((7, 9)) * 5
+    p = O.softmax_rows(s)
+    np.testing.assert_allclose(p.sum(-1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(p, torch.softmax(t64(s), -1).numpy(), rtol=1e-12, atol=1e-15)
+    m = RNG.standard_normal((3, 9, 8))
+    np.testing.assert_allclose(O.maxpool3x3s2(m), F.max_pool2d(t64(m)[None], 3, 2, 1)[0].numpy())
+
+
+# ------------------------------------------------------------------ MHSA
+def _mhsa_params(D, Hd):
+    return dict(wq=RNG.standard_normal((Hd, D)) * 0.2, bq=RNG.standard_normal(Hd) * 0.1,
+                wk=RNG.standard_normal((Hd, D)) * 0.2, bk=RNG.standard_normal(Hd) * 0.1,
+                wv=RNG.standard_normal((Hd, D)) * 0.2, bv=RNG.standard_normal(Hd) * 0.1,
+                wproj=RNG.standard_normal((D, Hd)) * 0.2, bproj=RNG.standard_normal(D) * 0.1)
+
+
+def _mhsa(x, P, h, dh):
+    return O.sliced_mhsa(x, P["wq"], P["bq"], P["wk"], P["bk"], P["wv"], P["bv"], P["wproj"], P["bproj"], h, dh)
+
+
+def test_mhsa_matches_library_on_copied_slices():
+    D, H, dh, N, d_e, h = 12, 4, 4, 7, 8, 3
+    P = _mhsa_params(D, H * dh)
+    x = RNG.standard_normal((N, d_e))
+    hd = h * dh
+    q = F.linear(t64(x), t64(P["wq"][:hd, :d_e].copy()), t64(P["bq"][:hd].copy()))
+    k = F.linear(t64(x), t64(P["wk"][:hd, :d_e].copy()), t64(P["bk"][:hd].copy()))
+    v = F.linear(t64(x), t64(P["wv"][:hd, :d_e].copy()), t64(P["bv"][:hd].copy()))
+    sp = lambda z: z.reshape(N, h, dh).transpose(0, 1)
+    a = F.scaled_dot_product_attention(sp(q), sp(k), sp(v)).transpose(0, 1).reshape(N, hd)
+    want = F.linear(a, t64(P["wproj"][:d_e, :hd].copy()), t64(P["bproj"][:d_e].copy())).numpy()
+    np.testing.assert_allclose(_mhsa(x, P, h, dh), want, rtol=1e-11, atol=1e-12)
+
+
+def test_mhsa_masked_heads_and_degenerate_case():
+    D, H, dh, N, d_e, h = 12, 4, 4, 6, 8, 2
+    P = _mhsa_params(D, H * dh)
+    x = RNG.standard_normal((N, d_e))
+    got = _mhsa(x, P, h, dh)
+    # zero the tail heads' V rows / projection columns and the tail embedding: full layer == sliced
+    Pm = {k: v.copy() for k, v in P.items()}
+    for nm in ("wq", "wk", "wv"):
+        Pm[nm][h * dh:] = 0; Pm[nm][:, d_e:] = 0
+    for nm in ("bq", "bk", "bv"):
+        Pm[nm][h * dh:] = 0
+    Pm["wproj"][:, h * dh:] = 0
+    xm = np.zeros((N, D)); xm[:, :d_e] = x
+    full = _mhsa(xm, Pm, H, dh)[:, :d_e]
+    np.testing.assert_allclose(got, full, rtol=1e-12, atol=1e-12)
+    # one token, one head: softmax of a single score is 1, so out = Wproj[:d_e,:dh] (Wv x + bv) + bproj
+    x1 = RNG.standard_normal((1, d_e))
+    v1 = P["wv"][:dh, :d_e] @ x1[0] + P["bv"][:dh]
+    want = P["wproj"][:d_e, :dh] @ v1 + P["bproj"][:d_e]
+    np.testing.assert_allclose(_mhsa(x1, P, 1, dh)[0], want, rtol=1e-12, atol=1e-12)
+    # full heads and width == static layer
+    D = H * dh
+    P = _mhsa_params(D, H * dh)
+    xf = RNG.standard_normal((N, D))
+    mha = torch.nn.MultiheadAttention(D, H, bias=True, batch_first=True, dtype=torch.float64)
+    with torch.no_grad():
+        mha.in_proj_weight.copy_(t64(np.concatenate([P["wq"], P["wk"], P["wv"]])))
+        mha.in_proj_bias.copy_(t64(np.concatenate([P["bq"], P["bk"], P["bv"]])))
+        mha.out_proj.weight.copy_(t64(P["wproj"])); mha.out_proj.bias.copy_(t64(P["bproj"]))
+        want = mha(t64(xf)[None], t64(xf)[None], t64(xf)[None], need_weights=False)[0][0].numpy()
+    np.testing.assert_allclose(_mhsa(xf, P, H, dh), want, rtol=1e-11, atol=1e-12)
+
+
+def test_patchify_order_matches_strided_conv():
+    D, P_, H = 5, 4, 12
+    img = RNG.standard_normal((3, H, H))
+    w = RNG.standard_normal((D, 3, P_, P_))
+    want = F.conv2d(t64(img)[None], t64(w), stride=P_)[0].reshape(D, -1).T.numpy()
+    got = O.patchify(img, P_) @ w.reshape(D, -1).T
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)

@@ -1,0 +1,214 @@
+"""Pins for the oracle's network assemblies and multiply-add model.
+
+The assemblies are checked against library routines (torch CPU, float64) applied
+layer by layer to explicitly copied weight slices on test-sized networks, and the
+multiply-add model against the counts the paper prints (tests/golden/paper_madds.txt).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import workloads as WL
+from oracle import ds_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_madds.txt")
+
+
+def t64(a):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.float64)))
+
+
+def _gold():
+    out = {}
+    for line in open(GOLD):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, val, tol = line.split()[:3]
+        out[name] = (float(val), float(tol))
+    return out
+
+
+# ------------------------------------------------------------------ multiply-add model
+def _mb_scaled(frac_num, frac_den):
+    a = WL.mbnet_arch()
+    sc = lambda c: c * frac_num // frac_den
+    arch = dict(a, stem_out=sc(a["stem_out"]))
+    cin = [sc(ci) for ci, _, _ in a["blocks"]]
+    cout = [sc(co) for _, co, _ in a["blocks"]]
+    return O.madds_mbnet(arch, cin, cout, cout[-1])
+
+
+def _rn_scaled(frac_num, frac_den):
+    a = WL.resnet_arch()
+    sc = lambda c: c * frac_num // frac_den
+    arch = dict(a, stem_out=sc(a["stem_out"]))
+    mids = [sc(w) for w in a["widths"]]
+    return O.madds_resnet(arch, mids, [4 * m for m in mids])
+
+
+def test_madds_model_reproduces_paper_counts():
+    g = _gold()
+    got = {
+        "mobilenetv1_1.0x": _mb_scaled(1, 1), "mobilenetv1_0.75x": _mb_scaled(3, 4),
+        "mobilenetv1_0.5x": _mb_scaled(1, 2),
+        "resnet50_1.0x": _rn_scaled(1, 1), "resnet50_0.75x": _rn_scaled(3, 4), "resnet50_0.5x": _rn_scaled(1, 2),
+    }
+    v = WL.vit_arch()
+    got["deit_s"] = O.madds_vit(v, 384, 6, 1536)
+    for k, val in got.items():
+        want, tol = g[k]
+        assert abs(val - want) / want <= tol, (k, val, want)
+
+
+def test_madds_route_tables_are_nested_and_largest_route_is_the_full_net():
+    a = WL.mbnet_arch()
+    m = [O.madds_mbnet(a, a["cin"][t], a["cout"][t], int(a["cout"][t, -1])) for t in range(a["T"])]
+    assert all(m[i] < m[i + 1] for i in range(len(m) - 1))      # routes ordered by complexity
+    assert m[-1] == _mb_scaled(1, 1)
+    assert a["cout"][:, 6].tolist() == [176, 208, 232, 256, 280, 304, 336, 360, 384, 408, 432, 464, 488, 512]
+    assert a["cout"][:, 12].tolist() == [360, 408, 464, 512, 560, 616, 664, 720, 768, 816, 872, 920, 976, 1024]
+    r = WL.resnet_arch()
+    assert O.madds_resnet(r, r["mid"][:, 3], r["out"][:, 3]) == _rn_scaled(1, 1)
+    v = WL.vit_arch()
+    assert v["T"] == 48 and tuple(v["routes"][-1]) == (384, 6, 1536) and tuple(v["routes"][0]) == (192, 3, 384)
+
+
+# ------------------------------------------------------------------ library-built references
+def _bn(x, bn, t, c, eps):
+    return F.batch_norm(x, t64(bn["mean"][t, :c]), t64(bn["var"][t, :c]), t64(bn["gamma"][:c]),
+                        t64(bn["beta"][:c]), False, 0.0, eps)
+
+
+def _ref_mbnet(arch, p, img, t):
+    eps = arch["bn_eps"]
+    x = t64(img)[None]
+    x = F.relu(_bn(F.conv2d(x, t64(p["stem.w"]), stride=2, padding=1), p["stem.bn"], 0, arch["stem_out"], eps))
+    for i, (_a, _b, s) in enumerate(arch["blocks"]):
+        tb = t if i >= arch["gate_after"] else 0
+        ci, co = int(arch["cin"][t, i]), int(arch["cout"][t, i])
+        x = F.relu(_bn(F.conv2d(x, t64(p[f"ds{i}.dw.w"][:ci]), stride=s, padding=1, groups=ci),
+                       p[f"ds{i}.dw.bn"], tb, ci, eps))
+        x = F.relu(_bn(F.conv2d(x, t64(p[f"ds{i}.pw.w"][:co, :ci])), p[f"ds{i}.pw.bn"], tb, co, eps))
+    c = x.shape[1]
+    return F.linear(x.mean((2, 3)), t64(p["fc.w"][:, :c]), t64(p["fc.b"]))[0].numpy()
+
+
+def _ref_resnet(arch, p, img, routes):
+    eps = arch["bn_eps"]
+    x = t64(img)[None]
+    x = F.relu(_bn(F.conv2d(x, t64(p["stem.w"]), stride=2, padding=3), p["stem.bn"], 0, arch["stem_out"], eps))
+    x = F.max_pool2d(x, 3, 2, 1)
+    for s, nb in enumerate(arch["blocks"]):
+        t = routes[s]
+        mid, out = int(arch["mid"][s, t]), int(arch["out"][s, t])
+        for b in range(nb):
+            bp = f"s{s}.b{b}"
+            st = 2 if (b == 0 and s > 0) else 1
+            ci = x.shape[1]
+            sc = x
+            if b == 0:
+                sc = _bn(F.conv2d(x, t64(p[bp + ".proj.w"][:out, :ci]), stride=st), p[bp + ".proj.bn"], t, out, eps)
+            y = F.relu(_bn(F.conv2d(x, t64(p[bp + ".c1.w"][:mid, :ci])), p[bp + ".c1.bn"], t, mid, eps))
+            y = F.relu(_bn(F.conv2d(y, t64(p[bp + ".c2.w"][:mid, :mid]), stride=st, padding=1), p[bp + ".c2.bn"], t, mid, eps))
+            y = _bn(F.conv2d(y, t64(p[bp + ".c3.w"][:out, :mid])), p[bp + ".c3.bn"], t, out, eps)
+            x = F.relu(y + sc)
+    c = x.shape[1]
+    return F.linear(x.mean((2, 3)), t64(p["fc.w"][:, :c]), t64(p["fc.b"]))[0].numpy()
+
+
+def _ref_vit(arch, p, img, route):
+    d, h, hid = (int(v) for v in arch["routes"][route])
+    dh, eps = arch["head_dim"], arch["ln_eps"]
+    hd = h * dh
+    tok = F.conv2d(t64(img)[None], t64(p["embed.w"][:d]), t64(p["embed.b"][:d]), stride=arch["patch"])
+    tok = tok.flatten(2).transpose(1, 2)[0] + t64(p["pos"][1:, :d])
+    x = torch.cat([(t64(p["cls"][:d]) + t64(p["pos"][0, :d]))[None], tok], 0)
+    N = x.shape[0]
+    for l in range(arch["depth"]):
+        q_ = f"l{l}"
+        a = F.layer_norm(x, (d,), t64(p[q_ + ".ln1.g"][:d]), t64(p[q_ + ".ln1.b"][:d]), eps)
+        q, k, v = (F.linear(a, t64(p[q_ + f".w{n}"][:hd, :d]), t64(p[q_ + f".b{n}"][:hd])) for n in "qkv")
+        sp = lambda z: z.reshape(N, h, dh).transpose(0, 1)
+        o = F.scaled_dot_product_attention(sp(q), sp(k), sp(v)).transpose(0, 1).reshape(N, hd)
+        x = x + F.linear(o, t64(p[q_ + ".wproj"][:d, :hd]), t64(p[q_ + ".bproj"][:d]))
+        m = F.layer_norm(x, (d,), t64(p[q_ + ".ln2.g"][:d]), t64(p[q_ + ".ln2.b"][:d]), eps)
+        m = F.gelu(F.linear(m, t64(p[q_ + ".fc1.w"][:hid, :d]), t64(p[q_ + ".fc1.b"][:hid])))
+        x = x + F.linear(m, t64(p[q_ + ".fc2.w"][:d, :hid]), t64(p[q_ + ".fc2.b"][:d]))
+    f = F.layer_norm(x[:1], (d,), t64(p["ln.g"][:d]), t64(p["ln.b"][:d]), eps)
+    return F.linear(f[0], t64(p["head.w"][:, :d]), t64(p["head.b"])).numpy()
+
+
+# ------------------------------------------------------------------ assemblies
+@pytest.mark.parametrize("t", [0, 6, 13])
+def test_mbnet_assembly_matches_library_layers(t):
+    arch = WL.mbnet_arch(image=32, width_div=8)
+    p = WL.mbnet_params(arch, 11)
+    img = WL.images(12, 1, 32)[0]
+    got, rt, _ = O.forward_mbnet(arch, p, img, route_override=t, store="f64")
+    assert rt == t
+    np.testing.assert_allclose(got, _ref_mbnet(arch, p, img, t), rtol=1e-9, atol=1e-9)
+
+
+def test_mbnet_gate_picks_the_biased_route_and_bf16_storage_stays_close():
+    arch = WL.mbnet_arch(image=32, width_div=8)
+    p = WL.mbnet_params(arch, 11)
+    img = WL.images(12, 2, 32)
+    lb = WL.seeded_logit_bias(5, 2, arch["T"])
+    for b in range(2):
+        lo, t, z = O.forward_mbnet(arch, p, img[b], logit_bias=lb[b], store="bf16")
+        assert t == int(np.argmax(z)) and z.shape == (arch["T"],)
+        hi, t2, _ = O.forward_mbnet(arch, p, img[b], route_override=t, store="f64")
+        assert np.max(np.abs(lo - hi)) / np.max(np.abs(hi)) < 2e-2
+    taps = {}
+    O.forward_mbnet(arch, p, img[0], route_override=3, store="bf16", taps=taps)
+    for v in taps.values():
+        assert np.array_equal(O.bf16_round(v), v)              # stored tensors are bf16 values
+
+
+@pytest.mark.parametrize("routes", [(0, 0, 0, 0), (3, 3, 3, 3), (1, 3, 0, 2)])
+def test_resnet_assembly_matches_library_layers(routes):
+    arch = WL.resnet_arch(image=32, width_div=8, blocks=(2, 1, 2, 1))
+    p = WL.resnet_params(arch, 21)
+    img = WL.images(22, 1, 32)[0]
+    got, rt, _ = O.forward_resnet(arch, p, img, route_override=routes, store="f64")
+    assert tuple(rt) == routes
+    np.testing.assert_allclose(got, _ref_resnet(arch, p, img, routes), rtol=1e-9, atol=1e-9)
+
+
+def test_resnet_free_running_gates_follow_logit_bias():
+    arch = WL.resnet_arch(image=32, width_div=8, blocks=(1, 1, 1, 1))
+    p = WL.resnet_params(arch, 21)
+    img = WL.images(22, 1, 32)[0]
+    lb = np.stack([WL.seeded_logit_bias(30 + s, 1, 4)[0] for s in range(4)])
+    _, rt, zs = O.forward_resnet(arch, p, img, logit_bias=lb, store="bf16")
+    assert rt == [int(np.argmax(z)) for z in zs]
+
+
+@pytest.mark.parametrize("route", [0, 17, 47])
+def test_vit_assembly_matches_library_layers(route):
+    arch = WL.vit_arch(image=32, patch=8, embed=48, heads=6, head_dim=8, mlp=192, depth=2)
+    p = WL.vit_params(arch, 31)
+    img = WL.images(32, 1, 32)[0]
+    got = O.forward_vit(arch, p, img, route, store="f64")
+    np.testing.assert_allclose(got, _ref_vit(arch, p, img, route), rtol=1e-9, atol=1e-10)
+
+
+def test_vit_bf16_storage_stays_close():
+    arch = WL.vit_arch(image=32, patch=8, embed=48, heads=6, head_dim=8, mlp=192, depth=2, routes="diag")
+    p = WL.vit_params(arch, 31)
+    img = WL.images(32, 1, 32)[0]
+    for route in range(4):
+        lo = O.forward_vit(arch, p, img, route, store="bf16")
+        hi = O.forward_vit(arch, p, img, route, store="f64")
+        assert np.max(np.abs(lo - hi)) / np.max(np.abs(hi)) < 2e-2
+
+
+def test_seeded_logit_bias_makes_every_route_occur():
+    for B, T in [(256, 14), (256, 48), (64, 4)]:
+        lb = WL.seeded_logit_bias(7, B, T)
+        r = np.argmax(lb, axis=1)
+        cnt = np.bincount(r, minlength=T)
+        assert cnt.min() >= B // T and cnt.max() <= B // T + 1

@@ -1,0 +1,47 @@
+"""Seeded inputs of the two single-layer configurations.
+
+config1: one dynamic slimmable block in fp32 (gate, sliced 3x3 conv, split
+batch-norm, ReLU).  config2: the sliced-linear sweep in bf16 with four
+embedding slices.  Data only; no arithmetic of the method.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .nets import BASE_SEED, Draw, as_bf16_values, bn_tables
+
+
+def config1(seed: int = BASE_SEED + 1, B: int = 8, C: int = 64, HW: int = 16) -> dict:
+    d = Draw(seed)
+    T = 4
+    hid = C // 4
+    cfg = {
+        "B": B, "C": C, "H": HW, "W": HW, "T": T, "stride": 1, "pad": 1, "bn_eps": 1e-5,
+        "c_out": np.array([C * q // 4 for q in (1, 2, 3, 4)], np.int32),
+        "x": d.normal((B, C, HW, HW)),
+        "gate.w1": d.normal((hid, C), std=C ** -0.5),
+        "gate.b1": d.normal((hid,), std=0.1),
+        "gate.w2": d.normal((T, hid), std=hid ** -0.5),
+        "gate.b2": d.normal((T,), std=0.1),
+        "conv.w": d.normal((C, C, 3, 3), std=(2.0 / (C * 9)) ** 0.5),
+    }
+    cfg["bn"] = bn_tables(d, T, C)
+    return cfg
+
+
+def config2(seed: int = BASE_SEED + 2, B: int = 64, N: int = 197, K: int = 384,
+            balanced: bool = False) -> dict:
+    """Each image gets an input-embedding slice k_in from 4 equispaced choices and
+    an output slice of 4*k_in from the stored [4K, K] weight."""
+    d = Draw(seed)
+    x = as_bf16_values(d.normal((B, N, K)))
+    w = as_bf16_values(d.normal((4 * K, K), std=0.02))
+    bias = d.normal((4 * K,), std=0.02)
+    if balanced:
+        route = (d.permutation(B) % 4).astype(np.int32)
+    else:
+        route = d.randint(B, 4)
+    step = K // 6
+    k_in = np.array([3 * step, 4 * step, 5 * step, 6 * step], np.int32)
+    return {"B": B, "N": N, "K": K, "T": 4, "x": x, "w": w, "bias": bias, "route": route,
+            "k_in": k_in, "k_out": (4 * k_in).astype(np.int32)}

@@ -1,0 +1,255 @@
+"""Network descriptions (layer lists, route tables) and seeded random parameters.
+
+Everything here is data: shapes, integer slice tables and random tensors drawn
+from a seeded CPU generator in a fixed order.  Values meant for bf16 storage are
+rounded once to bf16 (round-to-nearest-even) and handed out as float32 arrays
+holding exactly those bf16 values, so every consumer starts from the same bits.
+
+Shapes follow the routing spaces of the paper's Section 5.2 ("Architecture
+details") and its routing-space tables, restricted to channel / embedding /
+head / MLP slicing.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+BASE_SEED = 210910060
+
+
+# --------------------------------------------------------------------------
+# random helpers (no arithmetic of the method)
+# --------------------------------------------------------------------------
+class Draw:
+    """Sequential draws from one seeded CPU generator."""
+
+    def __init__(self, seed: int):
+        self.g = torch.Generator(device="cpu")
+        self.g.manual_seed(int(seed))
+
+    def normal(self, shape, std=1.0, mean=0.0) -> np.ndarray:
+        t = torch.empty(tuple(shape), dtype=torch.float32)
+        t.normal_(mean=float(mean), std=float(std), generator=self.g)
+        return t.numpy()
+
+    def uniform(self, shape, lo, hi) -> np.ndarray:
+        t = torch.empty(tuple(shape), dtype=torch.float32)
+        t.uniform_(float(lo), float(hi), generator=self.g)
+        return t.numpy()
+
+    def randint(self, n, high) -> np.ndarray:
+        return torch.randint(0, int(high), (int(n),), generator=self.g).numpy().astype(np.int32)
+
+    def permutation(self, n) -> np.ndarray:
+        return torch.randperm(int(n), generator=self.g).numpy().astype(np.int64)
+
+
+def as_bf16_values(a: np.ndarray) -> np.ndarray:
+    """Round a float32 array once to bf16 (RNE); return float32 holding those values."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def bn_tables(d: Draw, T: int, C: int) -> dict:
+    """Affine parameters shared by all routes plus per-route running statistics."""
+    return {
+        "gamma": d.uniform((C,), 0.5, 1.5),
+        "beta": d.normal((C,), std=0.1),
+        "mean": d.normal((T, C), std=0.1),
+        "var": d.uniform((T, C), 0.5, 1.5),
+    }
+
+
+def seeded_logit_bias(seed: int, B: int, T: int) -> np.ndarray:
+    """Per-sample additive gate logits: small noise plus 4 on a seeded target route,
+    so that every route occurs about B/T times and margins are far above rounding noise."""
+    d = Draw(seed)
+    noise = d.normal((B, T), std=0.1)
+    pi = d.permutation(B)
+    bias = noise.copy()
+    bias[np.arange(B), (pi % T).astype(np.int64)] += 4.0
+    return bias.astype(np.float32)
+
+
+def images(seed: int, B: int, size: int = 224, bf16: bool = True) -> np.ndarray:
+    """Synthetic ImageNet-shaped batch, N(0,1) pixels, NCHW."""
+    d = Draw(seed)
+    x = d.normal((B, 3, size, size))
+    return as_bf16_values(x) if bf16 else x
+
+
+def _kaiming(d: Draw, shape) -> np.ndarray:
+    fan_in = int(np.prod(shape[1:]))
+    return d.normal(shape, std=(2.0 / fan_in) ** 0.5)
+
+
+# --------------------------------------------------------------------------
+# DS-MBNet: MobileNetV1 with one gate after the 5th depthwise-separable block
+# --------------------------------------------------------------------------
+def _round8(C: int, i: int) -> int:
+    # nearest multiple of 8 to C*(0.35+0.05 i), ties up, integer only
+    return 8 * ((C * (35 + 5 * i) + 400) // 800)
+
+
+def mbnet_arch(image: int = 224, width_div: int = 1) -> dict:
+    """Layer list of the MobileNetV1-shaped dynamic net.
+
+    `width_div` shrinks every stored channel count (test-sized nets); 1 gives
+    the standard 32..1024 channels.  cin/cout are [T, 13] integer tables: the
+    valid channels of block i on route t.  Blocks 1-5 are fixed; blocks 6-13 and
+    the classifier's input width follow the route.
+    """
+    base = [(32, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2), (256, 256, 1),
+            (256, 512, 2), (512, 512, 1), (512, 512, 1), (512, 512, 1), (512, 512, 1),
+            (512, 512, 1), (512, 1024, 2), (1024, 1024, 1)]
+    blocks = [(ci // width_div, co // width_div, s) for ci, co, s in base]
+    T = 14
+    cin = np.zeros((T, 13), np.int32)
+    cout = np.zeros((T, 13), np.int32)
+    for t in range(T):
+        for i, (ci, co, _s) in enumerate(blocks):
+            cin[t, i] = ci if i < 6 else _round8(ci, t)
+            cout[t, i] = co if i < 5 else _round8(co, t)
+    return {
+        "name": "mbnet", "image": image, "stem_out": 32 // width_div, "blocks": blocks,
+        "gate_after": 5, "gate_hidden": blocks[4][1] // 4, "T": T,
+        "cin": cin, "cout": cout, "num_classes": 1000, "bn_eps": 1e-5,
+    }
+
+
+def mbnet_params(arch: dict, seed: int) -> dict:
+    d = Draw(seed)
+    T = arch["T"]
+    p = {}
+    so = arch["stem_out"]
+    p["stem.w"] = as_bf16_values(_kaiming(d, (so, 3, 3, 3)))
+    p["stem.bn"] = bn_tables(d, 1, so)
+    for i, (ci, co, _s) in enumerate(arch["blocks"]):
+        Tb = 1 if i < arch["gate_after"] else T
+        p[f"ds{i}.dw.w"] = as_bf16_values(_kaiming(d, (ci, 1, 3, 3)))
+        p[f"ds{i}.dw.bn"] = bn_tables(d, Tb, ci)
+        p[f"ds{i}.pw.w"] = as_bf16_values(_kaiming(d, (co, ci, 1, 1)))
+        p[f"ds{i}.pw.bn"] = bn_tables(d, Tb, co)
+    cg = arch["blocks"][arch["gate_after"] - 1][1]
+    hid = arch["gate_hidden"]
+    p["gate.w1"] = d.normal((hid, cg), std=cg ** -0.5)
+    p["gate.b1"] = d.normal((hid,), std=0.1)
+    p["gate.w2"] = d.normal((T, hid), std=hid ** -0.5)
+    p["gate.b2"] = d.normal((T,), std=0.1)
+    cf = arch["blocks"][-1][1]
+    p["fc.w"] = as_bf16_values(d.normal((arch["num_classes"], cf), std=cf ** -0.5))
+    p["fc.b"] = d.normal((arch["num_classes"],), std=0.1)
+    return p
+
+
+# --------------------------------------------------------------------------
+# DS-ResNet: ResNet-50 with a gate in the first block of each stage
+# --------------------------------------------------------------------------
+def resnet_arch(image: int = 224, width_div: int = 1, blocks=(3, 4, 6, 3)) -> dict:
+    """Bottleneck stages with mid width w*q/4 and output width 4w*q/4, q=1..4.
+
+    mid[s][q-1], out[s][q-1] are the valid channel counts of stage s on ratio
+    index q-1.  The 7x7 stem and the max-pool are never sliced.
+    """
+    widths = [64 // width_div, 128 // width_div, 256 // width_div, 512 // width_div]
+    mid = np.array([[w * q // 4 for q in (1, 2, 3, 4)] for w in widths], np.int32)
+    out = 4 * mid
+    return {
+        "name": "resnet", "image": image, "stem_out": 64 // width_div, "widths": widths,
+        "blocks": list(blocks), "T": 4, "mid": mid, "out": out.astype(np.int32),
+        "gate_hidden": [max(1, (64 // width_div) // 4)] + [max(1, 4 * w // 4) for w in widths[:-1]],
+        "num_classes": 1000, "bn_eps": 1e-5,
+    }
+
+
+def resnet_params(arch: dict, seed: int) -> dict:
+    d = Draw(seed)
+    T = arch["T"]
+    p = {}
+    so = arch["stem_out"]
+    p["stem.w"] = as_bf16_values(_kaiming(d, (so, 3, 7, 7)))
+    p["stem.bn"] = bn_tables(d, 1, so)
+    cprev = so
+    for s, (w, nb) in enumerate(zip(arch["widths"], arch["blocks"])):
+        hid = arch["gate_hidden"][s]
+        p[f"s{s}.gate.w1"] = d.normal((hid, cprev), std=cprev ** -0.5)
+        p[f"s{s}.gate.b1"] = d.normal((hid,), std=0.1)
+        p[f"s{s}.gate.w2"] = d.normal((T, hid), std=hid ** -0.5)
+        p[f"s{s}.gate.b2"] = d.normal((T,), std=0.1)
+        for b in range(nb):
+            cin = cprev if b == 0 else 4 * w
+            pre = f"s{s}.b{b}"
+            p[pre + ".c1.w"] = as_bf16_values(_kaiming(d, (w, cin, 1, 1)))
+            p[pre + ".c1.bn"] = bn_tables(d, T, w)
+            p[pre + ".c2.w"] = as_bf16_values(_kaiming(d, (w, w, 3, 3)))
+            p[pre + ".c2.bn"] = bn_tables(d, T, w)
+            p[pre + ".c3.w"] = as_bf16_values(_kaiming(d, (4 * w, w, 1, 1)))
+            p[pre + ".c3.bn"] = bn_tables(d, T, 4 * w)
+            if b == 0:
+                p[pre + ".proj.w"] = as_bf16_values(_kaiming(d, (4 * w, cin, 1, 1)))
+                p[pre + ".proj.bn"] = bn_tables(d, T, 4 * w)
+        cprev = 4 * w
+    p["fc.w"] = as_bf16_values(d.normal((arch["num_classes"], cprev), std=cprev ** -0.5))
+    p["fc.b"] = d.normal((arch["num_classes"],), std=0.1)
+    return p
+
+
+# --------------------------------------------------------------------------
+# DS-ViT: DeiT-S-shaped transformer, one route per image chosen before the patch embed
+# --------------------------------------------------------------------------
+def vit_arch(image: int = 224, patch: int = 16, embed: int = 384, heads: int = 6,
+             head_dim: int = 64, mlp: int = 1536, depth: int = 12, routes: str = "cross") -> dict:
+    """routes[t] = (d_e, h, hidden): embedding slice, head count and MLP hidden slice.
+
+    "cross": every combination of 4 embedding slices, 4 head counts and MLP
+    ratios 2,3,4 (hidden = ratio * d_e); "diag": 4 nested routes.
+    """
+    step = embed // 6
+    de_list = [3 * step, 4 * step, 5 * step, 6 * step]
+    h_list = [heads - 3, heads - 2, heads - 1, heads]
+    if routes == "cross":
+        table = [(de, h, r * de) for de in de_list for h in h_list for r in (2, 3, 4)]
+    elif routes == "diag":
+        table = [(de_list[0], h_list[0], 2 * de_list[0]), (de_list[1], h_list[1], 3 * de_list[1]),
+                 (de_list[2], h_list[2], 3 * de_list[2]), (de_list[3], h_list[3], 4 * de_list[3])]
+    else:
+        raise ValueError(routes)
+    n_tok = (image // patch) ** 2 + 1
+    return {
+        "name": "vit", "image": image, "patch": patch, "embed": embed, "heads": heads,
+        "head_dim": head_dim, "mlp": mlp, "depth": depth, "tokens": n_tok,
+        "routes": np.array(table, np.int32), "T": len(table), "num_classes": 1000, "ln_eps": 1e-6,
+    }
+
+
+def vit_params(arch: dict, seed: int) -> dict:
+    d = Draw(seed)
+    D, Hd, M = arch["embed"], arch["heads"] * arch["head_dim"], arch["mlp"]
+    P = arch["patch"]
+    std = 0.02
+    bf = as_bf16_values
+    p = {}
+    p["embed.w"] = bf(d.normal((D, 3, P, P), std=std))
+    p["embed.b"] = d.normal((D,), std=std)
+    p["cls"] = bf(d.normal((D,), std=std))
+    p["pos"] = bf(d.normal((arch["tokens"], D), std=std))
+    for l in range(arch["depth"]):
+        pre = f"l{l}"
+        p[pre + ".ln1.g"] = 1.0 + d.normal((D,), std=std)
+        p[pre + ".ln1.b"] = d.normal((D,), std=std)
+        for nm in ("q", "k", "v"):
+            p[pre + f".w{nm}"] = bf(d.normal((Hd, D), std=std))
+            p[pre + f".b{nm}"] = d.normal((Hd,), std=std)
+        p[pre + ".wproj"] = bf(d.normal((D, Hd), std=std))
+        p[pre + ".bproj"] = d.normal((D,), std=std)
+        p[pre + ".ln2.g"] = 1.0 + d.normal((D,), std=std)
+        p[pre + ".ln2.b"] = d.normal((D,), std=std)
+        p[pre + ".fc1.w"] = bf(d.normal((M, D), std=std))
+        p[pre + ".fc1.b"] = d.normal((M,), std=std)
+        p[pre + ".fc2.w"] = bf(d.normal((D, M), std=std))
+        p[pre + ".fc2.b"] = d.normal((D,), std=std)
+    p["ln.g"] = 1.0 + d.normal((D,), std=std)
+    p["ln.b"] = d.normal((D,), std=std)
+    p["head.w"] = bf(d.normal((arch["num_classes"], D), std=std))
+    p["head.b"] = d.normal((arch["num_classes"],), std=std)
+    return p
