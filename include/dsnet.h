@@ -1,0 +1,183 @@
+/*
+ * dsnet.h - C ABI of the gate-routed, weight-sliced inference path of DS-Net++
+ * (arXiv 2109.10060) for AMD gfx950.
+ *
+ * The method (Section 3): a routing agent picks one route per input (Section 3.1,
+ * Eq. 1; Section 3.5, Eq. 21-22) and every layer of the supernet then computes
+ * with the leading contiguous block W[:k_out, :k_in] of its statically stored
+ * weight (Section 3.2, Eq. 8), across filters (Eq. 9), depthwise channels
+ * (Eq. 10), embedding width, heads and MLP width (Eq. 15-19).  A batch with
+ * mixed routes is executed by bucketing samples by route (ds_route_bucket) and
+ * running dense kernels per bucket; results equal per-sample execution.
+ *
+ * Conventions for every call
+ *  - Pointers named "device" point to GPU memory owned by the caller; the library
+ *    never allocates or frees memory and never writes weights.  Scratch comes
+ *    from the caller's workspace `ws` (device, 256-byte aligned) of `ws_bytes`.
+ *  - Weights are passed at FULL stored size with their full leading strides;
+ *    slices are read in place.  Output elements beyond a sample's valid slice
+ *    are not written.
+ *  - `stream` is a hipStream_t (NULL = default stream).  Calls enqueue work and
+ *    return; nothing synchronises and no route decision is read back to the host.
+ *  - Return value: DS_OK or a negative code.  Arguments are validated on the
+ *    host before any launch, so a failing call has no device side effects.
+ *    ds_last_error() gives a thread-local message.  B == 0 is a valid no-op.
+ *  - bf16 tensors need 16-byte aligned base pointers and slice sizes, leading
+ *    strides and channel counts that are multiples of 8 (DS_EALIGN otherwise).
+ */
+#ifndef DSNET_H
+#define DSNET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DS_OK            0
+#define DS_EINVAL       (-1)  /* null pointer, negative size, slice larger than stored size */
+#define DS_ESHAPE       (-2)  /* inconsistent shapes */
+#define DS_EALIGN       (-3)  /* pointer / stride / slice not aligned for the bf16 path */
+#define DS_EUNSUPPORTED (-4)  /* dtype / layout combination not implemented */
+#define DS_EWORKSPACE   (-5)  /* workspace too small or missing */
+#define DS_EHIP         (-6)  /* HIP launch error */
+
+#define DS_F32  0
+#define DS_BF16 1
+
+#define DS_NCHW 0   /* [B, C, H, W]; weights [C_O, C_I, K, K]                       */
+#define DS_NHWC 1   /* [B, H, W, C]; weights [C_O, K, K, C_I]; depthwise [K, K, C]  */
+
+#define DS_ACT_NONE 0
+#define DS_ACT_RELU 1
+#define DS_ACT_GELU 2   /* exact erf form */
+
+#define DS_MAX_GROUPS 64
+
+/* Route groups of one layer.  Group t covers bucket slots offsets[t]..offsets[t+1]
+ * (as written by ds_route_bucket); slot j holds sample perm[j] (NULL = identity).
+ * k_in/k_out are the valid input/output widths of the group (the paper's routing
+ * spaces are explicit integer lists, so no ratios cross the ABI); table_row picks
+ * the row of per-route tables (split batch-norm statistics, Eq. 14).  Host struct. */
+typedef struct ds_groups {
+    int32_t T;
+    const int32_t* offsets;             /* device [T+1] */
+    const int32_t* perm;                /* device [B] or NULL */
+    int32_t k_in[DS_MAX_GROUPS];
+    int32_t k_out[DS_MAX_GROUPS];
+    int32_t table_row[DS_MAX_GROUPS];
+} ds_groups;
+
+const char* ds_last_error(void);
+int32_t ds_version(void);
+
+/* Fold split batch-norm (Eq. 14) into per-route scale/shift tables:
+ * scale[t,c] = gamma[c] / sqrt(var[t,c] + eps), shift[t,c] = beta[c] - mean[t,c] * scale[t,c].
+ * All device fp32; mean/var/scale/shift are [T, C]. */
+int32_t ds_bn_fold(const float* gamma, const float* beta, const float* mean, const float* var,
+                   float eps, int32_t T, int32_t C, float* scale, float* shift, void* stream);
+
+/* Routing agent (Section 3.5).  Encoder: mean over H*W of each valid channel
+ * (Eq. 21).  Head: logits = W2 . relu(W1[:, :c_in[b]] . pooled + b1) + b2
+ * (+ logit_bias[b]); route = argmax (Eq. 22 at inference; ties -> lowest index, NaN
+ * never selected).  x: device [B,C,HW] (DS_NCHW) or [B,HW,C] (DS_NHWC), fp32 or
+ * bf16; x == NULL skips encoder and MLP and routes on logit_bias alone.  c_in:
+ * device [B] or NULL (= C).  w1 [C_mlp, C], w2 [T, C_mlp], biases nullable,
+ * logit_bias [B,T] nullable: device fp32.  Outputs: logits_out [B,T] fp32,
+ * route_out [B] int32 (device).  ws: at least ds_gate_workspace(B, C) bytes
+ * (partial sums of the encoder); not needed when x == NULL. */
+size_t ds_gate_workspace(int32_t B, int32_t C);
+int32_t ds_gate(const void* x, int32_t x_dtype, int32_t x_layout, int32_t B, int32_t C, int32_t HW,
+                const int32_t* c_in, const float* w1, const float* b1, int32_t C_mlp,
+                const float* w2, const float* b2, int32_t T, const float* logit_bias,
+                float* logits_out, int32_t* route_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Bucket a batch by route: offsets[t] = #samples with route < t (offsets[T] counts
+ * the samples with a valid id, so offsets[T] != B flags an id outside [0,T));
+ * perm lists samples bucket by bucket, ascending inside a bucket (stable);
+ * inv_perm[perm[j]] = j.  All device int32.  1 <= T <= 1024. */
+int32_t ds_route_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm,
+                        int32_t* inv_perm, int32_t* offsets, void* stream);
+
+/* Sliced linear layer (Eq. 8): for every sample b of group t and each of its
+ * `rows` rows, y[b, r, :k_out] = act(x[b, r, :k_in] . W[:k_out, :k_in]^T + bias[:k_out])
+ * with the residual, when given, added before the activation:
+ * act(x W^T + bias + residual).  x: device bf16 [B, rows, x_ld]; W: device bf16
+ * [N_full, w_ld]; bias: device fp32 [N_full] or NULL; residual: device bf16
+ * [B, rows, r_ld] or NULL; y: device [B, rows, y_ld], bf16 or fp32.  Samples stay
+ * in their original order in x and y. */
+size_t ds_sliced_linear_workspace(int32_t B, int32_t rows, int32_t T);
+int32_t ds_sliced_linear(const void* x, int64_t x_ld, const void* w, int64_t w_ld, int32_t N_full,
+                         int32_t K_full, const float* bias, const ds_groups* g, int32_t B,
+                         int32_t rows, int32_t act, const void* residual, int64_t r_ld, void* y,
+                         int32_t y_dtype, int64_t y_ld, void* ws, size_t ws_bytes, void* stream);
+
+/* Sliced dense convolution with split batch-norm (Eq. 9 and Eq. 14):
+ * y[b, :c_out] = act(scale[row, :c_out] * (W[:c_out, :c_in] * x[b, :c_in]) + shift[row, :c_out]
+ *                    + residual[b, :c_out]),  row = table_row[t].
+ * Supported: (DS_F32, DS_NCHW) direct kernel; (DS_BF16, DS_NHWC) matrix-core
+ * implicit GEMM.  x: [B, C_I, H, W] / [B, H, W, C_I]; y: [B, C_O, Ho, Wo] /
+ * [B, Ho, Wo, C_O] at full channel stride; scale/shift: device fp32 [n_rows, C_O]
+ * (scale NULL = 1); residual: like y, or NULL. */
+size_t ds_sliced_conv_workspace(int32_t B, int32_t Ho, int32_t Wo, int32_t T);
+int32_t ds_sliced_conv(const void* x, int32_t dtype, int32_t layout, int32_t B, int32_t C_I,
+                       int32_t H, int32_t W, const void* w, int32_t C_O, int32_t K,
+                       const float* scale, const float* shift, const ds_groups* g, int32_t stride,
+                       int32_t pad, int32_t act, const void* residual, void* y, void* ws,
+                       size_t ws_bytes, void* stream);
+
+/* Sliced depthwise 3x3 convolution (Eq. 10, one channel per group) with split
+ * batch-norm and activation; output width = input width = k_in[t].  bf16 NHWC;
+ * w: device bf16 [3, 3, C]; scale/shift device fp32 [n_rows, C]. */
+size_t ds_slot_workspace(int32_t B);   /* workspace of ds_sliced_dwconv / ds_sliced_layernorm */
+int32_t ds_sliced_dwconv(const void* x, int32_t B, int32_t C, int32_t H, int32_t W, const void* w,
+                         const float* scale, const float* shift, const ds_groups* g,
+                         int32_t stride, int32_t act, void* y, void* ws, size_t ws_bytes,
+                         void* stream);
+
+/* LayerNorm over the k_in[t] valid features of each row with gamma[:k], beta[:k]
+ * (the statistics use the valid features only).  x, y: device bf16 [B, rows, ld]. */
+int32_t ds_sliced_layernorm(const void* x, int64_t x_ld, const float* gamma, const float* beta,
+                            float eps, const ds_groups* g, int32_t B, int32_t rows, void* y,
+                            int64_t y_ld, void* ws, size_t ws_bytes, void* stream);
+
+/* Sliced multi-head self-attention (Eq. 16-18): Q,K,V = x[:, :d_e] . W{q,k,v}[:h*Dh, :d_e]^T + b;
+ * per head j < h: softmax(Q_j K_j^T / sqrt(Dh)) V_j; y = concat . Wproj[:d_e, :h*Dh]^T + bproj
+ * (+ residual).  Group t uses d_e = k_in[t] and h*Dh = k_out[t].  x, residual, y:
+ * device bf16 [B, N, D_e]; wqkv: device bf16 [3, H*Dh, D_e] (Wq, Wk, Wv stacked, each
+ * sliced to its own leading block); bqkv: device fp32 [3, H*Dh] or NULL; wproj:
+ * device bf16 [D_e, H*Dh]; bproj: device fp32 [D_e] or NULL.  head_dim must be 64,
+ * N <= 224. */
+size_t ds_sliced_mhsa_workspace(int32_t B, int32_t N, int32_t H, int32_t head_dim, int32_t T);
+int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D_e, const void* wqkv,
+                       const float* bqkv, const void* wproj, const float* bproj, int32_t H,
+                       int32_t head_dim, const ds_groups* g, const void* residual, void* y,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Whole-network forward (Section 5.2 assemblies).  arch selects the graph; `ints`
+ * is the host integer description and `params` the device parameter pointers, in
+ * the order documented next to each DS_ARCH_* below.  images: device bf16
+ * [B, 3, image, image]; route_override: device int32 [n_gates, B] or NULL;
+ * logit_bias: device fp32 [n_gates, B, T] or NULL; logits: device fp32
+ * [B, num_classes] in the original sample order; routes_out: device int32
+ * [n_gates, B]. */
+#define DS_ARCH_MBNET  1
+#define DS_ARCH_RESNET 2
+#define DS_ARCH_VIT    3
+typedef struct ds_net {
+    int32_t arch;
+    int32_t n_ints;
+    const int32_t* ints;            /* host */
+    int32_t n_params;
+    const void* const* params;      /* host array of device pointers */
+} ds_net;
+size_t ds_forward_workspace(const ds_net* net, int32_t B);
+int32_t ds_forward(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
+                   const float* logit_bias, float* logits, int32_t* routes_out, void* ws,
+                   size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSNET_H */

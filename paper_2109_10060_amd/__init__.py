@@ -1,0 +1,252 @@
+"""Thin ctypes binding over libdsnet.so (HIP kernels for gfx950).
+
+Every function here has the name of the C entry point it forwards to (see
+include/dsnet.h) and does argument marshalling only: it checks tensor dtypes,
+allocates outputs and workspaces with torch, and passes raw device pointers plus
+the current HIP stream.  All arithmetic of the method runs in the library's
+kernels.  There is no CPU or eager fallback: if the shared library is missing
+or cannot be loaded, load() raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+from .net import Net, build_mbnet, build_resnet, build_vit  # noqa: F401  (re-exported)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdsnet.so")
+
+DS_OK = 0
+DS_EINVAL, DS_ESHAPE, DS_EALIGN, DS_EUNSUPPORTED, DS_EWORKSPACE, DS_EHIP = -1, -2, -3, -4, -5, -6
+DS_F32, DS_BF16 = 0, 1
+DS_NCHW, DS_NHWC = 0, 1
+DS_ACT_NONE, DS_ACT_RELU, DS_ACT_GELU = 0, 1, 2
+DS_MAX_GROUPS = 64
+DS_ARCH_MBNET, DS_ARCH_RESNET, DS_ARCH_VIT = 1, 2, 3
+
+EXPORTS = [
+    "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_route_bucket",
+    "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
+    "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
+    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward",
+]
+
+
+class DsError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libdsnet error {code}: {msg}")
+        self.code = code
+
+
+class ds_groups(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("offsets", ctypes.c_void_p), ("perm", ctypes.c_void_p),
+                ("k_in", ctypes.c_int32 * DS_MAX_GROUPS), ("k_out", ctypes.c_int32 * DS_MAX_GROUPS),
+                ("table_row", ctypes.c_int32 * DS_MAX_GROUPS)]
+
+
+class ds_net(ctypes.Structure):
+    _fields_ = [("arch", ctypes.c_int32), ("n_ints", ctypes.c_int32), ("ints", ctypes.POINTER(ctypes.c_int32)),
+                ("n_params", ctypes.c_int32), ("params", ctypes.POINTER(ctypes.c_void_p))]
+
+
+_lib = None
+
+
+def load(path: Optional[str] = None):
+    """Load libdsnet.so; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_2109_10060_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    lib.ds_last_error.restype = ctypes.c_char_p
+    for name in ("ds_gate_workspace", "ds_sliced_linear_workspace", "ds_sliced_conv_workspace",
+                 "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace"):
+        getattr(lib, name).restype = ctypes.c_size_t
+    _lib = lib
+    return lib
+
+
+def _chk(rc: int):
+    if rc != DS_OK:
+        raise DsError(rc, load().ds_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None):
+    if t is None:
+        return ctypes.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    if dtype is not None:
+        assert t.dtype == dtype, f"expected {dtype}, got {t.dtype}"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes: int, like: torch.Tensor) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
+
+
+def make_groups(offsets: torch.Tensor, perm: Optional[torch.Tensor], k_in: Sequence[int],
+                k_out: Optional[Sequence[int]] = None, table_row: Optional[Sequence[int]] = None) -> ds_groups:
+    g = ds_groups()
+    T = len(k_in)
+    assert T <= DS_MAX_GROUPS
+    g.T = T
+    g.offsets = _ptr(offsets, torch.int32).value
+    g.perm = _ptr(perm, torch.int32).value if perm is not None else None
+    k_out = k_in if k_out is None else k_out
+    table_row = range(T) if table_row is None else table_row
+    for t in range(T):
+        g.k_in[t], g.k_out[t], g.table_row[t] = int(k_in[t]), int(k_out[t]), int(table_row[t])
+    return g
+
+
+# --------------------------------------------------------------------------
+# entry points
+# --------------------------------------------------------------------------
+def ds_bn_fold(gamma, beta, mean, var, eps: float):
+    T, C = mean.shape
+    scale, shift = torch.empty_like(mean), torch.empty_like(mean)
+    _chk(load().ds_bn_fold(_ptr(gamma, torch.float32), _ptr(beta, torch.float32), _ptr(mean, torch.float32),
+                           _ptr(var, torch.float32), ctypes.c_float(eps), T, C, _ptr(scale), _ptr(shift), _stream()))
+    return scale, shift
+
+
+def ds_gate(x, layout, w1, b1, w2, b2, T: int, logit_bias=None, c_in=None, B: Optional[int] = None):
+    """Returns (logits [B,T] fp32, route [B] int32)."""
+    lib = load()
+    if x is not None:
+        B = x.shape[0]
+        if layout == DS_NCHW:
+            C, HW = x.shape[1], x.shape[2] * x.shape[3]
+        else:
+            C, HW = x.shape[-1], x.numel() // (x.shape[0] * x.shape[-1])
+        dt = DS_BF16 if x.dtype == torch.bfloat16 else DS_F32
+        dev = x.device
+        C_mlp = w1.shape[0]
+    else:
+        C = HW = C_mlp = 0
+        dt = DS_F32
+        dev = logit_bias.device
+        B = logit_bias.shape[0] if B is None else B
+    logits = torch.empty((B, T), dtype=torch.float32, device=dev)
+    route = torch.empty((B,), dtype=torch.int32, device=dev)
+    nb = lib.ds_gate_workspace(B, C)
+    ws = _ws(nb, logits)
+    _chk(lib.ds_gate(_ptr(x), dt, layout, B, C, HW, _ptr(c_in), _ptr(w1), _ptr(b1), C_mlp, _ptr(w2), _ptr(b2), T,
+                     _ptr(logit_bias), _ptr(logits), _ptr(route), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return logits, route
+
+
+def ds_route_bucket(route: torch.Tensor, T: int):
+    """Returns (perm, inv_perm, offsets[T+1]) as int32 device tensors."""
+    B = route.shape[0]
+    perm = torch.empty((B,), dtype=torch.int32, device=route.device)
+    inv = torch.empty((B,), dtype=torch.int32, device=route.device)
+    off = torch.empty((T + 1,), dtype=torch.int32, device=route.device)
+    _chk(load().ds_route_bucket(_ptr(route, torch.int32), B, T, _ptr(perm), _ptr(inv), _ptr(off), _stream()))
+    return perm, inv, off
+
+
+def ds_sliced_linear(x, w, bias, groups: ds_groups, act=DS_ACT_NONE, residual=None, y=None, y_dtype=torch.bfloat16,
+                     n_full: Optional[int] = None):
+    """x: [B, rows, x_ld] bf16; w: [N_full, K_full] bf16.  Writes only the valid slices of y."""
+    lib = load()
+    B, rows, x_ld = x.shape
+    N_full, K_full = w.shape
+    if y is None:
+        y = torch.zeros((B, rows, N_full), dtype=y_dtype, device=x.device)
+    ws = _ws(lib.ds_sliced_linear_workspace(B, rows, groups.T), x)
+    _chk(lib.ds_sliced_linear(_ptr(x, torch.bfloat16), ctypes.c_int64(x_ld), _ptr(w, torch.bfloat16),
+                              ctypes.c_int64(w.stride(0)), N_full, K_full, _ptr(bias), ctypes.byref(groups), B, rows,
+                              act, _ptr(residual), ctypes.c_int64(residual.shape[-1] if residual is not None else 0),
+                              _ptr(y), DS_BF16 if y.dtype == torch.bfloat16 else DS_F32, ctypes.c_int64(y.shape[-1]),
+                              _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return y
+
+
+def ds_sliced_conv(x, w, scale, shift, groups: ds_groups, stride: int, pad: int, act=DS_ACT_RELU, residual=None,
+                   y=None):
+    """fp32: x [B,C_I,H,W], w [C_O,C_I,K,K].  bf16: x [B,H,W,C_I], w [C_O,K,K,C_I]."""
+    lib = load()
+    if x.dtype == torch.float32:
+        B, C_I, H, W = x.shape
+        C_O, K = w.shape[0], w.shape[2]
+        dt, layout = DS_F32, DS_NCHW
+    else:
+        B, H, W, C_I = x.shape
+        C_O, K = w.shape[0], w.shape[1]
+        dt, layout = DS_BF16, DS_NHWC
+    Ho, Wo = (H + 2 * pad - K) // stride + 1, (W + 2 * pad - K) // stride + 1
+    if y is None:
+        shp = (B, C_O, Ho, Wo) if layout == DS_NCHW else (B, Ho, Wo, C_O)
+        y = torch.zeros(shp, dtype=x.dtype, device=x.device)
+    ws = _ws(lib.ds_sliced_conv_workspace(B, Ho, Wo, groups.T), x)
+    _chk(lib.ds_sliced_conv(_ptr(x), dt, layout, B, C_I, H, W, _ptr(w, x.dtype), C_O, K, _ptr(scale), _ptr(shift),
+                            ctypes.byref(groups), stride, pad, act, _ptr(residual), _ptr(y), _ptr(ws),
+                            ctypes.c_size_t(ws.numel()), _stream()))
+    return y
+
+
+def ds_sliced_dwconv(x, w, scale, shift, groups: ds_groups, stride: int, act=DS_ACT_RELU, y=None):
+    """x: [B,H,W,C] bf16; w: [3,3,C] bf16."""
+    lib = load()
+    B, H, W, C = x.shape
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    if y is None:
+        y = torch.zeros((B, Ho, Wo, C), dtype=x.dtype, device=x.device)
+    ws = _ws(lib.ds_slot_workspace(B), x)
+    _chk(lib.ds_sliced_dwconv(_ptr(x, torch.bfloat16), B, C, H, W, _ptr(w, torch.bfloat16), _ptr(scale), _ptr(shift),
+                              ctypes.byref(groups), stride, act, _ptr(y), _ptr(ws), ctypes.c_size_t(ws.numel()),
+                              _stream()))
+    return y
+
+
+def ds_sliced_layernorm(x, gamma, beta, eps: float, groups: ds_groups, y=None):
+    lib = load()
+    B, rows, ld = x.shape
+    if y is None:
+        y = torch.zeros_like(x)
+    ws = _ws(lib.ds_slot_workspace(B), x)
+    _chk(lib.ds_sliced_layernorm(_ptr(x, torch.bfloat16), ctypes.c_int64(ld), _ptr(gamma, torch.float32),
+                                 _ptr(beta, torch.float32), ctypes.c_float(eps), ctypes.byref(groups), B, rows,
+                                 _ptr(y), ctypes.c_int64(y.shape[-1]), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return y
+
+
+def ds_sliced_mhsa(x, wqkv, bqkv, wproj, bproj, H: int, head_dim: int, groups: ds_groups, residual=None, y=None):
+    """x: [B,N,D_e] bf16; wqkv: [3,H*Dh,D_e] bf16; wproj: [D_e,H*Dh] bf16."""
+    lib = load()
+    B, N, D_e = x.shape
+    if y is None:
+        y = torch.zeros_like(x)
+    ws = _ws(lib.ds_sliced_mhsa_workspace(B, N, H, head_dim, groups.T), x)
+    _chk(lib.ds_sliced_mhsa(_ptr(x, torch.bfloat16), B, N, D_e, _ptr(wqkv, torch.bfloat16), _ptr(bqkv),
+                            _ptr(wproj, torch.bfloat16), _ptr(bproj), H, head_dim, ctypes.byref(groups),
+                            _ptr(residual), _ptr(y), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return y
+
+
+def ds_forward(net: "Net", images, route_override=None, logit_bias=None, logits=None, routes=None, ws=None):
+    """images: [B,3,S,S] bf16.  Returns (logits [B,classes] fp32, routes [n_gates,B] int32)."""
+    lib = load()
+    B = images.shape[0]
+    if logits is None:
+        logits = torch.empty((B, net.num_classes), dtype=torch.float32, device=images.device)
+    if routes is None:
+        routes = torch.empty((net.n_gates, B), dtype=torch.int32, device=images.device)
+    if ws is None:
+        ws = net.workspace(B)
+    _chk(lib.ds_forward(ctypes.byref(net.c_struct), _ptr(images, torch.bfloat16), B, _ptr(route_override),
+                        _ptr(logit_bias), _ptr(logits), _ptr(routes), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return logits, routes

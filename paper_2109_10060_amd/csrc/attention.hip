@@ -1,0 +1,139 @@
+// Head-sliced self-attention (Section 3.4, Eq. 17): one workgroup per (slot, head),
+// heads at or beyond the slot's head count exit at once.  Head dimension 64,
+// sequence length up to 224 (7 key tiles of 32).
+//
+// K and V^T of the head live in LDS.  Each wavefront takes 32-query tiles:
+//   S^T[key][q] = K . Q^T   (v_mfma_f32_32x32x16_bf16; A = K rows from LDS, B = Q rows from global)
+// so that one lane owns a fixed query column and half of its keys: the row
+// maximum and sum of the softmax are in-lane reductions plus one exchange with
+// lane^32.  The normalised probabilities are rounded to bf16 in registers and fed
+// straight back as the A operand of  O = P . V ; the key order an accumulator
+// holds (runs of 4 keys) is reproduced on the V^T side with two 8-byte LDS reads,
+// so no shuffle or LDS round trip of P is needed.
+#include "common.h"
+
+namespace {
+
+constexpr int DH = 64, NKT = 7, KEYS = NKT * 32, K_LD = DH + 8, V_LD = KEYS + 8;
+
+__global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                        const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
+                                                        int64_t sample_stride, int ld, int o_ld,
+                                                        int64_t o_sample_stride, const int32_t* slot_group,
+                                                        const GroupTable gt, int N, float scale) {
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[KEYS * K_LD];
+    __shared__ __attribute__((aligned(16))) bf16_t Vt[DH * V_LD];
+    const int slot = blockIdx.x, head = blockIdx.y;
+    const int g = slot_group ? slot_group[slot] : 0;
+    if (head * DH >= gt.k_out[g]) return;
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)slot * sample_stride + head * DH;
+
+    for (int c = tid; c < KEYS * 8; c += 256) {
+        const int row = c >> 3, ch = (c & 7) * 8;
+        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+        if (row < N) {
+            kv = *(const uint4*)(k + base + (int64_t)row * ld + ch);
+            vv = *(const uint4*)(v + base + (int64_t)row * ld + ch);
+        }
+        *(uint4*)(Ks + row * K_LD + ch) = kv;
+        const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            Vt[(ch + 2 * i) * V_LD + row] = (bf16_t)(w[i] & 0xffffu);
+            Vt[(ch + 2 * i + 1) * V_LD + row] = (bf16_t)(w[i] >> 16);
+        }
+    }
+    __syncthreads();
+
+    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    const int nqt = (N + 31) / 32;
+    for (int qt = wave; qt < nqt; qt += 4) {
+        const int qrow = qt * 32 + l32;
+        bf16x8_t qf[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4 t = make_uint4(0, 0, 0, 0);
+            if (qrow < N) t = *(const uint4*)(q + base + (int64_t)qrow * ld + kk * 16 + lhi * 8);
+            qf[kk] = *(bf16x8_t*)&t;
+        }
+        f32x16_t sacc[NKT];
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sacc[kt][e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8_t kf = *(const bf16x8_t*)(Ks + (kt * 32 + l32) * K_LD + kk * 16 + lhi * 8);
+                sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kt], 0, 0, 0);
+            }
+        }
+        float m = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = kt * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                const float s = key < N ? sacc[kt][e] * scale : -INFINITY;
+                sacc[kt][e] = s;
+                m = fmaxf(m, s);
+            }
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        float sum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float p = __expf(sacc[kt][e] - m);
+                sacc[kt][e] = p;
+                sum += p;
+            }
+        sum += __shfl_xor(sum, 32, 64);
+        const float inv = 1.0f / sum;
+
+        f32x16_t oacc[2];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[dt][e] = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                union { uint16_t u[8]; bf16x8_t v; } pf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf.u[e] = f2bf(sacc[kt][8 * half + e] * inv);
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const bf16_t* vp = Vt + (dt * 32 + l32) * V_LD + kt * 32 + 16 * half + 4 * lhi;
+                    union { uint2 h[2]; bf16x8_t v; } vf;
+                    vf.h[0] = *(const uint2*)vp;
+                    vf.h[1] = *(const uint2*)(vp + 8);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf.v, vf.v, oacc[dt], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int qr = qt * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+            if (qr < N) {
+                bf16_t* op = o + (int64_t)slot * o_sample_stride + (int64_t)qr * o_ld + head * DH + l32;
+                op[0] = f2bf(oacc[0][e]);
+                op[32] = f2bf(oacc[1][e]);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* o, int64_t sample_stride,
+                            int32_t ld, int32_t o_ld, int64_t o_sample_stride, const int32_t* slot_group,
+                            const GroupTable& gt, int32_t B, int32_t N, int32_t H, hipStream_t s) {
+    if (B <= 0 || H <= 0) return DS_OK;
+    if (N < 1 || N > KEYS) DS_FAIL(DS_EUNSUPPORTED, "attention: sequence length %d outside 1..%d", N, KEYS);
+    hipLaunchKernelGGL(attention_kernel, dim3((unsigned)B, (unsigned)H), dim3(256), 0, s, q, k, v, o, sample_stride,
+                       ld, o_ld, o_sample_stride, slot_group, gt, N, 0.125f);
+    DS_CHECK_LAUNCH("attention");
+    return DS_OK;
+}

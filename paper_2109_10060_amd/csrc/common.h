@@ -1,0 +1,154 @@
+// Internal declarations shared by the HIP translation units of libdsnet.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "dsnet.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even float -> bf16 (NaN stays NaN)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// ---- error reporting --------------------------------------------------------
+void ds_set_error(const char* fmt, ...);
+#define DS_FAIL(code, ...)            \
+    do {                              \
+        ds_set_error(__VA_ARGS__);    \
+        return (code);                \
+    } while (0)
+#define DS_CHECK_LAUNCH(what)                                                  \
+    do {                                                                       \
+        hipError_t e__ = hipGetLastError();                                    \
+        if (e__ != hipSuccess) DS_FAIL(DS_EHIP, "%s: %s", what, hipGetErrorString(e__)); \
+    } while (0)
+
+static inline bool ds_aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+static inline size_t ds_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- group table passed by value to kernels ---------------------------------
+struct GroupTable {
+    int32_t T;
+    int32_t k_in[DS_MAX_GROUPS];
+    int32_t k_out[DS_MAX_GROUPS];
+    int32_t row[DS_MAX_GROUPS];
+};
+
+// ---- grouped GEMM / implicit-GEMM convolution -------------------------------
+#define DS_GEMM_BM 128
+
+struct GemmArgs {
+    // operands
+    const bf16_t* A;       // activations
+    const bf16_t* Wt;      // weights [N_full][KK][w_tap_stride] (w_ld elements per output row)
+    void* C;               // output
+    const bf16_t* R;       // residual (nullable), addressed like C unless r_sample_stride is set
+    const float* scale;    // [rows][tab_ld] nullable (=1)
+    const float* shift;    // [rows][tab_ld] nullable (=0)
+    // addressing: element offset of (slot, local row p, col) =
+    //   index[slot] * sample_stride + (p + row0) * ld + col ;  ld <= 0 -> group's own width
+    const int32_t* a_index;  // slot -> sample (nullable = identity)
+    const int32_t* c_index;
+    int64_t a_sample_stride, c_sample_stride, r_sample_stride;
+    int32_t a_ld, c_ld, r_ld;
+    int32_t c_row0;          // output/residual row shift inside a sample
+    int32_t r_use_index;     // 0: residual ignores c_index (broadcast table such as a position embedding)
+    // weights
+    int64_t w_ld, w_tap_stride, w_seg_stride, c_seg_stride;
+    int32_t n_seg, tab_ld, tab_seg_stride;
+    // geometry: rows of a sample are the Ho*Wo output pixels of a KxK convolution over HxW
+    int32_t H, W, Ho, Wo, K, stride, pad, rows;
+    // schedule
+    const int32_t* offsets;  // device [T+1] slots
+    const int2* mtiles;      // device [(group, first row inside group)]
+    const int32_t* n_mtiles; // device scalar
+    int32_t act, out_f32;
+    GroupTable gt;
+};
+
+size_t ds_mtile_capacity(int32_t B, int32_t rows, int32_t T);
+// builds the m-tile list for (offsets, rows); list needs ds_mtile_capacity()*8 + 16 bytes
+int32_t ds_build_mtiles(const int32_t* offsets, int32_t T, int32_t rows, void* list, hipStream_t s);
+int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
+
+static inline const int2* ds_mtile_entries(const void* list) { return (const int2*)((const char*)list + 16); }
+static inline const int32_t* ds_mtile_count(const void* list) { return (const int32_t*)list; }
+
+// ---- routing agent ------------------------------------------------------------
+struct GateArgs {
+    const void* x;            // feature maps; nullptr = route on logit_bias alone
+    int32_t dtype, layout;
+    int32_t B, C, HW;         // items, stored channels, pixels
+    const int32_t* c_in;      // per item valid channels (nullable = C)
+    const int32_t* x_index;   // item -> sample block in x (nullable = identity)
+    int64_t x_sample_stride;
+    int32_t x_ld;             // NHWC row stride; <= 0 -> the item's own channel count
+    const float *w1, *b1, *w2, *b2;
+    int32_t C_mlp, T;
+    const float* logit_bias;        // [*, T] indexed by output row, nullable
+    const int32_t* out_index;       // item -> output row (nullable = identity)
+    const int32_t* route_override;  // indexed by output row, nullable
+    float* logits;
+    int32_t* route;
+    float* partial;           // [B][splits][C] scratch
+};
+size_t ds_gate_partial_bytes(int32_t B, int32_t C);
+int32_t ds_launch_gate(const GateArgs& a, hipStream_t s);
+int32_t ds_launch_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
+                         int32_t* offsets, int32_t* slot_group, hipStream_t s);
+
+// ---- memory-bound layers ------------------------------------------------------
+// Activations are [slot][pixel or token][channel]; a slot's block starts at
+// index[slot] * sample_stride and its rows have stride ld (<= 0: the slot's own width).
+struct ActView {
+    void* p;
+    const int32_t* index;
+    int64_t sample_stride;
+    int32_t ld;
+};
+
+int32_t ds_launch_expand_groups(const int32_t* offsets, int32_t T, int32_t* slot_group, hipStream_t s);
+int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* scale, const float* shift,
+                         int32_t tab_ld, const int32_t* slot_group, const GroupTable& gt, int32_t B, int32_t C,
+                         int32_t H, int32_t W, int32_t stride, int32_t act, hipStream_t s);
+int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const float* beta, float eps,
+                            const int32_t* slot_group, const GroupTable& gt, int32_t B, int32_t rows,
+                            int32_t row0, int32_t n_rows, hipStream_t s);
+int32_t ds_launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
+                       const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
+                       int32_t pad, int32_t Cout, hipStream_t s);
+int32_t ds_launch_maxpool(const bf16_t* x, bf16_t* y, int32_t B, int32_t H, int32_t W, int32_t C, hipStream_t s);
+// classifier: logits[out_index[slot]][o] = sum_c W[o][c] * v[c] + b[o]; v = spatial mean of x (HW > 0) or row 0 (HW == 0)
+int32_t ds_launch_head(ActView x, int32_t HW, const bf16_t* w, int32_t w_ld, const float* bias, int32_t n_out,
+                       const int32_t* slot_group, const GroupTable& gt, const int32_t* out_index, float* logits,
+                       int32_t B, int32_t C, hipStream_t s);
+int32_t ds_launch_patchify(const bf16_t* img, const int32_t* index, bf16_t* patches, int32_t B, int32_t H,
+                           int32_t W, int32_t P, hipStream_t s);
+int32_t ds_launch_cls_rows(ActView x, const bf16_t* cls, const bf16_t* pos, const int32_t* slot_group,
+                           const GroupTable& gt, int32_t B, hipStream_t s);
+int32_t ds_launch_conv_f32_nchw(const float* x, const float* w, const float* scale, const float* shift,
+                                int32_t tab_ld, const float* residual, float* y, const int32_t* slot_group,
+                                const int32_t* perm, const GroupTable& gt, int32_t B, int32_t C_I, int32_t C_O,
+                                int32_t H, int32_t W, int32_t K, int32_t stride, int32_t pad, int32_t act,
+                                hipStream_t s);
+int32_t ds_launch_compose_index(const int32_t* inner, const int32_t* outer, int32_t* out, int32_t B, hipStream_t s);
+int32_t ds_launch_lookup(const int32_t* idx, const GroupTable& gt, int32_t which, int32_t* out, int32_t B, hipStream_t s);
+
+// ---- attention ----------------------------------------------------------------
+// q, k, v, o: bf16 [slot][N][ld]; head j uses columns j*64..j*64+63; group g runs heads < k_out[g]/64
+int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* o, int64_t sample_stride,
+                            int32_t ld, int32_t o_ld, int64_t o_sample_stride, const int32_t* slot_group,
+                            const GroupTable& gt, int32_t B, int32_t N, int32_t H, hipStream_t s);

@@ -1,0 +1,466 @@
+// Memory-bound layers of the sliced networks: depthwise convolution (Section 3.3,
+// Eq. 10 with one channel per group) with split batch-norm (Eq. 14), LayerNorm over
+// the valid embedding slice, the unsliced stem convolution, max-pool, the
+// pool + classifier head with sliced input width, patch extraction, and the fp32
+// NCHW direct convolution used by the single-block configuration (Eq. 9).
+// All bf16 kernels move 8 channels (16 bytes) per lane and keep lanes of a
+// wavefront on consecutive channels of one pixel so that global accesses coalesce.
+#include "common.h"
+
+namespace {
+
+__device__ __forceinline__ void unpack8(const uint4 q, float* v) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ uint4 pack8(const float* v) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+__device__ __forceinline__ void loadf8(const float* p, float* v) {
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+__global__ void expand_groups_kernel(const int32_t* offsets, int T, int32_t* slot_group) {
+    for (int t = 0; t < T; ++t) {
+        const int b0 = offsets[t], b1 = offsets[t + 1];
+        for (int j = b0 + threadIdx.x; j < b1; j += blockDim.x) slot_group[j] = t;
+    }
+}
+
+// ---- depthwise 3x3 + scale/shift + activation ---------------------------------
+// grid (ceil(Ho*Wo*C/8 / 256), B); thread = (output pixel, 8-channel chunk)
+__global__ __launch_bounds__(256) void dwconv_kernel(ActView x, ActView y, const bf16_t* w, const float* scale,
+                                                     const float* shift, int tab_ld, const int32_t* slot_group,
+                                                     const GroupTable gt, int C, int H, int W, int Ho, int Wo,
+                                                     int stride, int act) {
+    const int slot = blockIdx.y;
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int c = gt.k_in[g];
+    const int chunks = c >> 3;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= Ho * Wo * chunks) return;
+    const int pix = idx / chunks, ch = (idx - pix * chunks) * 8;
+    const int oy = pix / Wo, ox = pix - oy * Wo;
+    const int xs = x.index ? x.index[slot] : slot;
+    const int ys = y.index ? y.index[slot] : slot;
+    const int xld = x.ld > 0 ? x.ld : c, yld = y.ld > 0 ? y.ld : c;
+    const bf16_t* xp = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride + ch;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+        const int iy = oy * stride + u - 1;
+        if (iy < 0 || iy >= H) continue;
+#pragma unroll
+        for (int v = 0; v < 3; ++v) {
+            const int ix = ox * stride + v - 1;
+            if (ix < 0 || ix >= W) continue;
+            float xv[8], wv[8];
+            unpack8(*(const uint4*)(xp + (int64_t)(iy * W + ix) * xld), xv);
+            unpack8(*(const uint4*)(w + (u * 3 + v) * C + ch), wv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
+        }
+    }
+    const int64_t ti = (int64_t)gt.row[g] * tab_ld + ch;
+    float sc[8], sh[8];
+    loadf8(scale + ti, sc);
+    loadf8(shift + ti, sh);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        acc[i] = acc[i] * sc[i] + sh[i];
+        if (act == DS_ACT_RELU) acc[i] = fmaxf(acc[i], 0.f);
+    }
+    *(uint4*)((bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)pix * yld + ch) = pack8(acc);
+}
+
+// ---- LayerNorm over the valid slice; one wavefront per row ----------------------
+__global__ __launch_bounds__(256) void layernorm_kernel(ActView x, ActView y, const float* gamma,
+                                                        const float* beta, float eps, const int32_t* slot_group,
+                                                        const GroupTable gt, int B, int rows, int row0, int n_rows) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (r >= B * n_rows) return;
+    const int slot = r / n_rows, p = row0 + (r - slot * n_rows);
+    (void)rows;
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int d = gt.k_in[g];
+    const int xs = x.index ? x.index[slot] : slot, ys = y.index ? y.index[slot] : slot;
+    const int xld = x.ld > 0 ? x.ld : d, yld = y.ld > 0 ? y.ld : d;
+    const bf16_t* xr = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride + (int64_t)p * xld;
+    bf16_t* yr = (bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)p * yld;
+    constexpr int MAXC = 4;  // up to 4 chunks of 8 per lane: d <= 2048
+    float v[MAXC][8];
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        const int ch = (k * 64 + lane) * 8;
+        if (ch < d) {
+            unpack8(*(const uint4*)(xr + ch), v[k]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += v[k][i];
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    const float mu = s / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        const int ch = (k * 64 + lane) * 8;
+        if (ch < d) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float t = v[k][i] - mu;
+                q += t * t;
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+    const float rstd = 1.0f / sqrtf(q / (float)d + eps);
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        const int ch = (k * 64 + lane) * 8;
+        if (ch < d) {
+            float gm[8], bt[8], o8[8];
+            loadf8(gamma + ch, gm);
+            loadf8(beta + ch, bt);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o8[i] = (v[k][i] - mu) * rstd * gm[i] + bt[i];
+            *(uint4*)(yr + ch) = pack8(o8);
+        }
+    }
+}
+
+// ---- stem: KxK stride-s convolution of a 3-channel NCHW image -> NHWC ----------
+// weights [K*K*3][Cout] bf16 staged in LDS as fp32; thread = (pixel, 8 output channels)
+__global__ __launch_bounds__(256) void stem_kernel(const bf16_t* img, const int32_t* index, bf16_t* y,
+                                                   const bf16_t* w, const float* scale, const float* shift, int H,
+                                                   int W, int Ho, int Wo, int K, int stride, int pad, int Cout) {
+    extern __shared__ float wl[];  // [K*K*3][Cout]
+    const int nw = K * K * 3 * Cout;
+    for (int i = threadIdx.x; i < nw; i += 256) wl[i] = bf2f(w[i]);
+    __syncthreads();
+    const int chunks = Cout >> 3;
+    const int ppb = 256 / chunks;  // pixels per block
+    const int slot = blockIdx.y;
+    const int pl = threadIdx.x / chunks, ch = (threadIdx.x - pl * chunks) * 8;
+    const int pix = blockIdx.x * ppb + pl;
+    if (pl >= ppb || pix >= Ho * Wo) return;
+    const int oy = pix / Wo, ox = pix - oy * Wo;
+    const int sample = index ? index[slot] : slot;
+    const bf16_t* ip = img + (int64_t)sample * 3 * H * W;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int u = 0; u < K; ++u) {
+        const int iy = oy * stride + u - pad;
+        if (iy < 0 || iy >= H) continue;
+        for (int v = 0; v < K; ++v) {
+            const int ix = ox * stride + v - pad;
+            if (ix < 0 || ix >= W) continue;
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const float xv = bf2f(ip[((int64_t)c * H + iy) * W + ix]);
+                const float* wp = wl + ((u * K + v) * 3 + c) * Cout + ch;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = fmaf(xv, wp[i], acc[i]);
+            }
+        }
+    }
+    float sc[8], sh[8];
+    loadf8(scale + ch, sc);
+    loadf8(shift + ch, sh);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = fmaxf(acc[i] * sc[i] + sh[i], 0.f);
+    *(uint4*)(y + ((int64_t)slot * Ho * Wo + pix) * Cout + ch) = pack8(acc);
+}
+
+// ---- 3x3 stride-2 pad-1 max-pool, NHWC -----------------------------------------
+__global__ __launch_bounds__(256) void maxpool_kernel(const bf16_t* x, bf16_t* y, int H, int W, int Ho, int Wo, int C) {
+    const int chunks = C >> 3;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= Ho * Wo * chunks) return;
+    const int b = blockIdx.y;
+    const int pix = idx / chunks, ch = (idx - pix * chunks) * 8;
+    const int oy = pix / Wo, ox = pix - oy * Wo;
+    float m[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m[i] = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+        const int iy = oy * 2 + u - 1;
+        if (iy < 0 || iy >= H) continue;
+#pragma unroll
+        for (int v = 0; v < 3; ++v) {
+            const int ix = ox * 2 + v - 1;
+            if (ix < 0 || ix >= W) continue;
+            float xv[8];
+            unpack8(*(const uint4*)(x + (((int64_t)b * H + iy) * W + ix) * C + ch), xv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], xv[i]);
+        }
+    }
+    *(uint4*)(y + (((int64_t)b * Ho + oy) * Wo + ox) * C + ch) = pack8(m);
+}
+
+// ---- pool + classifier; one workgroup per slot ----------------------------------
+__global__ __launch_bounds__(256) void head_kernel(ActView x, int HW, const bf16_t* w, int w_ld, const float* bias,
+                                                   int n_out, const int32_t* slot_group, const GroupTable gt,
+                                                   const int32_t* out_index, float* logits) {
+    extern __shared__ float vec[];  // [c]
+    __shared__ float red[8][256 + 8];
+    const int slot = blockIdx.x;
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int c = gt.k_in[g];
+    const int xs = x.index ? x.index[slot] : slot;
+    const int ld = x.ld > 0 ? x.ld : c;
+    const bf16_t* xp = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride;
+    const int tid = threadIdx.x;
+    if (HW > 0) {
+        const int lane_c = tid & 31, lane_r = tid >> 5;
+        const float inv = 1.0f / (float)HW;
+        for (int c0 = 0; c0 < c; c0 += 256) {
+            const int ch = c0 + lane_c * 8;
+            float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (ch < c) {
+                for (int r = lane_r; r < HW; r += 8) {
+                    float v[8];
+                    unpack8(*(const uint4*)(xp + (int64_t)r * ld + ch), v);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) s[i] += v[i];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) red[lane_r][lane_c * 8 + i] = s[i];
+            __syncthreads();
+            if (c0 + tid < c) {
+                float t = 0.f;
+#pragma unroll
+                for (int r = 0; r < 8; ++r) t += red[r][tid];
+                vec[c0 + tid] = t * inv;
+            }
+            __syncthreads();
+        }
+    } else {
+        for (int i = tid; i < c; i += 256) vec[i] = bf2f(xp[i]);
+        __syncthreads();
+    }
+    const int wave = tid >> 6, lane = tid & 63;
+    const int out = out_index ? out_index[slot] : slot;
+    for (int o = wave; o < n_out; o += 4) {
+        const bf16_t* wr = w + (int64_t)o * w_ld;
+        float s = 0.f;
+        for (int ch = lane * 8; ch < c; ch += 512) {
+            float wv[8];
+            unpack8(*(const uint4*)(wr + ch), wv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s = fmaf(wv[i], vec[ch + i], s);
+        }
+#pragma unroll
+        for (int k = 32; k > 0; k >>= 1) s += __shfl_xor(s, k, 64);
+        if (lane == 0) logits[(int64_t)out * n_out + o] = s + (bias ? bias[o] : 0.f);
+    }
+}
+
+// ---- patch extraction: NCHW image -> [slot][patch][(c,u,v)] ----------------------
+__global__ __launch_bounds__(256) void patchify_kernel(const bf16_t* img, const int32_t* index, bf16_t* out, int H,
+                                                       int W, int P) {
+    const int gw = W / P, gh = H / P;
+    const int kchunks = 3 * P * P / 8;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= gh * gw * kchunks) return;
+    const int slot = blockIdx.y;
+    const int sample = index ? index[slot] : slot;
+    const int patch = idx / kchunks, kc = (idx - patch * kchunks) * 8;
+    const int gy = patch / gw, gx = patch - gy * gw;
+    const int c = kc / (P * P), rem = kc - c * P * P;
+    const int u = rem / P, v = rem - u * P;
+    const uint4 q = *(const uint4*)(img + (((int64_t)sample * 3 + c) * H + gy * P + u) * W + gx * P + v);
+    *(uint4*)(out + ((int64_t)slot * gh * gw + patch) * (3 * P * P) + kc) = q;
+}
+
+// class-token row: x[slot][0][:d] = cls[:d] + pos[0][:d]
+__global__ void cls_rows_kernel(ActView x, const bf16_t* cls, const bf16_t* pos, const int32_t* slot_group,
+                                const GroupTable gt) {
+    const int slot = blockIdx.x;
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int d = gt.k_in[g];
+    const int xs = x.index ? x.index[slot] : slot;
+    bf16_t* xr = (bf16_t*)x.p + (int64_t)xs * x.sample_stride;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) xr[i] = f2bf(bf2f(cls[i]) + bf2f(pos[i]));
+}
+
+// ---- fp32 NCHW direct convolution (single dynamic block, Eq. 9 + Eq. 14) ---------
+// grid (ceil(Ho*Wo/256), C_O, B); thread = one output element; samples keep their order
+__global__ __launch_bounds__(256) void conv_f32_kernel(const float* x, const float* w, const float* scale,
+                                                       const float* shift, int tab_ld, const float* residual,
+                                                       float* y, const int32_t* slot_group, const int32_t* perm,
+                                                       const GroupTable gt, int C_I, int C_O, int H, int W, int Ho,
+                                                       int Wo, int K, int stride, int pad, int act) {
+    const int slot = blockIdx.z;
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int o = blockIdx.y;
+    if (o >= gt.k_out[g]) return;
+    const int pix = blockIdx.x * 256 + threadIdx.x;
+    if (pix >= Ho * Wo) return;
+    const int b = perm ? perm[slot] : slot;
+    const int c_in = gt.k_in[g];
+    const int oy = pix / Wo, ox = pix - oy * Wo;
+    const float* xb = x + (int64_t)b * C_I * H * W;
+    const float* wo = w + (int64_t)o * C_I * K * K;
+    float acc = 0.f;
+    for (int i = 0; i < c_in; ++i) {
+        for (int u = 0; u < K; ++u) {
+            const int iy = oy * stride + u - pad;
+            if (iy < 0 || iy >= H) continue;
+            for (int v = 0; v < K; ++v) {
+                const int ix = ox * stride + v - pad;
+                if (ix < 0 || ix >= W) continue;
+                acc = fmaf(wo[(i * K + u) * K + v], xb[((int64_t)i * H + iy) * W + ix], acc);
+            }
+        }
+    }
+    const int64_t ti = (int64_t)gt.row[g] * tab_ld + o;
+    float val = acc * (scale ? scale[ti] : 1.f) + (shift ? shift[ti] : 0.f);
+    const int64_t yi = (((int64_t)b * C_O + o) * Ho + oy) * Wo + ox;
+    if (residual) val += residual[yi];
+    if (act == DS_ACT_RELU) val = fmaxf(val, 0.f);
+    y[yi] = val;
+}
+
+__global__ void compose_index_kernel(const int32_t* inner, const int32_t* outer, int32_t* out, int B) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < B) out[j] = inner[outer[j]];
+}
+
+__global__ void lookup_kernel(const int32_t* idx, const GroupTable gt, int which, int32_t* out, int B) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= B) return;
+    const int g = idx[j];
+    out[j] = which == 0 ? gt.k_in[g] : (which == 1 ? gt.k_out[g] : gt.row[g]);
+}
+
+}  // namespace
+
+int32_t ds_launch_expand_groups(const int32_t* offsets, int32_t T, int32_t* slot_group, hipStream_t s) {
+    hipLaunchKernelGGL(expand_groups_kernel, dim3(1), dim3(256), 0, s, offsets, T, slot_group);
+    DS_CHECK_LAUNCH("expand groups");
+    return DS_OK;
+}
+
+int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* scale, const float* shift,
+                         int32_t tab_ld, const int32_t* slot_group, const GroupTable& gt, int32_t B, int32_t C,
+                         int32_t H, int32_t W, int32_t stride, int32_t act, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    const int Ho = (H + 2 - 3) / stride + 1, Wo = (W + 2 - 3) / stride + 1;
+    int cmax = 0;
+    for (int t = 0; t < gt.T; ++t) cmax = gt.k_in[t] > cmax ? gt.k_in[t] : cmax;
+    const int64_t n = (int64_t)Ho * Wo * (cmax / 8);
+    if (n <= 0) return DS_OK;
+    dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(dwconv_kernel, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
+                       Ho, Wo, stride, act);
+    DS_CHECK_LAUNCH("depthwise conv");
+    return DS_OK;
+}
+
+int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const float* beta, float eps,
+                            const int32_t* slot_group, const GroupTable& gt, int32_t B, int32_t rows,
+                            int32_t row0, int32_t n_rows, hipStream_t s) {
+    if (B <= 0 || n_rows <= 0) return DS_OK;
+    const int64_t total = (int64_t)B * n_rows;
+    hipLaunchKernelGGL(layernorm_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, x, y, gamma, beta, eps,
+                       slot_group, gt, B, rows, row0, n_rows);
+    DS_CHECK_LAUNCH("layernorm");
+    return DS_OK;
+}
+
+int32_t ds_launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
+                       const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
+                       int32_t pad, int32_t Cout, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    const int Ho = (H + 2 * pad - K) / stride + 1, Wo = (W + 2 * pad - K) / stride + 1;
+    const int chunks = Cout / 8, ppb = 256 / chunks;
+    dim3 grid((unsigned)((Ho * Wo + ppb - 1) / ppb), (unsigned)B);
+    const size_t shm = (size_t)K * K * 3 * Cout * sizeof(float);
+    hipLaunchKernelGGL(stem_kernel, grid, dim3(256), shm, s, img, index, y, w, scale, shift, H, W, Ho, Wo, K, stride,
+                       pad, Cout);
+    DS_CHECK_LAUNCH("stem conv");
+    return DS_OK;
+}
+
+int32_t ds_launch_maxpool(const bf16_t* x, bf16_t* y, int32_t B, int32_t H, int32_t W, int32_t C, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    const int Ho = (H + 2 - 3) / 2 + 1, Wo = (W + 2 - 3) / 2 + 1;
+    const int64_t n = (int64_t)Ho * Wo * (C / 8);
+    dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(maxpool_kernel, grid, dim3(256), 0, s, x, y, H, W, Ho, Wo, C);
+    DS_CHECK_LAUNCH("maxpool");
+    return DS_OK;
+}
+
+int32_t ds_launch_head(ActView x, int32_t HW, const bf16_t* w, int32_t w_ld, const float* bias, int32_t n_out,
+                       const int32_t* slot_group, const GroupTable& gt, const int32_t* out_index, float* logits,
+                       int32_t B, int32_t C, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    hipLaunchKernelGGL(head_kernel, dim3((unsigned)B), dim3(256), (size_t)C * sizeof(float), s, x, HW, w, w_ld, bias,
+                       n_out, slot_group, gt, out_index, logits);
+    DS_CHECK_LAUNCH("classifier head");
+    return DS_OK;
+}
+
+int32_t ds_launch_patchify(const bf16_t* img, const int32_t* index, bf16_t* patches, int32_t B, int32_t H,
+                           int32_t W, int32_t P, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    const int64_t n = (int64_t)(H / P) * (W / P) * (3 * P * P / 8);
+    dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(patchify_kernel, grid, dim3(256), 0, s, img, index, patches, H, W, P);
+    DS_CHECK_LAUNCH("patchify");
+    return DS_OK;
+}
+
+int32_t ds_launch_cls_rows(ActView x, const bf16_t* cls, const bf16_t* pos, const int32_t* slot_group,
+                           const GroupTable& gt, int32_t B, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    hipLaunchKernelGGL(cls_rows_kernel, dim3((unsigned)B), dim3(128), 0, s, x, cls, pos, slot_group, gt);
+    DS_CHECK_LAUNCH("class-token rows");
+    return DS_OK;
+}
+
+int32_t ds_launch_conv_f32_nchw(const float* x, const float* w, const float* scale, const float* shift,
+                                int32_t tab_ld, const float* residual, float* y, const int32_t* slot_group,
+                                const int32_t* perm, const GroupTable& gt, int32_t B, int32_t C_I, int32_t C_O,
+                                int32_t H, int32_t W, int32_t K, int32_t stride, int32_t pad, int32_t act,
+                                hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    const int Ho = (H + 2 * pad - K) / stride + 1, Wo = (W + 2 * pad - K) / stride + 1;
+    int omax = 0;
+    for (int t = 0; t < gt.T; ++t) omax = gt.k_out[t] > omax ? gt.k_out[t] : omax;
+    if (omax <= 0) return DS_OK;
+    dim3 grid((unsigned)((Ho * Wo + 255) / 256), (unsigned)omax, (unsigned)B);
+    hipLaunchKernelGGL(conv_f32_kernel, grid, dim3(256), 0, s, x, w, scale, shift, tab_ld, residual, y, slot_group,
+                       perm, gt, C_I, C_O, H, W, Ho, Wo, K, stride, pad, act);
+    DS_CHECK_LAUNCH("fp32 conv");
+    return DS_OK;
+}
+
+int32_t ds_launch_compose_index(const int32_t* inner, const int32_t* outer, int32_t* out, int32_t B, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    hipLaunchKernelGGL(compose_index_kernel, dim3((B + 255) / 256), dim3(256), 0, s, inner, outer, out, B);
+    DS_CHECK_LAUNCH("compose index");
+    return DS_OK;
+}
+
+int32_t ds_launch_lookup(const int32_t* idx, const GroupTable& gt, int32_t which, int32_t* out, int32_t B, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    hipLaunchKernelGGL(lookup_kernel, dim3((B + 255) / 256), dim3(256), 0, s, idx, gt, which, out, B);
+    DS_CHECK_LAUNCH("lookup");
+    return DS_OK;
+}

@@ -1,0 +1,283 @@
+// Routing agent and batch bucketing.
+//
+// Gate (Section 3.5): the encoder averages each valid channel over H*W (Eq. 21);
+// the routing head is a two-layer MLP whose first layer is input-sliced to the
+// valid channels, followed at inference by an argmax over the route scores
+// (Eq. 22).  Bucketing turns the per-sample route ids into a stable bucket-major
+// permutation so that every route group is a contiguous range of slots.
+#include "common.h"
+
+namespace {
+
+constexpr int POOL_SPLIT_MAX = 8;
+
+// ---- encoder: partial spatial sums -------------------------------------------
+// NHWC: grid (items, splits); block 256 = 32 channel chunks of 8 x 8 row lanes.
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float* v);
+template <>
+__device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float* v) {
+    const uint4 q = *(const uint4*)p;
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+template <>
+__device__ __forceinline__ void load8<float>(const float* p, float* v) {
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pool_nhwc_kernel(const GateArgs a, int splits) {
+    __shared__ float red[8][256 + 8];
+    const int item = blockIdx.x, sp = blockIdx.y;
+    const int c = a.c_in ? a.c_in[item] : a.C;
+    const int sample = a.x_index ? a.x_index[item] : item;
+    const int ld = a.x_ld > 0 ? a.x_ld : c;
+    const T* x = (const T*)a.x + (int64_t)sample * a.x_sample_stride;
+    const int lane_c = threadIdx.x & 31, lane_r = threadIdx.x >> 5;
+    const int per = (a.HW + splits - 1) / splits;
+    const int r0 = sp * per, r1 = min(a.HW, r0 + per);
+    for (int c0 = 0; c0 < c; c0 += 256) {
+        const int ch = c0 + lane_c * 8;
+        float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (ch < c) {
+            for (int r = r0 + lane_r; r < r1; r += 8) {
+                float v[8];
+                load8<T>(x + (int64_t)r * ld + ch, v);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) s[i] += v[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) red[lane_r][lane_c * 8 + i] = s[i];
+        __syncthreads();
+        const int cc = c0 + threadIdx.x;
+        if (cc < c) {
+            float t = 0.f;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) t += red[r][threadIdx.x];
+            a.partial[((int64_t)item * splits + sp) * a.C + cc] = t;
+        }
+        __syncthreads();
+    }
+}
+
+// NCHW: one wavefront per (item, channel); grid (items, ceil(C/4)), block 256; splits == 1.
+template <typename T>
+__global__ __launch_bounds__(256) void pool_nchw_kernel(const GateArgs a) {
+    const int item = blockIdx.x;
+    const int ch = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int c = a.c_in ? a.c_in[item] : a.C;
+    if (ch >= c) return;
+    const int sample = a.x_index ? a.x_index[item] : item;
+    const T* x = (const T*)a.x + (int64_t)sample * a.x_sample_stride + (int64_t)ch * a.HW;
+    float s = 0.f;
+    for (int i = lane; i < a.HW; i += 64) {
+        if constexpr (sizeof(T) == 2) s += bf2f(x[i]);
+        else s += x[i];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (lane == 0) a.partial[(int64_t)item * a.C + ch] = s;
+}
+
+// ---- routing head: MLP + argmax, one workgroup per item -----------------------
+__global__ __launch_bounds__(256) void gate_head_kernel(const GateArgs a, int splits) {
+    extern __shared__ double sm[];          // pooled[C] then hidden[C_mlp]
+    double* pooled = sm;
+    double* hidden = sm + a.C;
+    const int item = blockIdx.x;
+    const int out = a.out_index ? a.out_index[item] : item;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool have_x = a.x != nullptr;
+    if (have_x) {
+        const int c = a.c_in ? a.c_in[item] : a.C;
+        const double inv = 1.0 / (double)a.HW;
+        for (int i = tid; i < c; i += 256) {
+            double s = 0.0;
+            for (int sp = 0; sp < splits; ++sp) s += (double)a.partial[((int64_t)item * splits + sp) * a.C + i];
+            pooled[i] = s * inv;
+        }
+        __syncthreads();
+        for (int j = wave; j < a.C_mlp; j += 4) {
+            const float* wr = a.w1 + (int64_t)j * a.C;
+            double s = 0.0;
+            for (int i = lane; i < c; i += 64) s += (double)wr[i] * pooled[i];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+            if (lane == 0) {
+                s += a.b1 ? (double)a.b1[j] : 0.0;
+                hidden[j] = s > 0.0 ? s : 0.0;
+            }
+        }
+        __syncthreads();
+    }
+    for (int t = wave; t < a.T; t += 4) {
+        double s = 0.0;
+        if (have_x) {
+            const float* wr = a.w2 + (int64_t)t * a.C_mlp;
+            for (int j = lane; j < a.C_mlp; j += 64) s += (double)wr[j] * hidden[j];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+            s += a.b2 ? (double)a.b2[t] : 0.0;
+        }
+        if (lane == 0) {
+            if (a.logit_bias) s += (double)a.logit_bias[(int64_t)out * a.T + t];
+            a.logits[(int64_t)out * a.T + t] = (float)s;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int arg = 0;
+        bool have = false;
+        float best = 0.f;
+        for (int t = 0; t < a.T; ++t) {
+            const float v = a.logits[(int64_t)out * a.T + t];
+            if (v != v) continue;
+            if (!have || v > best) { best = v; arg = t; have = true; }
+        }
+        if (a.route_override) arg = a.route_override[out];
+        a.route[out] = arg;
+    }
+}
+
+// ---- bucketing ----------------------------------------------------------------
+__global__ __launch_bounds__(1024) void bucket_kernel(const int32_t* route, int B, int T, int32_t* perm,
+                                                      int32_t* inv_perm, int32_t* offsets, int32_t* slot_group) {
+    __shared__ int hist[1024 + 1];
+    __shared__ int chunk[1024];
+    const int tid = threadIdx.x;
+    for (int t = tid; t <= T; t += 1024) hist[t] = 0;
+    __syncthreads();
+    for (int b = tid; b < B; b += 1024) {
+        const int r = route[b];
+        if (r >= 0 && r < T) atomicAdd(&hist[r], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int acc = 0;
+        for (int t = 0; t < T; ++t) {
+            const int h = hist[t];
+            hist[t] = acc;
+            acc += h;
+        }
+        hist[T] = acc;
+    }
+    __syncthreads();
+    for (int t = tid; t <= T; t += 1024) offsets[t] = hist[t];
+    int pos = tid < T ? hist[tid] : 0;
+    for (int b0 = 0; b0 < B; b0 += 1024) {
+        __syncthreads();
+        if (b0 + tid < B) chunk[tid] = route[b0 + tid];
+        __syncthreads();
+        if (tid < T) {
+            const int n = min(1024, B - b0);
+            for (int i = 0; i < n; ++i) {
+                if (chunk[i] == tid) {
+                    perm[pos] = b0 + i;
+                    if (inv_perm) inv_perm[b0 + i] = pos;
+                    if (slot_group) slot_group[pos] = tid;
+                    ++pos;
+                }
+            }
+        }
+    }
+}
+
+__global__ void bn_fold_kernel(const float* gamma, const float* beta, const float* mean, const float* var,
+                               float eps, int T, int C, float* scale, float* shift) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T * C) return;
+    const int c = i % C;
+    const float s = gamma[c] / sqrtf(var[i] + eps);
+    scale[i] = s;
+    shift[i] = beta[c] - mean[i] * s;
+}
+
+}  // namespace
+
+size_t ds_gate_partial_bytes(int32_t B, int32_t C) { return (size_t)B * C * POOL_SPLIT_MAX * sizeof(float); }
+
+int32_t ds_launch_gate(const GateArgs& a, hipStream_t s) {
+    if (a.B <= 0) return DS_OK;
+    int splits = 1;
+    if (a.x) {
+        if (a.layout == DS_NHWC) {
+            splits = a.HW >= 2048 ? 8 : (a.HW >= 512 ? 4 : (a.HW >= 128 ? 2 : 1));
+            dim3 grid(a.B, splits);
+            if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nhwc_kernel<bf16_t>, grid, dim3(256), 0, s, a, splits);
+            else hipLaunchKernelGGL(pool_nhwc_kernel<float>, grid, dim3(256), 0, s, a, splits);
+        } else {
+            dim3 grid(a.B, (a.C + 3) / 4);
+            if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nchw_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+            else hipLaunchKernelGGL(pool_nchw_kernel<float>, grid, dim3(256), 0, s, a);
+        }
+        DS_CHECK_LAUNCH("gate encoder");
+    }
+    const size_t shm = (size_t)(a.C + a.C_mlp) * sizeof(double);
+    hipLaunchKernelGGL(gate_head_kernel, dim3(a.B), dim3(256), shm, s, a, splits);
+    DS_CHECK_LAUNCH("gate head");
+    return DS_OK;
+}
+
+int32_t ds_launch_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
+                         int32_t* offsets, int32_t* slot_group, hipStream_t s) {
+    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(1024), 0, s, route, B, T, perm, inv_perm, offsets, slot_group);
+    DS_CHECK_LAUNCH("route bucket");
+    return DS_OK;
+}
+
+extern "C" int32_t ds_bn_fold(const float* gamma, const float* beta, const float* mean, const float* var,
+                              float eps, int32_t T, int32_t C, float* scale, float* shift, void* stream) {
+    if (T < 0 || C < 0) DS_FAIL(DS_EINVAL, "ds_bn_fold: negative size");
+    if (T == 0 || C == 0) return DS_OK;
+    if (!gamma || !beta || !mean || !var || !scale || !shift) DS_FAIL(DS_EINVAL, "ds_bn_fold: null pointer");
+    const int n = T * C;
+    hipLaunchKernelGGL(bn_fold_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, gamma, beta, mean,
+                       var, eps, T, C, scale, shift);
+    DS_CHECK_LAUNCH("bn fold");
+    return DS_OK;
+}
+
+extern "C" int32_t ds_gate(const void* x, int32_t x_dtype, int32_t x_layout, int32_t B, int32_t C, int32_t HW,
+                           const int32_t* c_in, const float* w1, const float* b1, int32_t C_mlp, const float* w2,
+                           const float* b2, int32_t T, const float* logit_bias, float* logits_out,
+                           int32_t* route_out, void* ws, size_t ws_bytes, void* stream) {
+    if (B < 0 || T < 1) DS_FAIL(DS_EINVAL, "ds_gate: B < 0 or T < 1");
+    if (B == 0) return DS_OK;
+    if (!logits_out || !route_out) DS_FAIL(DS_EINVAL, "ds_gate: null output");
+    GateArgs a = {};
+    if (x) {
+        if (C < 1 || HW < 1 || C_mlp < 1) DS_FAIL(DS_EINVAL, "ds_gate: bad C/HW/C_mlp");
+        if (!w1 || !w2) DS_FAIL(DS_EINVAL, "ds_gate: null weights");
+        if (x_dtype != DS_F32 && x_dtype != DS_BF16) DS_FAIL(DS_EUNSUPPORTED, "ds_gate: dtype");
+        if (x_layout != DS_NCHW && x_layout != DS_NHWC) DS_FAIL(DS_EUNSUPPORTED, "ds_gate: layout");
+        if (x_layout == DS_NHWC && ((C % 8) != 0 || !ds_aligned16(x))) DS_FAIL(DS_EALIGN, "ds_gate: NHWC needs C %% 8 == 0 and a 16-byte aligned x");
+        if ((size_t)C + C_mlp > 6000) DS_FAIL(DS_EUNSUPPORTED, "ds_gate: C + C_mlp too large");
+        if (!ws || ws_bytes < ds_gate_partial_bytes(B, C)) DS_FAIL(DS_EWORKSPACE, "ds_gate: workspace needs %zu bytes", ds_gate_partial_bytes(B, C));
+    } else if (!logit_bias) {
+        DS_FAIL(DS_EINVAL, "ds_gate: neither x nor logit_bias given");
+    } else {
+        C = 0; C_mlp = 0;
+    }
+    a.x = x; a.dtype = x_dtype; a.layout = x_layout; a.B = B; a.C = C; a.HW = HW;
+    a.c_in = c_in; a.x_index = nullptr; a.x_sample_stride = (int64_t)C * HW; a.x_ld = C;
+    a.w1 = w1; a.b1 = b1; a.w2 = w2; a.b2 = b2; a.C_mlp = C_mlp; a.T = T;
+    a.logit_bias = logit_bias; a.out_index = nullptr; a.route_override = nullptr;
+    a.logits = logits_out; a.route = route_out; a.partial = (float*)ws;
+    return ds_launch_gate(a, (hipStream_t)stream);
+}
+
+extern "C" int32_t ds_route_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
+                                   int32_t* offsets, void* stream) {
+    if (B < 0 || T < 1 || T > 1024) DS_FAIL(DS_EINVAL, "ds_route_bucket: need B >= 0 and 1 <= T <= 1024");
+    if (!offsets) DS_FAIL(DS_EINVAL, "ds_route_bucket: null offsets");
+    if (B > 0 && (!route || !perm || !inv_perm)) DS_FAIL(DS_EINVAL, "ds_route_bucket: null pointer");
+    return ds_launch_bucket(route, B, T, perm, inv_perm, offsets, nullptr, (hipStream_t)stream);
+}

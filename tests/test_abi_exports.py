@@ -1,0 +1,67 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol that
+include/dsnet.h declares; host-side argument validation returns error codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2109_10060_amd as ds
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    if not os.path.exists(ds.LIB_PATH):
+        from paper_2109_10060_amd.build import build
+        build(verbose=False)
+    return ds.load()
+
+
+def test_every_declared_symbol_is_exported():
+    lib = _lib()
+    header = open(os.path.join(ROOT, "include", "dsnet.h")).read()
+    declared = set(re.findall(r"\b(ds_[a-z0-9_]+)\s*\(", header))
+    assert {"ds_gate", "ds_route_bucket", "ds_sliced_conv", "ds_sliced_dwconv", "ds_sliced_linear",
+            "ds_sliced_mhsa", "ds_forward"} <= declared
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in dsnet.h but not exported"
+    assert declared == set(ds.EXPORTS)
+    assert lib.ds_version() >= 1
+
+
+def test_host_validation_returns_codes_without_a_gpu():
+    lib = _lib()
+    g = ds.ds_groups()
+    g.T = 0
+    rc = lib.ds_sliced_linear(None, ctypes.c_int64(8), None, ctypes.c_int64(8), 8, 8, None, ctypes.byref(g), 4, 4, 0,
+                              None, ctypes.c_int64(0), None, 1, ctypes.c_int64(8), None, ctypes.c_size_t(0), None)
+    assert rc == ds.DS_EINVAL and b"T=0" in lib.ds_last_error()
+    assert lib.ds_route_bucket(None, 4, 0, None, None, None, None) == ds.DS_EINVAL
+    assert lib.ds_route_bucket(None, -1, 4, None, None, None, None) == ds.DS_EINVAL
+    assert lib.ds_gate(None, 0, 0, 4, 8, 16, None, None, None, 4, None, None, 0, None, None, None, None,
+                       ctypes.c_size_t(0), None) == ds.DS_EINVAL
+    g.T = 1
+    g.offsets = 1024  # never dereferenced on the host
+    g.k_in[0], g.k_out[0] = 12, 8
+    rc = lib.ds_sliced_linear(None, ctypes.c_int64(16), None, ctypes.c_int64(16), 8, 16, None, ctypes.byref(g), 4, 4,
+                              0, None, ctypes.c_int64(0), None, 1, ctypes.c_int64(8), None, ctypes.c_size_t(0), None)
+    assert rc == ds.DS_EALIGN
+    g.k_in[0] = 32
+    rc = lib.ds_sliced_linear(None, ctypes.c_int64(16), None, ctypes.c_int64(16), 8, 16, None, ctypes.byref(g), 4, 4,
+                              0, None, ctypes.c_int64(0), None, 1, ctypes.c_int64(8), None, ctypes.c_size_t(0), None)
+    assert rc == ds.DS_EINVAL          # slice larger than the stored weight
+    assert lib.ds_sliced_mhsa(None, 2, 300, 64, None, None, None, None, 2, 64, ctypes.byref(g), None, None, None,
+                              ctypes.c_size_t(0), None) == ds.DS_EUNSUPPORTED
+    assert lib.ds_sliced_linear_workspace(64, 197, 4) >= 16 + 8 * (64 * 197 // 128 + 4)
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    import importlib
+    old = ds._lib
+    ds._lib = None
+    try:
+        with pytest.raises(RuntimeError, match="no fallback"):
+            ds.load(str(tmp_path / "nope.so"))
+    finally:
+        ds._lib = old

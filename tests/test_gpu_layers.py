@@ -1,0 +1,304 @@
+"""GPU parity of every C-ABI layer call against the CPU oracle on the same seeded inputs.
+
+Tolerances (max |gpu - oracle| / max |oracle| per output tensor): 1e-5 for fp32,
+2e-2 for bf16 inputs with fp32 accumulation; integer outputs are bit-exact, routes
+are exempt only where the oracle's top-2 scores are closer than 1e-6.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import ds_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32, TOL_BF16 = 1e-5, 2e-2
+DEV = "cuda:0"
+
+
+def dev(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV).to(dtype).contiguous()
+
+
+def relerr(got, want):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape
+    return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30))
+
+
+def host(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+# ------------------------------------------------------------------ route bucket
+@pytest.mark.parametrize("B,T,seed", [(0, 4, 0), (1, 1, 1), (7, 3, 2), (64, 4, 3), (256, 14, 4), (256, 48, 5),
+                                      (256, 16, 6), (3000, 64, 7), (2049, 1024, 8)])
+def test_route_bucket_bit_exact(gpu_lib, B, T, seed):
+    rng = np.random.default_rng(seed)
+    route = rng.integers(0, T, B).astype(np.int32)
+    if B > 10:
+        route[route == 1 % T] = 0          # force an empty bucket
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    operm, oinv, ooff = O.route_bucket(route, T)
+    assert np.array_equal(perm.cpu().numpy(), operm)
+    assert np.array_equal(inv.cpu().numpy(), oinv)
+    assert np.array_equal(off.cpu().numpy(), ooff)
+
+
+def test_route_bucket_flags_out_of_range_ids(gpu_lib):
+    route = np.array([0, 5, 1, -1, 1], np.int32)
+    _, _, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), 2)
+    assert off.cpu().numpy().tolist() == [0, 1, 3]      # offsets[T] = 3 valid ids != B
+
+
+# ------------------------------------------------------------------ gate
+def _check_routes(route_gpu, logits_oracle):
+    for b, z in enumerate(logits_oracle):
+        if O.gate_margin(z) >= 1e-6:
+            assert int(route_gpu[b]) == O.gate_route(z), (b, z)
+
+
+def test_gate_config1_fp32_nchw(gpu_lib):
+    c = WL.config1()
+    x = dev(c["x"])
+    logits, route = gpu_lib.ds_gate(x, gpu_lib.DS_NCHW, dev(c["gate.w1"]), dev(c["gate.b1"]), dev(c["gate.w2"]),
+                                    dev(c["gate.b2"]), c["T"])
+    want = np.stack([O.gate_logits(O.gate_encoder(c["x"][b]), c["gate.w1"], c["gate.b1"], c["gate.w2"], c["gate.b2"])
+                     for b in range(c["B"])])
+    assert relerr(host(logits), want) < TOL_F32
+    _check_routes(route.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("C,HW,hid,T,B", [(256, 784, 64, 14, 33), (64, 3136, 16, 4, 9), (1024, 196, 256, 4, 17)])
+def test_gate_bf16_nhwc_with_sliced_input_and_bias(gpu_lib, C, HW, hid, T, B):
+    d = WL.nets.Draw(100 + C)
+    x = WL.nets.as_bf16_values(d.normal((B, HW, C)))
+    w1, b1 = d.normal((hid, C), std=C ** -0.5), d.normal((hid,), std=0.1)
+    w2, b2 = d.normal((T, hid), std=hid ** -0.5), d.normal((T,), std=0.1)
+    lb = WL.seeded_logit_bias(7, B, T)
+    c_in = (8 * d.randint(B, C // 8) + 8).astype(np.int32)
+    logits, route = gpu_lib.ds_gate(dev(x, torch.bfloat16), gpu_lib.DS_NHWC, dev(w1), dev(b1), dev(w2), dev(b2), T,
+                                    logit_bias=dev(lb), c_in=dev(c_in, torch.int32))
+    want = np.stack([O.gate_logits(O.gate_encoder(x[b].T[:c_in[b]].reshape(c_in[b], HW, 1)), w1, b1, w2, b2, lb[b])
+                     for b in range(B)])
+    assert relerr(host(logits), want) < TOL_F32
+    _check_routes(route.cpu().numpy(), want)
+
+
+def test_gate_argmax_only_ties_and_nan(gpu_lib):
+    lb = np.array([[0.1, 0.7, 0.3], [0.7, 0.7, 0.3], [0.1, 0.7, 0.7], [np.nan, 0.2, 0.1], [np.nan] * 3], np.float32)
+    logits, route = gpu_lib.ds_gate(None, 0, None, None, None, None, 3, logit_bias=dev(lb))
+    assert route.cpu().numpy().tolist() == [O.gate_route(z) for z in lb] == [1, 0, 1, 1, 0]
+    assert np.array_equal(logits.cpu().numpy(), lb, equal_nan=True)
+
+
+# ------------------------------------------------------------------ sliced linear (config 2)
+def _linear_case(gpu_lib, c, y_dtype, act=0, with_res=False):
+    B, N, K = c["B"], c["N"], c["K"]
+    route = dev(c["route"], torch.int32)
+    perm, inv, off = gpu_lib.ds_route_bucket(route, c["T"])
+    g = gpu_lib.make_groups(off, perm, c["k_in"], c["k_out"])
+    x, w, bias = dev(c["x"], torch.bfloat16), dev(c["w"], torch.bfloat16), dev(c["bias"])
+    y = torch.full((B, N, 4 * K), float("nan"), dtype=y_dtype, device=DEV)
+    res = None
+    if with_res:
+        res_h = WL.nets.as_bf16_values(WL.nets.Draw(9).normal((B, N, 4 * K)))
+        res = dev(res_h, torch.bfloat16)
+    gpu_lib.ds_sliced_linear(x, w, bias, g, act=act, residual=res, y=y)
+    yh = host(y)
+    worst = 0.0
+    for b in range(B):
+        ki, ko = int(c["k_in"][c["route"][b]]), int(c["k_out"][c["route"][b]])
+        want = O.sliced_linear(c["x"][b, :, :ki], c["w"], c["bias"], ko)
+        if with_res:
+            want = want + res_h[b, :, :ko]
+        if act == 2:
+            want = O.gelu(want)
+        if y_dtype == torch.bfloat16:
+            want = O.bf16_round(want)
+        assert np.all(np.isnan(yh[b, :, ko:])), "tail beyond the valid slice was written"
+        worst = max(worst, relerr(yh[b, :, :ko], want))
+    return worst
+
+
+@pytest.mark.parametrize("balanced", [False, True])
+@pytest.mark.parametrize("y_dtype", [torch.bfloat16, torch.float32])
+def test_sliced_linear_config2(gpu_lib, balanced, y_dtype):
+    c = WL.config2(balanced=balanced)
+    assert _linear_case(gpu_lib, c, y_dtype) < (TOL_BF16 if y_dtype == torch.bfloat16 else 1e-4)
+
+
+def test_sliced_linear_gelu_residual_ragged_small(gpu_lib):
+    c = WL.config2(seed=77, B=5, N=37, K=48)          # k_in 24..48: K tails inside a 32-wide slab
+    assert _linear_case(gpu_lib, c, torch.bfloat16, act=2) < TOL_BF16
+    assert _linear_case(gpu_lib, c, torch.bfloat16, with_res=True) < TOL_BF16
+    c = WL.config2(seed=78, B=3, N=1, K=96)
+    assert _linear_case(gpu_lib, c, torch.float32) < 1e-4
+
+
+def test_sliced_linear_one_bucket_gets_everything_and_empty_batch(gpu_lib):
+    c = WL.config2(seed=79, B=6, N=50, K=48)
+    c["route"][:] = 2
+    assert _linear_case(gpu_lib, c, torch.bfloat16) < TOL_BF16
+    off = torch.zeros(5, dtype=torch.int32, device=DEV)
+    g = gpu_lib.make_groups(off, None, c["k_in"], c["k_out"])
+    x0 = torch.zeros((0, 50, 48), dtype=torch.bfloat16, device=DEV)
+    y0 = gpu_lib.ds_sliced_linear(x0, dev(c["w"], torch.bfloat16), None, g)
+    assert y0.shape[0] == 0
+
+
+# ------------------------------------------------------------------ config 1: gate + sliced conv + split BN + ReLU, fp32
+def _config1_block(gpu_lib, c, forced=None):
+    B, T = c["B"], c["T"]
+    x = dev(c["x"])
+    if forced is None:
+        _, route = gpu_lib.ds_gate(x, gpu_lib.DS_NCHW, dev(c["gate.w1"]), dev(c["gate.b1"]), dev(c["gate.w2"]),
+                                   dev(c["gate.b2"]), T)
+    else:
+        route = dev(np.asarray(forced, np.int32), torch.int32)
+    perm, inv, off = gpu_lib.ds_route_bucket(route, T)
+    bn = c["bn"]
+    scale, shift = gpu_lib.ds_bn_fold(dev(bn["gamma"]), dev(bn["beta"]), dev(bn["mean"]), dev(bn["var"]), c["bn_eps"])
+    g = gpu_lib.make_groups(off, perm, [c["C"]] * T, c["c_out"])
+    y = torch.full((B, c["C"], c["H"], c["W"]), float("nan"), device=DEV)
+    gpu_lib.ds_sliced_conv(x, dev(c["conv.w"]), scale, shift, g, c["stride"], c["pad"], act=gpu_lib.DS_ACT_RELU, y=y)
+    return route.cpu().numpy(), host(y)
+
+
+def _config1_oracle(c, b, t):
+    co = int(c["c_out"][t])
+    y = O.sliced_conv2d(c["x"][b], c["conv.w"], co, c["stride"], c["pad"])
+    return O.relu(O.re_sbn(y, c["bn"], t, c["bn_eps"]))
+
+
+def test_config1_free_running_block(gpu_lib):
+    c = WL.config1()
+    route, y = _config1_block(gpu_lib, c)
+    z = [O.gate_logits(O.gate_encoder(c["x"][b]), c["gate.w1"], c["gate.b1"], c["gate.w2"], c["gate.b2"])
+         for b in range(c["B"])]
+    _check_routes(route, z)
+    for b in range(c["B"]):
+        t = int(route[b])
+        co = int(c["c_out"][t])
+        assert relerr(y[b, :co], _config1_oracle(c, b, t)) < TOL_F32
+        assert np.all(np.isnan(y[b, co:]))
+
+
+def test_config1_forced_routes_cover_all_ratios(gpu_lib):
+    c = WL.config1()
+    forced = [0, 1, 2, 3, 3, 2, 1, 0]
+    _, y = _config1_block(gpu_lib, c, forced)
+    for b, t in enumerate(forced):
+        co = int(c["c_out"][t])
+        assert relerr(y[b, :co], _config1_oracle(c, b, t)) < TOL_F32
+        assert np.all(np.isnan(y[b, co:]))
+
+
+# ------------------------------------------------------------------ bf16 NHWC conv (implicit GEMM)
+@pytest.mark.parametrize("K,stride,pad,H,CI,CO,res", [(3, 1, 1, 14, 64, 64, False), (3, 2, 1, 15, 48, 80, False),
+                                                       (1, 1, 0, 9, 96, 40, True), (1, 2, 0, 14, 64, 128, False),
+                                                       (3, 1, 1, 7, 136, 24, True)])
+def test_sliced_conv_bf16_nhwc(gpu_lib, K, stride, pad, H, CI, CO, res):
+    B, T = 11, 4
+    d = WL.nets.Draw(1000 + K * 10 + stride + CI)
+    x = WL.nets.as_bf16_values(d.normal((B, CI, H, H)))
+    w = WL.nets.as_bf16_values(d.normal((CO, CI, K, K), std=(2.0 / (CI * K * K)) ** 0.5))
+    bn = WL.bn_tables(d, T, CO)
+    route = d.randint(B, T)
+    c_in = [CI * q // 4 // 8 * 8 for q in (1, 2, 3, 4)]
+    c_out = [max(8, CO * q // 4 // 8 * 8) for q in (1, 2, 3, 4)]
+    Ho = (H + 2 * pad - K) // stride + 1
+    resid = WL.nets.as_bf16_values(d.normal((B, CO, Ho, Ho))) if res else None
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    scale, shift = gpu_lib.ds_bn_fold(dev(bn["gamma"]), dev(bn["beta"]), dev(bn["mean"]), dev(bn["var"]), 1e-5)
+    g = gpu_lib.make_groups(off, perm, c_in, c_out)
+    xg = dev(x.transpose(0, 2, 3, 1), torch.bfloat16)
+    wg = dev(w.transpose(0, 2, 3, 1), torch.bfloat16)
+    rg = dev(resid.transpose(0, 2, 3, 1), torch.bfloat16) if res else None
+    y = torch.full((B, Ho, Ho, CO), float("nan"), dtype=torch.bfloat16, device=DEV)
+    gpu_lib.ds_sliced_conv(xg, wg, scale, shift, g, stride, pad, act=gpu_lib.DS_ACT_RELU, residual=rg, y=y)
+    yh = host(y).transpose(0, 3, 1, 2)
+    for b in range(B):
+        t = int(route[b])
+        ci, co = c_in[t], c_out[t]
+        want = O.re_sbn(O.sliced_conv2d(x[b, :ci], w, co, stride, pad), bn, t, 1e-5)
+        if res:
+            want = want + resid[b, :co]
+        want = O.bf16_round(O.relu(want))
+        assert relerr(yh[b, :co], want) < TOL_BF16
+        assert np.all(np.isnan(yh[b, co:]))
+
+
+# ------------------------------------------------------------------ depthwise conv
+@pytest.mark.parametrize("stride,H,C", [(1, 14, 64), (2, 14, 96), (2, 7, 40), (1, 9, 264)])
+def test_sliced_dwconv(gpu_lib, stride, H, C):
+    B, T = 9, 5
+    d = WL.nets.Draw(2000 + stride + C)
+    x = WL.nets.as_bf16_values(d.normal((B, C, H, H)))
+    w = WL.nets.as_bf16_values(d.normal((C, 1, 3, 3), std=0.5))
+    bn = WL.bn_tables(d, T, C)
+    route = d.randint(B, T)
+    cs = [max(8, C * q // 5 // 8 * 8) for q in (1, 2, 3, 4, 5)]
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    scale, shift = gpu_lib.ds_bn_fold(dev(bn["gamma"]), dev(bn["beta"]), dev(bn["mean"]), dev(bn["var"]), 1e-5)
+    g = gpu_lib.make_groups(off, perm, cs)
+    Ho = (H - 1) // stride + 1
+    y = torch.full((B, Ho, Ho, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+    gpu_lib.ds_sliced_dwconv(dev(x.transpose(0, 2, 3, 1), torch.bfloat16), dev(w[:, 0].transpose(1, 2, 0), torch.bfloat16),
+                             scale, shift, g, stride, y=y)
+    yh = host(y).transpose(0, 3, 1, 2)
+    for b in range(B):
+        t = int(route[b])
+        c = cs[t]
+        want = O.bf16_round(O.relu(O.re_sbn(O.sliced_dwconv2d(x[b, :c], w, stride, 1), bn, t, 1e-5)))
+        assert relerr(yh[b, :c], want) < TOL_BF16
+        assert np.all(np.isnan(yh[b, c:]))
+
+
+# ------------------------------------------------------------------ LayerNorm
+def test_sliced_layernorm(gpu_lib):
+    B, N, D, T = 13, 29, 384, 4
+    d = WL.nets.Draw(3000)
+    x = WL.nets.as_bf16_values(d.normal((B, N, D), std=2.0, mean=0.5))
+    gm, bt = 1.0 + d.normal((D,), std=0.1), d.normal((D,), std=0.1)
+    route = d.randint(B, T)
+    ks = [192, 256, 320, 384]
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    g = gpu_lib.make_groups(off, perm, ks)
+    y = torch.full((B, N, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    gpu_lib.ds_sliced_layernorm(dev(x, torch.bfloat16), dev(gm), dev(bt), 1e-6, g, y=y)
+    yh = host(y)
+    for b in range(B):
+        k = ks[route[b]]
+        want = O.bf16_round(O.layernorm_sliced(x[b, :, :k], gm, bt, 1e-6))
+        assert relerr(yh[b, :, :k], want) < TOL_BF16
+        assert np.all(np.isnan(yh[b, :, k:]))
+
+
+# ------------------------------------------------------------------ MHSA
+@pytest.mark.parametrize("N,B", [(197, 10), (17, 7), (64, 5)])
+def test_sliced_mhsa(gpu_lib, N, B):
+    D, H, dh = 384, 6, 64
+    d = WL.nets.Draw(4000 + N)
+    bf = WL.nets.as_bf16_values
+    x = bf(d.normal((B, N, D)))
+    wq, wk, wv = (bf(d.normal((H * dh, D), std=0.06)) for _ in range(3))
+    bq, bk, bv = (d.normal((H * dh,), std=0.1) for _ in range(3))
+    wp, bp = bf(d.normal((D, H * dh), std=0.05)), d.normal((D,), std=0.1)
+    routes = [(192, 3), (256, 4), (320, 5), (384, 6), (192, 6), (384, 3)]
+    route = d.randint(B, len(routes))
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), len(routes))
+    g = gpu_lib.make_groups(off, perm, [r[0] for r in routes], [r[1] * dh for r in routes])
+    y = torch.full((B, N, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    xg = dev(x, torch.bfloat16)
+    gpu_lib.ds_sliced_mhsa(xg, dev(np.stack([wq, wk, wv]), torch.bfloat16), dev(np.stack([bq, bk, bv])),
+                           dev(wp, torch.bfloat16), dev(bp), H, dh, g, residual=xg, y=y)
+    yh = host(y)
+    for b in range(B):
+        de, h = routes[route[b]]
+        att = O.sliced_mhsa(x[b, :, :de], wq, bq, wk, bk, wv, bv, wp, bp, h, dh, store="bf16")
+        want = O.bf16_round(x[b, :, :de] + att)
+        assert relerr(yh[b, :, :de], want) < TOL_BF16
+        assert np.all(np.isnan(yh[b, :, de:]))
