@@ -152,3 +152,8 @@ int32_t ds_launch_lookup(const int32_t* idx, const GroupTable& gt, int32_t which
 int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* o, int64_t sample_stride,
                             int32_t ld, int32_t o_ld, int64_t o_sample_stride, const int32_t* slot_group,
                             const GroupTable& gt, int32_t B, int32_t N, int32_t H, hipStream_t s);
+
+// ---- small index helpers ---------------------------------------------------------
+int32_t ds_launch_set_offsets(int32_t* offsets, int32_t B, hipStream_t s);  // offsets[0..1] = {0, B}
+// key[b] = hi[b] * mul + (lo ? lo[b] : 0)
+int32_t ds_launch_make_key(const int32_t* hi, const int32_t* lo, int32_t mul, int32_t* key, int32_t B, hipStream_t s);

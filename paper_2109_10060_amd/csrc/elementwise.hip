@@ -347,7 +347,29 @@ __global__ void lookup_kernel(const int32_t* idx, const GroupTable gt, int which
     out[j] = which == 0 ? gt.k_in[g] : (which == 1 ? gt.k_out[g] : gt.row[g]);
 }
 
+__global__ void set_offsets_kernel(int32_t* offsets, int B) {
+    if (threadIdx.x == 0) { offsets[0] = 0; offsets[1] = B; }
+}
+
+__global__ void make_key_kernel(const int32_t* hi, const int32_t* lo, int mul, int32_t* key, int B) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < B) key[j] = hi[j] * mul + (lo ? lo[j] : 0);
+}
+
 }  // namespace
+
+int32_t ds_launch_set_offsets(int32_t* offsets, int32_t B, hipStream_t s) {
+    hipLaunchKernelGGL(set_offsets_kernel, dim3(1), dim3(64), 0, s, offsets, B);
+    DS_CHECK_LAUNCH("set offsets");
+    return DS_OK;
+}
+
+int32_t ds_launch_make_key(const int32_t* hi, const int32_t* lo, int32_t mul, int32_t* key, int32_t B, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    hipLaunchKernelGGL(make_key_kernel, dim3((B + 255) / 256), dim3(256), 0, s, hi, lo, mul, key, B);
+    DS_CHECK_LAUNCH("make key");
+    return DS_OK;
+}
 
 int32_t ds_launch_expand_groups(const int32_t* offsets, int32_t T, int32_t* slot_group, hipStream_t s) {
     hipLaunchKernelGGL(expand_groups_kernel, dim3(1), dim3(256), 0, s, offsets, T, slot_group);

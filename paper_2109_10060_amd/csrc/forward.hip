@@ -1,10 +1,621 @@
-// Whole-network forward passes (placeholder until the assemblies land).
+// Whole-network forward passes of the three dynamic nets (Section 5.2):
+// DS-MBNet (one gate after the 5th depthwise-separable block), DS-ResNet (a gate in
+// the first block of each of the four stages, projection shortcut sliced with it)
+// and DS-ViT (one route per image chosen before the patch embedding).
+//
+// Host code only enqueues kernels.  Route decisions never leave the device: the
+// gate writes route ids, the bucket kernel turns them into slot order, group
+// offsets and per-slot group ids, and every later launch is sized for the worst
+// case and reads those tables.
+//
+// Activation layout after a gate: slot-major.  Slot j (bucket order) owns a block
+// of fixed size rows * C_stored elements; inside it the rows are packed with the
+// slot's own width as leading stride, so a bucket's rows are dense and only valid
+// bytes are touched.  The first sliced layer gathers whole samples through the
+// permutation; the classifier scatters logits back to the original order.
+#include <string.h>
+
 #include "common.h"
 
-extern "C" size_t ds_forward_workspace(const ds_net* net, int32_t B) { (void)net; (void)B; return 0; }
+namespace {
+
+struct Bump {
+    char* base;
+    size_t off;
+    template <typename T>
+    T* take(size_t n) {
+        off = ds_align_up(off, 256);
+        T* p = base ? (T*)(base + off) : nullptr;
+        off += n * sizeof(T);
+        return p;
+    }
+};
+
+GroupTable table1(int k_in, int k_out) {
+    GroupTable g;
+    memset(&g, 0, sizeof(g));
+    g.T = 1;
+    g.k_in[0] = k_in;
+    g.k_out[0] = k_out;
+    g.row[0] = 0;
+    return g;
+}
+
+int max_out(const GroupTable& g) {
+    int m = 0;
+    for (int t = 0; t < g.T; ++t) m = g.k_out[t] > m ? g.k_out[t] : m;
+    return m;
+}
+
+struct MList {  // m-tile list of one (bucketing, rows-per-sample) pair
+    void* list;
+    int cap;
+    int rows;
+};
+
+#define RC(x)                  \
+    do {                       \
+        int32_t rc__ = (x);    \
+        if (rc__) return rc__; \
+    } while (0)
+
+// pointwise / KxK convolution through the grouped GEMM
+int32_t conv_gemm(const bf16_t* A, const int32_t* a_index, int64_t a_sstride, int a_ld, const bf16_t* Wt, int C_I_full,
+                  int K, int stride, int pad, int H, int W, const float* scale, const float* shift, int tab_ld,
+                  const bf16_t* R, bf16_t* C, int64_t c_sstride, int c_ld, const int32_t* offsets, const MList& ml,
+                  const GroupTable& gt, int act, hipStream_t s) {
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    const int Ho = (H + 2 * pad - K) / stride + 1, Wo = (W + 2 * pad - K) / stride + 1;
+    a.A = A; a.Wt = Wt; a.C = C; a.R = R;
+    a.scale = scale; a.shift = shift; a.tab_ld = tab_ld;
+    a.a_index = a_index; a.c_index = nullptr;
+    a.a_sample_stride = a_sstride; a.c_sample_stride = c_sstride; a.r_sample_stride = c_sstride;
+    a.a_ld = a_ld; a.c_ld = c_ld; a.r_ld = c_ld; a.r_use_index = 1;
+    a.w_ld = (int64_t)K * K * C_I_full; a.w_tap_stride = C_I_full; a.n_seg = 1;
+    a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.K = K; a.stride = stride; a.pad = pad; a.rows = Ho * Wo;
+    a.offsets = offsets; a.mtiles = ds_mtile_entries(ml.list); a.n_mtiles = ds_mtile_count(ml.list);
+    a.act = act; a.out_f32 = 0; a.gt = gt;
+    return ds_launch_gemm(a, ml.cap, max_out(gt), s);
+}
+
+// =====================================================================================
+// DS-MBNet
+//  ints:   image, stem_out, n_blocks, gate_after, gate_hidden, T, num_classes,
+//          n_blocks x (C_in, C_out, stride), cin[T][n_blocks], cout[T][n_blocks]
+//  params: stem.w [27][stem_out] bf16, stem.scale, stem.shift,
+//          per block: dw.w [3][3][C_in] bf16, dw.scale, dw.shift [Tb][C_in], pw.w [C_out][C_in] bf16,
+//                     pw.scale, pw.shift [Tb][C_out]   (Tb = 1 before the gate, T after),
+//          gate.w1, gate.b1, gate.w2, gate.b2, fc.w [classes][C_last] bf16, fc.b
+// =====================================================================================
+struct MbDesc {
+    int image, stem_out, nb, gate_after, gate_hidden, T, classes;
+    const int32_t *blk, *cin, *cout;
+};
+
+bool parse_mb(const ds_net* net, MbDesc* d) {
+    if (net->n_ints < 7) return false;
+    const int32_t* v = net->ints;
+    d->image = v[0]; d->stem_out = v[1]; d->nb = v[2]; d->gate_after = v[3]; d->gate_hidden = v[4]; d->T = v[5];
+    d->classes = v[6];
+    if (d->nb < 1 || d->nb > 64 || d->T < 1 || d->T > DS_MAX_GROUPS) return false;
+    if (net->n_ints != 7 + 3 * d->nb + 2 * d->T * d->nb) return false;
+    if (net->n_params != 3 + 6 * d->nb + 6) return false;
+    d->blk = v + 7;
+    d->cin = d->blk + 3 * d->nb;
+    d->cout = d->cin + d->T * d->nb;
+    return d->gate_after >= 1 && d->gate_after < d->nb;
+}
+
+struct MbPlan {
+    bf16_t *bufA, *bufB;
+    float *gate_logits, *gate_partial;
+    int32_t *off1, *offs, *perm, *inv, *slot_group, *route;
+    void* lists[8];
+    int n_lists;
+};
+
+void plan_mb(const MbDesc& d, int B, Bump& bp, MbPlan* p) {
+    const int r1 = (d.image + 2 - 3) / 2 + 1;
+    size_t maxel = (size_t)r1 * r1 * d.stem_out;
+    int r = r1;
+    for (int i = 0; i < d.nb; ++i) {
+        const int ci = d.blk[3 * i], co = d.blk[3 * i + 1], st = d.blk[3 * i + 2];
+        r = (r + 2 - 3) / st + 1;
+        maxel = maxel > (size_t)r * r * ci ? maxel : (size_t)r * r * ci;
+        maxel = maxel > (size_t)r * r * co ? maxel : (size_t)r * r * co;
+    }
+    p->bufA = bp.take<bf16_t>(maxel * B);
+    p->bufB = bp.take<bf16_t>(maxel * B);
+    const int cg = d.blk[3 * (d.gate_after - 1) + 1];
+    p->gate_logits = bp.take<float>((size_t)B * d.T);
+    p->gate_partial = bp.take<float>(ds_gate_partial_bytes(B, cg) / sizeof(float));
+    p->off1 = bp.take<int32_t>(2);
+    p->offs = bp.take<int32_t>(d.T + 1);
+    p->perm = bp.take<int32_t>(B);
+    p->inv = bp.take<int32_t>(B);
+    p->slot_group = bp.take<int32_t>(B);
+    p->route = bp.take<int32_t>(B);
+    // one m-tile list per distinct (bucketing, resolution)
+    p->n_lists = 0;
+    r = r1;
+    int last_rows = -1, last_phase = -1;
+    for (int i = 0; i < d.nb; ++i) {
+        r = (r + 2 - 3) / d.blk[3 * i + 2] + 1;
+        const int phase = i >= d.gate_after;
+        if (r * r != last_rows || phase != last_phase) {
+            p->lists[p->n_lists++] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, phase ? d.T : 1) * 8);
+            last_rows = r * r;
+            last_phase = phase;
+        }
+    }
+}
+
+int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int B, const int32_t* route_override,
+                   const float* logit_bias, float* logits, int32_t* routes_out, const MbPlan& p, hipStream_t s) {
+    const void* const* P = net->params;
+    int r = (d.image + 2 - 3) / 2 + 1;
+    RC(ds_launch_set_offsets(p.off1, B, s));
+    RC(ds_launch_stem(images, nullptr, p.bufA, (const bf16_t*)P[0], (const float*)P[1], (const float*)P[2], B, d.image,
+                      d.image, 3, 2, 1, d.stem_out, s));
+    bf16_t *cur = p.bufA, *oth = p.bufB;
+    int li = -1, last_rows = -1, last_phase = -1;
+    MList ml = {nullptr, 0, 0};
+    for (int i = 0; i < d.nb; ++i) {
+        const int ci = d.blk[3 * i], co = d.blk[3 * i + 1], st = d.blk[3 * i + 2];
+        const void* const* Q = P + 3 + 6 * i;
+        const int phase = i >= d.gate_after;
+        const int rin = r;
+        r = (r + 2 - 3) / st + 1;
+        if (i == d.gate_after) {
+            GateArgs g;
+            memset(&g, 0, sizeof(g));
+            const void* const* G = P + 3 + 6 * d.nb;
+            g.x = cur; g.dtype = DS_BF16; g.layout = DS_NHWC; g.B = B; g.C = ci; g.HW = rin * rin;
+            g.x_sample_stride = (int64_t)rin * rin * ci; g.x_ld = ci;
+            g.w1 = (const float*)G[0]; g.b1 = (const float*)G[1]; g.w2 = (const float*)G[2]; g.b2 = (const float*)G[3];
+            g.C_mlp = d.gate_hidden; g.T = d.T; g.logit_bias = logit_bias; g.route_override = route_override;
+            g.logits = p.gate_logits; g.route = routes_out ? routes_out : p.route; g.partial = p.gate_partial;
+            RC(ds_launch_gate(g, s));
+            RC(ds_launch_bucket(g.route, B, d.T, p.perm, p.inv, p.offs, p.slot_group, s));
+        }
+        GroupTable gdw, gpw;
+        memset(&gdw, 0, sizeof(gdw));
+        if (!phase) {
+            gdw = table1(ci, ci);
+            gpw = table1(ci, co);
+        } else {
+            gdw.T = d.T;
+            for (int t = 0; t < d.T; ++t) {
+                gdw.k_in[t] = gdw.k_out[t] = d.cin[t * d.nb + i];
+                gdw.row[t] = t;
+            }
+            gpw = gdw;
+            for (int t = 0; t < d.T; ++t) gpw.k_out[t] = d.cout[t * d.nb + i];
+        }
+        const int32_t* offsets = phase ? p.offs : p.off1;
+        if (r * r != last_rows || phase != last_phase) {
+            ++li;
+            ml.list = p.lists[li];
+            ml.cap = (int)ds_mtile_capacity(B, r * r, phase ? d.T : 1);
+            ml.rows = r * r;
+            RC(ds_build_mtiles(offsets, phase ? d.T : 1, r * r, ml.list, s));
+            last_rows = r * r;
+            last_phase = phase;
+        }
+        // depthwise: the first sliced block reads the fixed-width, original-order feature map through perm
+        const bool first = (i == d.gate_after);
+        ActView xv = {cur, first ? p.perm : nullptr, (int64_t)rin * rin * ci, (!phase || first) ? ci : 0};
+        ActView yv = {oth, nullptr, (int64_t)r * r * ci, phase ? 0 : ci};
+        RC(ds_launch_dwconv(xv, yv, (const bf16_t*)Q[0], (const float*)Q[1], (const float*)Q[2], ci,
+                            phase ? p.slot_group : nullptr, gdw, B, ci, rin, rin, st, DS_ACT_RELU, s));
+        // pointwise
+        RC(conv_gemm(oth, nullptr, (int64_t)r * r * ci, phase ? 0 : ci, (const bf16_t*)Q[3], ci, 1, 1, 0, r, r,
+                     (const float*)Q[4], (const float*)Q[5], co, nullptr, cur, (int64_t)r * r * co, phase ? 0 : co,
+                     offsets, ml, gpw, DS_ACT_RELU, s));
+    }
+    const void* const* F = P + 3 + 6 * d.nb + 4;
+    const int cl = d.blk[3 * (d.nb - 1) + 1];
+    GroupTable gh;
+    memset(&gh, 0, sizeof(gh));
+    gh.T = d.T;
+    for (int t = 0; t < d.T; ++t) gh.k_in[t] = gh.k_out[t] = d.cout[t * d.nb + d.nb - 1];
+    ActView xv = {cur, nullptr, (int64_t)r * r * cl, 0};
+    return ds_launch_head(xv, r * r, (const bf16_t*)F[0], cl, (const float*)F[1], d.classes, p.slot_group, gh, p.perm,
+                          logits, B, cl, s);
+}
+
+// =====================================================================================
+// DS-ResNet
+//  ints:   image, stem_out, T, num_classes, widths[4], blocks[4], gate_hidden[4], mid[4][T], out[4][T]
+//  params: stem.w [147][stem_out] bf16, stem.scale, stem.shift,
+//          per stage: gate.w1, gate.b1, gate.w2, gate.b2, then per block:
+//             c1.w [w][C_in] bf16, c1.scale, c1.shift [T][w], c2.w [w][3][3][w] bf16, c2.scale, c2.shift,
+//             c3.w [4w][w] bf16, c3.scale, c3.shift [T][4w], and for the first block
+//             proj.w [4w][C_in] bf16, proj.scale, proj.shift,
+//          fc.w [classes][4*w_last] bf16, fc.b
+// =====================================================================================
+struct RnDesc {
+    int image, stem_out, T, classes;
+    const int32_t *widths, *blocks, *hidden, *mid, *out;
+};
+
+bool parse_rn(const ds_net* net, RnDesc* d) {
+    if (net->n_ints < 4) return false;
+    const int32_t* v = net->ints;
+    d->image = v[0]; d->stem_out = v[1]; d->T = v[2]; d->classes = v[3];
+    if (d->T < 1 || d->T * d->T > DS_MAX_GROUPS) return false;
+    if (net->n_ints != 4 + 12 + 8 * d->T) return false;
+    d->widths = v + 4; d->blocks = v + 8; d->hidden = v + 12; d->mid = v + 16; d->out = d->mid + 4 * d->T;
+    int np = 3 + 2;
+    for (int s = 0; s < 4; ++s) np += 4 + 9 * d->blocks[s] + 3;
+    return net->n_params == np;
+}
+
+struct RnPlan {
+    bf16_t* buf[5];
+    float *gate_logits, *gate_partial;
+    int32_t *off1, *offs[4], *perm[4], *inv[4], *slot_group[4], *route[4], *key, *src_index, *slot_c;
+    void* lists[8];
+};
+
+void plan_rn(const RnDesc& d, int B, Bump& bp, RnPlan* p) {
+    const int r1 = (d.image + 6 - 7) / 2 + 1, r2 = (r1 + 2 - 3) / 2 + 1;
+    size_t maxel = (size_t)r1 * r1 * d.stem_out;
+    int r = r2;
+    for (int s = 0; s < 4; ++s) {
+        const size_t in_res = (size_t)r * r;
+        if (s > 0) r = (r + 2 - 3) / 2 + 1;
+        const size_t e1 = in_res * d.widths[s], e2 = (size_t)r * r * 4 * d.widths[s];
+        maxel = maxel > e1 ? maxel : e1;
+        maxel = maxel > e2 ? maxel : e2;
+    }
+    for (int i = 0; i < 5; ++i) p->buf[i] = bp.take<bf16_t>(maxel * B);
+    int cmax = d.stem_out;
+    for (int s = 0; s < 3; ++s) cmax = cmax > 4 * d.widths[s] ? cmax : 4 * d.widths[s];
+    p->gate_logits = bp.take<float>((size_t)B * d.T);
+    p->gate_partial = bp.take<float>(ds_gate_partial_bytes(B, cmax) / sizeof(float));
+    p->off1 = bp.take<int32_t>(2);
+    for (int s = 0; s < 4; ++s) {
+        p->offs[s] = bp.take<int32_t>(d.T * d.T + 1);
+        p->perm[s] = bp.take<int32_t>(B);
+        p->inv[s] = bp.take<int32_t>(B);
+        p->slot_group[s] = bp.take<int32_t>(B);
+        p->route[s] = bp.take<int32_t>(B);
+    }
+    p->key = bp.take<int32_t>(B);
+    p->src_index = bp.take<int32_t>(B);
+    p->slot_c = bp.take<int32_t>(B);
+    r = r2;
+    for (int s = 0; s < 4; ++s) {
+        p->lists[2 * s] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 8);  // input resolution
+        if (s > 0) r = (r + 2 - 3) / 2 + 1;
+        p->lists[2 * s + 1] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 8);  // output resolution
+    }
+}
+
+int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int B, const int32_t* route_override,
+                   const float* logit_bias, float* logits, int32_t* routes_out, const RnPlan& p, hipStream_t s) {
+    const void* const* P = net->params;
+    const int T = d.T, G = T * T;
+    const int r1 = (d.image + 6 - 7) / 2 + 1;
+    int r = (r1 + 2 - 3) / 2 + 1;
+    RC(ds_launch_stem(images, nullptr, p.buf[0], (const bf16_t*)P[0], (const float*)P[1], (const float*)P[2], B, d.image,
+                      d.image, 7, 2, 3, d.stem_out, s));
+    RC(ds_launch_maxpool(p.buf[0], p.buf[1], B, r1, r1, d.stem_out, s));
+    bf16_t* X = p.buf[1];          // stage input, slot order of the previous stage
+    int xi = 1;                    // index of X in buf[]
+    int c_prev_full = d.stem_out;
+    const void* const* Q = P + 3;
+    for (int st = 0; st < 4; ++st) {
+        const int w = d.widths[st], nb = d.blocks[st];
+        const int rin = r;
+        const int stride = st > 0 ? 2 : 1;
+        const int rout = (rin + 2 - 3) / stride + 1;
+        int32_t* route = routes_out ? routes_out + (size_t)st * B : p.route[st];
+        // ---- gate on the stage input (previous slot order), routes land in original sample order
+        GateArgs g;
+        memset(&g, 0, sizeof(g));
+        g.x = X; g.dtype = DS_BF16; g.layout = DS_NHWC; g.B = B; g.C = c_prev_full; g.HW = rin * rin;
+        g.c_in = st > 0 ? p.slot_c : nullptr;
+        g.x_sample_stride = (int64_t)rin * rin * c_prev_full; g.x_ld = 0;
+        g.w1 = (const float*)Q[0]; g.b1 = (const float*)Q[1]; g.w2 = (const float*)Q[2]; g.b2 = (const float*)Q[3];
+        g.C_mlp = d.hidden[st]; g.T = T;
+        g.logit_bias = logit_bias ? logit_bias + (size_t)st * B * T : nullptr;
+        g.out_index = st > 0 ? p.perm[st - 1] : nullptr;
+        g.route_override = route_override ? route_override + (size_t)st * B : nullptr;
+        g.logits = p.gate_logits; g.route = route; g.partial = p.gate_partial;
+        RC(ds_launch_gate(g, s));
+        Q += 4;
+        // ---- bucket by (this stage's route, previous stage's route)
+        const int32_t* route_prev = st > 0 ? (routes_out ? routes_out + (size_t)(st - 1) * B : p.route[st - 1]) : nullptr;
+        RC(ds_launch_make_key(route, route_prev, T, p.key, B, s));
+        RC(ds_launch_bucket(p.key, B, G, p.perm[st], p.inv[st], p.offs[st], p.slot_group[st], s));
+        const int32_t* src = p.perm[st];
+        if (st > 0) {
+            RC(ds_launch_compose_index(p.inv[st - 1], p.perm[st], p.src_index, B, s));
+            src = p.src_index;
+        }
+        MList ml_in = {p.lists[2 * st], (int)ds_mtile_capacity(B, rin * rin, G), rin * rin};
+        MList ml_out = {p.lists[2 * st + 1], (int)ds_mtile_capacity(B, rout * rout, G), rout * rout};
+        RC(ds_build_mtiles(p.offs[st], G, rin * rin, ml_in.list, s));
+        RC(ds_build_mtiles(p.offs[st], G, rout * rout, ml_out.list, s));
+        // ---- group tables: group id = q * T + q_prev
+        GroupTable g1f, gpj, g1, g2, g3;
+        memset(&g1f, 0, sizeof(g1f));
+        g1f.T = G;
+        for (int q = 0; q < T; ++q)
+            for (int qp = 0; qp < T; ++qp) {
+                const int id = q * T + qp;
+                g1f.k_in[id] = st > 0 ? d.out[(st - 1) * T + qp] : d.stem_out;
+                g1f.k_out[id] = d.mid[st * T + q];
+                g1f.row[id] = q;
+            }
+        gpj = g1f; g1 = g1f; g2 = g1f; g3 = g1f;
+        for (int id = 0; id < G; ++id) {
+            const int q = id / T;
+            gpj.k_out[id] = d.out[st * T + q];
+            g1.k_in[id] = d.out[st * T + q];
+            g2.k_in[id] = g2.k_out[id] = d.mid[st * T + q];
+            g3.k_in[id] = d.mid[st * T + q];
+            g3.k_out[id] = d.out[st * T + q];
+        }
+        // buffers other than X: Y1, Y2, Pj, Z
+        bf16_t* free4[4];
+        for (int i = 0, k = 0; i < 5; ++i)
+            if (i != xi) free4[k++] = p.buf[i];
+        bf16_t *Y1 = free4[0], *Y2 = free4[1], *Pj = free4[2], *Z = free4[3];
+        const int64_t x_ss = (int64_t)rin * rin * c_prev_full;
+        for (int b = 0; b < nb; ++b) {
+            const bool first = b == 0;
+            const int bs = first ? stride : 1;
+            const int rb = first ? rin : rout;  // resolution of the block input
+            const void* const* L = Q;
+            Q += first ? 12 : 9;
+            const bf16_t* in = first ? X : Z;
+            const int32_t* in_idx = first ? src : nullptr;
+            const int64_t in_ss = first ? x_ss : (int64_t)rout * rout * 4 * w;
+            const int in_full = first ? c_prev_full : 4 * w;
+            bf16_t* outbuf = first ? Z : (Z == free4[3] ? (bf16_t*)X : free4[3]);
+            (void)outbuf;
+            const bf16_t* shortcut;
+            if (first) {
+                RC(conv_gemm(in, in_idx, in_ss, 0, (const bf16_t*)L[9], in_full, 1, bs, 0, rb, rb, (const float*)L[10],
+                             (const float*)L[11], 4 * w, nullptr, Pj, (int64_t)rout * rout * 4 * w, 0, p.offs[st], ml_out,
+                             gpj, DS_ACT_NONE, s));
+                shortcut = Pj;
+            } else {
+                shortcut = Z;
+            }
+            RC(conv_gemm(in, in_idx, in_ss, 0, (const bf16_t*)L[0], in_full, 1, 1, 0, rb, rb, (const float*)L[1],
+                         (const float*)L[2], w, nullptr, Y1, (int64_t)rb * rb * w, 0, p.offs[st], first ? ml_in : ml_out,
+                         first ? g1f : g1, DS_ACT_RELU, s));
+            RC(conv_gemm(Y1, nullptr, (int64_t)rb * rb * w, 0, (const bf16_t*)L[3], w, 3, bs, 1, rb, rb, (const float*)L[4],
+                         (const float*)L[5], w, nullptr, Y2, (int64_t)rout * rout * w, 0, p.offs[st], ml_out, g2,
+                         DS_ACT_RELU, s));
+            // c3 adds the shortcut; later blocks update Z in place (each element is read and written by one thread)
+            RC(conv_gemm(Y2, nullptr, (int64_t)rout * rout * w, 0, (const bf16_t*)L[6], w, 1, 1, 0, rout, rout,
+                         (const float*)L[7], (const float*)L[8], 4 * w, shortcut, Z, (int64_t)rout * rout * 4 * w, 0,
+                         p.offs[st], ml_out, g3, DS_ACT_RELU, s));
+        }
+        RC(ds_launch_lookup(p.slot_group[st], g3, 1, p.slot_c, B, s));
+        X = Z;
+        for (int i = 0; i < 5; ++i)
+            if (p.buf[i] == Z) xi = i;
+        c_prev_full = 4 * w;
+        r = rout;
+    }
+    GroupTable gh;
+    memset(&gh, 0, sizeof(gh));
+    gh.T = G;
+    for (int id = 0; id < G; ++id) gh.k_in[id] = gh.k_out[id] = d.out[3 * T + id / T];
+    ActView xv = {X, nullptr, (int64_t)r * r * c_prev_full, 0};
+    return ds_launch_head(xv, r * r, (const bf16_t*)Q[0], c_prev_full, (const float*)Q[1], d.classes, p.slot_group[3], gh,
+                          p.perm[3], logits, B, c_prev_full, s);
+}
+
+// =====================================================================================
+// DS-ViT
+//  ints:   image, patch, embed, heads, head_dim, mlp, depth, tokens, T, num_classes, routes[T][3] = (d_e, h, hidden)
+//  params: embed.w [D][3*P*P] bf16, embed.b, cls [D] bf16, pos [tokens][D] bf16,
+//          per layer: ln1.g, ln1.b, wqkv [3][H*Dh][D] bf16, bqkv [3][H*Dh], wproj [D][H*Dh] bf16, bproj,
+//                     ln2.g, ln2.b, fc1.w [mlp][D] bf16, fc1.b, fc2.w [D][mlp] bf16, fc2.b,
+//          ln.g, ln.b, head.w [classes][D] bf16, head.b
+// =====================================================================================
+struct VitDesc {
+    int image, patch, D, H, dh, M, depth, N, T, classes;
+    const int32_t* routes;
+};
+
+bool parse_vit(const ds_net* net, VitDesc* d) {
+    if (net->n_ints < 10) return false;
+    const int32_t* v = net->ints;
+    d->image = v[0]; d->patch = v[1]; d->D = v[2]; d->H = v[3]; d->dh = v[4]; d->M = v[5]; d->depth = v[6];
+    d->N = v[7]; d->T = v[8]; d->classes = v[9];
+    if (d->T < 1 || d->T > DS_MAX_GROUPS) return false;
+    if (net->n_ints != 10 + 3 * d->T) return false;
+    d->routes = v + 10;
+    return net->n_params == 4 + 12 * d->depth + 4;
+}
+
+struct VitPlan {
+    bf16_t *patches, *x, *a, *qkv, *o, *h;
+    size_t qkv_seg;
+    float* gate_logits;
+    int32_t *offs, *perm, *inv, *slot_group, *route;
+    void *list_p, *list_t;
+};
+
+void plan_vit(const VitDesc& d, int B, Bump& bp, VitPlan* p) {
+    const int np = d.N - 1, kp = 3 * d.patch * d.patch, Hd = d.H * d.dh;
+    p->patches = bp.take<bf16_t>((size_t)B * np * kp);
+    p->x = bp.take<bf16_t>((size_t)B * d.N * d.D);
+    p->a = bp.take<bf16_t>((size_t)B * d.N * d.D);
+    p->qkv_seg = ds_align_up((size_t)B * d.N * Hd, 128);
+    p->qkv = bp.take<bf16_t>(3 * p->qkv_seg);
+    p->o = bp.take<bf16_t>((size_t)B * d.N * Hd);
+    p->h = bp.take<bf16_t>((size_t)B * d.N * d.M);
+    p->gate_logits = bp.take<float>((size_t)B * d.T);
+    p->offs = bp.take<int32_t>(d.T + 1);
+    p->perm = bp.take<int32_t>(B);
+    p->inv = bp.take<int32_t>(B);
+    p->slot_group = bp.take<int32_t>(B);
+    p->route = bp.take<int32_t>(B);
+    p->list_p = bp.take<char>(16 + ds_mtile_capacity(B, np, d.T) * 8);
+    p->list_t = bp.take<char>(16 + ds_mtile_capacity(B, d.N, d.T) * 8);
+}
+
+int32_t linear_gemm(const bf16_t* A, int64_t a_ss, int a_ld, const bf16_t* Wt, int64_t w_ld, const float* bias,
+                    const bf16_t* R, int64_t r_ss, int r_ld, int r_use_index, bf16_t* C, int64_t c_ss, int c_ld,
+                    int c_row0, int rows, int n_seg, int64_t w_seg, int64_t c_seg, int tab_seg, const int32_t* offsets,
+                    const MList& ml, const GroupTable& gt, int act, hipStream_t s) {
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.A = A; a.Wt = Wt; a.C = C; a.R = R;
+    a.scale = nullptr; a.shift = bias; a.tab_ld = 0; a.tab_seg_stride = tab_seg;
+    a.a_sample_stride = a_ss; a.c_sample_stride = c_ss; a.r_sample_stride = r_ss;
+    a.a_ld = a_ld; a.c_ld = c_ld; a.r_ld = r_ld; a.c_row0 = c_row0; a.r_use_index = r_use_index;
+    a.w_ld = w_ld; a.w_seg_stride = w_seg; a.c_seg_stride = c_seg; a.n_seg = n_seg;
+    a.H = 1; a.W = rows; a.Ho = 1; a.Wo = rows; a.K = 1; a.stride = 1; a.pad = 0; a.rows = rows;
+    a.offsets = offsets; a.mtiles = ds_mtile_entries(ml.list); a.n_mtiles = ds_mtile_count(ml.list);
+    a.act = act; a.out_f32 = 0; a.gt = gt;
+    return ds_launch_gemm(a, ml.cap, max_out(gt), s);
+}
+
+int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, int B, const int32_t* route_override,
+                    const float* logit_bias, float* logits, int32_t* routes_out, const VitPlan& p, hipStream_t s) {
+    const void* const* P = net->params;
+    const int np = d.N - 1, kp = 3 * d.patch * d.patch, Hd = d.H * d.dh, T = d.T;
+    if (!logit_bias && !route_override) DS_FAIL(DS_EINVAL, "ds_forward(vit): routes need logit_bias or route_override");
+    int32_t* route = routes_out ? routes_out : p.route;
+    GateArgs g;
+    memset(&g, 0, sizeof(g));
+    g.B = B; g.T = T; g.logit_bias = logit_bias; g.route_override = route_override;
+    g.logits = p.gate_logits; g.route = route;
+    RC(ds_launch_gate(g, s));
+    RC(ds_launch_bucket(route, B, T, p.perm, p.inv, p.offs, p.slot_group, s));
+    MList ml_p = {p.list_p, (int)ds_mtile_capacity(B, np, T), np};
+    MList ml_t = {p.list_t, (int)ds_mtile_capacity(B, d.N, T), d.N};
+    RC(ds_build_mtiles(p.offs, T, np, ml_p.list, s));
+    RC(ds_build_mtiles(p.offs, T, d.N, ml_t.list, s));
+    GroupTable ge, gq, gp, g1, g2;
+    memset(&ge, 0, sizeof(ge));
+    ge.T = T;
+    for (int t = 0; t < T; ++t) ge.row[t] = 0;
+    gq = ge; gp = ge; g1 = ge; g2 = ge;
+    for (int t = 0; t < T; ++t) {
+        const int de = d.routes[3 * t], h = d.routes[3 * t + 1], hid = d.routes[3 * t + 2];
+        ge.k_in[t] = kp; ge.k_out[t] = de;
+        gq.k_in[t] = de; gq.k_out[t] = h * d.dh;
+        gp.k_in[t] = h * d.dh; gp.k_out[t] = de;
+        g1.k_in[t] = de; g1.k_out[t] = hid;
+        g2.k_in[t] = hid; g2.k_out[t] = de;
+    }
+    const int64_t x_ss = (int64_t)d.N * d.D;
+    RC(ds_launch_patchify(images, p.perm, p.patches, B, d.image, d.image, d.patch, s));
+    // tokens 1..N-1: patch embedding + bias + position embedding (broadcast over samples)
+    RC(linear_gemm(p.patches, (int64_t)np * kp, kp, (const bf16_t*)P[0], kp, (const float*)P[1], (const bf16_t*)P[3], 0,
+                   d.D, 0, p.x, x_ss, 0, 1, np, 1, 0, 0, 0, p.offs, ml_p, ge, DS_ACT_NONE, s));
+    ActView xv = {p.x, nullptr, x_ss, 0}, av = {p.a, nullptr, x_ss, 0};
+    RC(ds_launch_cls_rows(xv, (const bf16_t*)P[2], (const bf16_t*)P[3], p.slot_group, gq, B, s));
+    const float eps = 1e-6f;
+    for (int l = 0; l < d.depth; ++l) {
+        const void* const* L = P + 4 + 12 * l;
+        RC(ds_launch_layernorm(xv, av, (const float*)L[0], (const float*)L[1], eps, p.slot_group, gq, B, d.N, 0, d.N, s));
+        RC(linear_gemm(p.a, x_ss, 0, (const bf16_t*)L[2], d.D, (const float*)L[3], nullptr, 0, 0, 0, p.qkv,
+                       (int64_t)d.N * Hd, Hd, 0, d.N, 3, (int64_t)Hd * d.D, (int64_t)p.qkv_seg, Hd, p.offs, ml_t, gq,
+                       DS_ACT_NONE, s));
+        RC(ds_launch_attention(p.qkv, p.qkv + p.qkv_seg, p.qkv + 2 * p.qkv_seg, p.o, (int64_t)d.N * Hd, Hd, Hd,
+                               (int64_t)d.N * Hd, p.slot_group, gq, B, d.N, d.H, s));
+        RC(linear_gemm(p.o, (int64_t)d.N * Hd, Hd, (const bf16_t*)L[4], Hd, (const float*)L[5], p.x, x_ss, 0, 1, p.x, x_ss,
+                       0, 0, d.N, 1, 0, 0, 0, p.offs, ml_t, gp, DS_ACT_NONE, s));
+        RC(ds_launch_layernorm(xv, av, (const float*)L[6], (const float*)L[7], eps, p.slot_group, gq, B, d.N, 0, d.N, s));
+        RC(linear_gemm(p.a, x_ss, 0, (const bf16_t*)L[8], d.D, (const float*)L[9], nullptr, 0, 0, 0, p.h,
+                       (int64_t)d.N * d.M, 0, 0, d.N, 1, 0, 0, 0, p.offs, ml_t, g1, DS_ACT_GELU, s));
+        RC(linear_gemm(p.h, (int64_t)d.N * d.M, 0, (const bf16_t*)L[10], d.M, (const float*)L[11], p.x, x_ss, 0, 1, p.x,
+                       x_ss, 0, 0, d.N, 1, 0, 0, 0, p.offs, ml_t, g2, DS_ACT_NONE, s));
+    }
+    const void* const* F = P + 4 + 12 * d.depth;
+    RC(ds_launch_layernorm(xv, av, (const float*)F[0], (const float*)F[1], eps, p.slot_group, gq, B, d.N, 0, 1, s));
+    return ds_launch_head(av, 0, (const bf16_t*)F[2], d.D, (const float*)F[3], d.classes, p.slot_group, gq, p.perm, logits,
+                          B, d.D, s);
+}
+
+}  // namespace
+
+extern "C" size_t ds_forward_workspace(const ds_net* net, int32_t B) {
+    if (!net || !net->ints || B <= 0) return 0;
+    Bump bp = {nullptr, 0};
+    if (net->arch == DS_ARCH_MBNET) {
+        MbDesc d;
+        MbPlan p;
+        if (!parse_mb(net, &d)) return 0;
+        plan_mb(d, B, bp, &p);
+    } else if (net->arch == DS_ARCH_RESNET) {
+        RnDesc d;
+        RnPlan p;
+        if (!parse_rn(net, &d)) return 0;
+        plan_rn(d, B, bp, &p);
+    } else if (net->arch == DS_ARCH_VIT) {
+        VitDesc d;
+        VitPlan p;
+        if (!parse_vit(net, &d)) return 0;
+        plan_vit(d, B, bp, &p);
+    } else {
+        return 0;
+    }
+    return ds_align_up(bp.off, 256);
+}
 
 extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
                               const float* logit_bias, float* logits, int32_t* routes_out, void* ws, size_t ws_bytes,
                               void* stream) {
-    DS_FAIL(DS_EUNSUPPORTED, "ds_forward: not built yet");
+    const char* who = "ds_forward";
+    if (!net || !net->ints || !net->params) DS_FAIL(DS_EINVAL, "%s: null net", who);
+    if (B < 0) DS_FAIL(DS_EINVAL, "%s: B < 0", who);
+    if (B == 0) return DS_OK;
+    if (!images || !logits) DS_FAIL(DS_EINVAL, "%s: null images or logits", who);
+    if (!ds_aligned16(images)) DS_FAIL(DS_EALIGN, "%s: images need 16-byte alignment", who);
+    for (int i = 0; i < net->n_params; ++i)
+        if (!net->params[i] || !ds_aligned16(net->params[i])) DS_FAIL(DS_EINVAL, "%s: parameter %d null or misaligned", who, i);
+    const size_t need = ds_forward_workspace(net, B);
+    if (need == 0) DS_FAIL(DS_ESHAPE, "%s: network description inconsistent with arch %d", who, net->arch);
+    if (!ws || ws_bytes < need || (((uintptr_t)ws) & 255u)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    hipStream_t s = (hipStream_t)stream;
+    Bump bp = {(char*)ws, 0};
+    if (net->arch == DS_ARCH_MBNET) {
+        MbDesc d;
+        MbPlan p;
+        parse_mb(net, &d);
+        if (d.stem_out % 8) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
+        for (int i = 0; i < d.nb * (3 + 2 * d.T); ++i)
+            if ((i >= 3 * d.nb || i % 3 != 2) && (d.blk[i] % 8)) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
+        plan_mb(d, B, bp, &p);
+        return forward_mb(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);
+    }
+    if (net->arch == DS_ARCH_RESNET) {
+        RnDesc d;
+        RnPlan p;
+        parse_rn(net, &d);
+        if (d.stem_out % 8) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
+        for (int i = 0; i < 8 * d.T; ++i)
+            if (d.mid[i] % 8) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
+        plan_rn(d, B, bp, &p);
+        return forward_rn(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);
+    }
+    VitDesc d;
+    VitPlan p;
+    parse_vit(net, &d);
+    if (d.dh != 64 || d.N > 224 || (d.image % d.patch) || d.N != (d.image / d.patch) * (d.image / d.patch) + 1 ||
+        (d.patch % 8))
+        DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 64, tokens <= 224, patch %% 8 == 0", who);
+    for (int i = 0; i < 3 * d.T; ++i) {
+        if (i % 3 == 1) {
+            if (d.routes[i] < 1 || d.routes[i] > d.H) DS_FAIL(DS_EINVAL, "%s: head count outside 1..%d", who, d.H);
+        } else if (d.routes[i] % 8) {
+            DS_FAIL(DS_EALIGN, "%s: route widths must be multiples of 8", who);
+        }
+    }
+    plan_vit(d, B, bp, &p);
+    return forward_vit(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);
 }

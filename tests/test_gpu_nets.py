@@ -1,0 +1,182 @@
+"""End-to-end GPU parity of ds_forward against the per-sample CPU oracle.
+
+Small nets: every sample of a mixed-route batch is checked.  Full-size configurations
+(batch 256, 224x224): the launch configuration the benchmark times; a seeded sample of
+images spanning the routes is recomputed one by one by the oracle, and batch-level
+properties (permutation equivariance, bit-exact repeatability, route histogram) are
+checked on the whole batch.  Logit tolerance: max |gpu - oracle| / max |oracle| <= 2e-2
+(bf16 storage, fp32 accumulation).  Routes must match the oracle exactly; the seeded
+logit bias keeps every gate margin far above 1e-6.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import ds_oracle as O
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = 2e-2
+S = WL.BASE_SEED
+
+
+def dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV).to(dtype).contiguous()
+
+
+def relerr(got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    return float(np.max(np.abs(got - want)) / np.max(np.abs(want)))
+
+
+# ------------------------------------------------------------------ DS-MBNet
+def _mb_case(gpu_lib, arch, params, imgs, lb, check):
+    net = gpu_lib.build_mbnet(arch, params, DEV)
+    B = imgs.shape[0]
+    xg, lbg = dev(imgs, torch.bfloat16), dev(lb[None], torch.float32)
+    logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
+    torch.cuda.synchronize()
+    lg, rt = logits.cpu().numpy(), routes.cpu().numpy()[0]
+    worst = 0.0
+    for b in check:
+        want, t, z = O.forward_mbnet(arch, params, imgs[b], logit_bias=lb[b])
+        assert O.gate_margin(z) > 1e-2
+        assert rt[b] == t, (b, rt[b], t)
+        worst = max(worst, relerr(lg[b], want))
+    assert worst < TOL, worst
+    # teacher-forced routes give the same result as the free-running gate when routes agree
+    l2, r2 = gpu_lib.ds_forward(net, xg, route_override=routes.clone(), logit_bias=lbg)
+    assert torch.equal(l2, logits) and torch.equal(r2, routes)
+    return net, xg, lbg, logits, routes
+
+
+def test_mbnet_small_all_samples(gpu_lib):
+    arch = WL.mbnet_arch(image=64, width_div=4)
+    params = WL.mbnet_params(arch, S + 30)
+    B = 31
+    imgs = WL.images(S + 31, B, 64)
+    lb = WL.seeded_logit_bias(S + 32, B, arch["T"])
+    _, _, _, _, routes = _mb_case(gpu_lib, arch, params, imgs, lb, range(B))
+    assert len(set(routes.cpu().numpy()[0].tolist())) == arch["T"]       # every width occurs
+
+
+def test_mbnet_config3_batch256(gpu_lib):
+    arch = WL.mbnet_arch()
+    params = WL.mbnet_params(arch, S + 3)
+    B = 256
+    imgs = WL.images(S + 103, B)
+    lb = WL.seeded_logit_bias(S + 203, B, arch["T"])
+    target = np.argmax(lb, axis=1)
+    check = [int(np.where(target == t)[0][0]) for t in (0, 5, 9, 13)] + [255]
+    net, xg, lbg, logits, routes = _mb_case(gpu_lib, arch, params, imgs, lb, check)
+    rt = routes.cpu().numpy()[0]
+    assert np.array_equal(rt, target)
+    assert np.bincount(rt, minlength=14).min() >= 18
+    # permuting the batch permutes the logits, bit for bit (bucketing is invisible)
+    pi = torch.randperm(B, generator=torch.Generator().manual_seed(1)).to(DEV)
+    l3, r3 = gpu_lib.ds_forward(net, xg[pi].contiguous(), logit_bias=lbg[:, pi].contiguous())
+    assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
+
+
+# ------------------------------------------------------------------ DS-ResNet
+def _rn_case(gpu_lib, arch, params, imgs, lb, check):
+    net = gpu_lib.build_resnet(arch, params, DEV)
+    xg, lbg = dev(imgs, torch.bfloat16), dev(lb, torch.float32)
+    logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
+    torch.cuda.synchronize()
+    lg, rt = logits.cpu().numpy(), routes.cpu().numpy()
+    worst = 0.0
+    for b in check:
+        want, ro, zs = O.forward_resnet(arch, params, imgs[b], logit_bias=lb[:, b])
+        if rt[:, b].tolist() != ro:
+            # mid-network gates read bf16 features, so a gate may only disagree where the oracle's
+            # margin is within that noise; activations are then compared under the GPU's routes
+            s0 = next(s for s in range(4) if rt[s, b] != ro[s])
+            assert O.gate_margin(zs[s0]) < 2e-2 * np.max(np.abs(zs[s0])), (b, rt[:, b], ro, zs[s0])
+            want, _, _ = O.forward_resnet(arch, params, imgs[b], logit_bias=lb[:, b], route_override=rt[:, b])
+        worst = max(worst, relerr(lg[b], want))
+    assert worst < TOL, worst
+    return net, xg, lbg, logits, routes
+
+
+def _rn_bias(seed, B, T):
+    return np.stack([WL.seeded_logit_bias(seed + s, B, T, amp=16.0) for s in range(4)])
+
+
+def test_resnet_small_all_samples(gpu_lib):
+    arch = WL.resnet_arch(image=64, width_div=2, blocks=(2, 2, 2, 2))
+    params = WL.resnet_params(arch, S + 40)
+    B = 37
+    imgs = WL.images(S + 41, B, 64)
+    lb = _rn_bias(S + 42, B, 4)
+    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, range(B))
+    # forcing the oracle's routes reproduces the free-running logits
+    l2, _ = gpu_lib.ds_forward(net, xg, route_override=routes.clone())
+    assert torch.equal(l2, logits)
+    # a uniform batch on the largest route equals the static full network
+    full = torch.full((4, B), 3, dtype=torch.int32, device=DEV)
+    l3, _ = gpu_lib.ds_forward(net, xg, route_override=full)
+    want, _, _ = O.forward_resnet(arch, params, imgs[5], route_override=[3, 3, 3, 3])
+    assert relerr(l3[5].cpu().numpy(), want) < TOL
+
+
+def test_resnet_config4_batch256(gpu_lib):
+    arch = WL.resnet_arch()
+    params = WL.resnet_params(arch, S + 4)
+    B = 256
+    imgs = WL.images(S + 104, B)
+    lb = _rn_bias(S + 204, B, 4)
+    target = np.argmax(lb, axis=2)                                  # [4, B]
+    check = [0, 101, 255]
+    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, check)
+    rt = routes.cpu().numpy()
+    assert np.mean(rt == target) > 0.97                              # the seeded bias decides nearly every gate
+    for s in range(1, 4):
+        assert len(set(zip(rt[s - 1].tolist(), rt[s].tolist()))) == 16   # all 16 (r_prev, r) boundary pairs occur
+    pi = torch.randperm(B, generator=torch.Generator().manual_seed(2)).to(DEV)
+    l3, r3 = gpu_lib.ds_forward(net, xg[pi].contiguous(), logit_bias=lbg[:, pi].contiguous())
+    assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
+
+
+# ------------------------------------------------------------------ DS-ViT
+def _vit_case(gpu_lib, arch, params, imgs, lb, check):
+    net = gpu_lib.build_vit(arch, params, DEV)
+    xg, lbg = dev(imgs, torch.bfloat16), dev(lb[None], torch.float32)
+    logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
+    torch.cuda.synchronize()
+    lg, rt = logits.cpu().numpy(), routes.cpu().numpy()[0]
+    assert np.array_equal(rt, [O.gate_route(z) for z in lb])
+    worst = 0.0
+    for b in check:
+        want = O.forward_vit(arch, params, imgs[b], int(rt[b]))
+        worst = max(worst, relerr(lg[b], want))
+    assert worst < TOL, worst
+    return net, xg, lbg, logits, routes
+
+
+@pytest.mark.parametrize("routes", ["cross", "diag"])
+def test_vit_small_all_samples(gpu_lib, routes):
+    arch = WL.vit_arch(image=64, patch=16, depth=2, routes=routes)      # 17 tokens, DeiT-S widths
+    params = WL.vit_params(arch, S + 50)
+    B = 53
+    imgs = WL.images(S + 51, B, 64)
+    lb = WL.seeded_logit_bias(S + 52, B, arch["T"])
+    _vit_case(gpu_lib, arch, params, imgs, lb, range(B))
+
+
+def test_vit_config5_batch256(gpu_lib):
+    arch = WL.vit_arch()
+    params = WL.vit_params(arch, S + 5)
+    B = 256
+    imgs = WL.images(S + 105, B)
+    lb = WL.seeded_logit_bias(S + 205, B, arch["T"])
+    target = np.argmax(lb, axis=1)
+    check = [int(np.where(target == t)[0][0]) for t in (0, 23, 47)] + [128]
+    net, xg, lbg, logits, routes = _vit_case(gpu_lib, arch, params, imgs, lb, check)
+    assert np.bincount(routes.cpu().numpy()[0], minlength=48).min() >= 5
+    pi = torch.randperm(B, generator=torch.Generator().manual_seed(3)).to(DEV)
+    l3, r3 = gpu_lib.ds_forward(net, xg[pi].contiguous(), logit_bias=lbg[:, pi].contiguous())
+    assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
+    l4, _ = gpu_lib.ds_forward(net, xg, route_override=routes.clone())
+    assert torch.equal(l4, logits)

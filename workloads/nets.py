@@ -60,14 +60,14 @@ def bn_tables(d: Draw, T: int, C: int) -> dict:
     }
 
 
-def seeded_logit_bias(seed: int, B: int, T: int) -> np.ndarray:
-    """Per-sample additive gate logits: small noise plus 4 on a seeded target route,
+def seeded_logit_bias(seed: int, B: int, T: int, amp: float = 4.0) -> np.ndarray:
+    """Per-sample additive gate logits: small noise plus `amp` on a seeded target route,
     so that every route occurs about B/T times and margins are far above rounding noise."""
     d = Draw(seed)
     noise = d.normal((B, T), std=0.1)
     pi = d.permutation(B)
     bias = noise.copy()
-    bias[np.arange(B), (pi % T).astype(np.int64)] += 4.0
+    bias[np.arange(B), (pi % T).astype(np.int64)] += float(amp)
     return bias.astype(np.float32)
 
 
@@ -185,6 +185,9 @@ def resnet_params(arch: dict, seed: int) -> dict:
             p[pre + ".c2.bn"] = bn_tables(d, T, w)
             p[pre + ".c3.w"] = as_bf16_values(_kaiming(d, (4 * w, w, 1, 1)))
             p[pre + ".c3.bn"] = bn_tables(d, T, 4 * w)
+            # small gain on the last batch-norm of the residual branch (the training recipe starts
+            # it at zero): keeps the random-init net's activations from doubling at every block
+            p[pre + ".c3.bn"]["gamma"] = (0.25 * p[pre + ".c3.bn"]["gamma"]).astype(np.float32)
             if b == 0:
                 p[pre + ".proj.w"] = as_bf16_values(_kaiming(d, (4 * w, cin, 1, 1)))
                 p[pre + ".proj.bn"] = bn_tables(d, T, 4 * w)
