@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Throughput of the gate-routed, weight-sliced forward pass on one MI355X.
+
+One step = one ds_forward pass (gate, bucketing, every sliced layer, classifier,
+un-permute) over a batch of 256 synthetic ImageNet-shaped images with mixed routes,
+inputs and weights resident in HBM.  Prints one JSON line:
+images/s, the roofline fraction of the dominant kernel (measured with HIP events
+around every launch of it inside the timed region) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16 matrix-core peak of MI355X
+PEAK_HBM_GBS = 8000.0
+
+
+def build_workload(name: str, B: int):
+    import numpy as np
+    import workloads as WL
+    S = WL.BASE_SEED
+    if name == "mbnet":
+        arch = WL.mbnet_arch()
+        params = WL.mbnet_params(arch, S + 3)
+        lb = WL.seeded_logit_bias(S + 203, B, arch["T"])[None]
+        label = "config3: DS-MBNet (MobileNetV1-shaped, 14 width routes), bf16"
+    elif name == "resnet":
+        arch = WL.resnet_arch()
+        params = WL.resnet_params(arch, S + 4)
+        lb = np.stack([WL.seeded_logit_bias(S + 204 + s, B, 4, amp=16.0) for s in range(4)])
+        label = "config4: DS-ResNet (ResNet-50-shaped, 4 gates x 4 width ratios), bf16"
+    elif name == "vit":
+        arch = WL.vit_arch()
+        params = WL.vit_params(arch, S + 5)
+        lb = WL.seeded_logit_bias(S + 205, B, arch["T"])[None]
+        label = "config5: DS-ViT (DeiT-S-shaped, 48 routes over embed/heads/MLP), bf16"
+    else:
+        raise SystemExit(f"unknown workload {name}")
+    imgs = WL.images(S + 100 + {"mbnet": 3, "resnet": 4, "vit": 5}[name], B)
+    return arch, params, imgs, lb.astype("float32"), label
+
+
+def cpu_baseline(name, arch, params, imgs, lb, budget_s=15.0):
+    """Times the oracle as it stands on a bounded sample of the same batch."""
+    from oracle import ds_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    n = 0
+    while n < imgs.shape[0] and (time.perf_counter() - t0 < budget_s or n < 2):
+        if name == "mbnet":
+            O.forward_mbnet(arch, params, imgs[n], logit_bias=lb[0, n])
+        elif name == "resnet":
+            O.forward_resnet(arch, params, imgs[n], logit_bias=lb[:, n])
+        else:
+            O.forward_vit(arch, params, imgs[n], O.gate_route(lb[0, n]))
+        n += 1
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "images/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {n} images of the same batch, one by one, float64 numpy ({dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit"])
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernel launches with HIP events (roofline is then null)")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
+
+    import numpy as np
+    import torch
+    import paper_2109_10060_amd as ds
+    from paper_2109_10060_amd import cost as C
+
+    ds.load()
+    dev = "cuda:0"
+    B = args.batch
+    arch, params, imgs, lb, label = build_workload(args.workload, B)
+    net = {"mbnet": ds.build_mbnet, "resnet": ds.build_resnet, "vit": ds.build_vit}[args.workload](arch, params, dev)
+    x = torch.from_numpy(imgs).to(dev).to(torch.bfloat16).contiguous()
+    lbg = torch.from_numpy(lb).to(dev).contiguous()
+    logits = torch.empty((B, net.num_classes), dtype=torch.float32, device=dev)
+    routes = torch.empty((net.n_gates, B), dtype=torch.int32, device=dev)
+    ws = net.workspace(B)
+
+    def step():
+        ds.ds_forward(net, x, logit_bias=lbg, logits=logits, routes=routes, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ds.ds_profile_enable(not args.no_kernel_events)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    prof = ds.ds_profile_read() if not args.no_kernel_events else {}
+    ds.ds_profile_enable(False)
+
+    rt = routes.cpu().numpy()
+    cost = {"mbnet": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost}[args.workload](arch, rt)
+    roofline = None
+    if prof:
+        # dominant kernel: the grouped GEMM (all its launches: linear/1x1 and tap-walking)
+        ms = prof["gemm"][0] + prof["gemm_taps"][0]
+        n = prof["gemm"][1] + prof["gemm_taps"][1]
+        flops = (cost["gemm"]["flops"] + cost["gemm_taps"]["flops"]) * args.steps
+        nbytes = (cost["gemm"]["bytes"] + cost["gemm_taps"]["bytes"]) * args.steps
+        if n and ms > 0:
+            tf = flops / (ms * 1e-3) / 1e12
+            gbs = nbytes / (ms * 1e-3) / 1e9
+            roofline = {"kernel": "gemm_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_BF16_TFLOPS, "traffic": None,
+                        "launches_per_step": n / args.steps, "avg_launch_us": ms * 1e3 / n,
+                        "share_of_step": ms / (ms_per_step * args.steps),
+                        "hbm_view": {"achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}}
+        if args.breakdown:
+            for k, (t, cnt) in prof.items():
+                if not cnt:
+                    continue
+                c = cost.get(k, {"flops": 0.0, "bytes": 0.0})
+                sys.stderr.write(f"{k:10s} {t / args.steps:8.3f} ms/step {cnt // args.steps:4d} launches  "
+                                 f"{c['flops'] / (t / args.steps * 1e-3) / 1e12 if t else 0:8.1f} TFLOP/s "
+                                 f"{c['bytes'] / (t / args.steps * 1e-3) / 1e9 if t else 0:8.0f} GB/s\n")
+
+    out = {
+        "metric": "images/sec at batch 256 (mixed gate widths)", "value": B / (ms_per_step * 1e-3), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": label, "batch": B, "image": arch["image"],
+                   "route_histogram": [np.bincount(r, minlength=net.T).tolist() for r in rt]},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload, arch, params, imgs, lb)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

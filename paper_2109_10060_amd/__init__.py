@@ -32,7 +32,7 @@ EXPORTS = [
     "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
     "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
-    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward",
+    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_profile_enable", "ds_profile_read",
 ]
 
 
@@ -250,3 +250,22 @@ def ds_forward(net: "Net", images, route_override=None, logit_bias=None, logits=
     _chk(lib.ds_forward(ctypes.byref(net.c_struct), _ptr(images, torch.bfloat16), B, _ptr(route_override),
                         _ptr(logit_bias), _ptr(logits), _ptr(routes), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
     return logits, routes
+
+
+KERNEL_CLASSES = ["gemm", "gemm_taps", "attention", "dwconv", "layernorm", "stem", "maxpool", "head", "gate",
+                  "bucket", "index"]
+
+
+def ds_profile_enable(on: bool):
+    _chk(load().ds_profile_enable(1 if on else 0))
+
+
+def ds_profile_read() -> dict:
+    """{kernel class: (total milliseconds, launches)} for the launches recorded since enable."""
+    lib = load()
+    out = {}
+    for k, name in enumerate(KERNEL_CLASSES):
+        ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+        _chk(lib.ds_profile_read(k, ctypes.byref(ms), ctypes.byref(n)))
+        out[name] = (ms.value, n.value)
+    return out

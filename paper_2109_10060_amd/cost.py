@@ -1,0 +1,110 @@
+"""Algorithmic work of one ds_forward pass, per kernel class, for a given route assignment.
+
+flops: 2 x multiply-adds the method itself must do on the valid slices (not the dense work
+it avoids).  bytes: each kernel reads its valid input once and writes its valid output once
+(bf16), reads a residual once where it has one, and reads the union of the weight slices
+once per launch.  These are the numerators of the roofline fractions bench.py reports.
+"""
+from __future__ import annotations
+
+from collections import defaultdict
+
+import numpy as np
+
+
+class Cost(defaultdict):
+    def __init__(self):
+        super().__init__(lambda: {"flops": 0.0, "bytes": 0.0, "launches": 0})
+
+    def add(self, kind, flops, nbytes):
+        e = self[kind]
+        e["flops"] += float(flops)
+        e["bytes"] += float(nbytes)
+        e["launches"] += 1
+
+
+def _osz(n, k, s, p):
+    return (n + 2 * p - k) // s + 1
+
+
+def _gemm(cost, kind, rows_in, rows_out, kk, k_in, k_out, residual=False, out_bytes=2):
+    """k_in, k_out: per-sample arrays of valid widths."""
+    k_in, k_out = np.asarray(k_in, np.float64), np.asarray(k_out, np.float64)
+    flops = 2.0 * rows_out * kk * np.sum(k_in * k_out)
+    nbytes = 2.0 * rows_in * np.sum(k_in) + out_bytes * rows_out * np.sum(k_out) * (2 if residual else 1)
+    nbytes += 2.0 * kk * float(np.max(k_in)) * float(np.max(k_out))
+    cost.add(kind, flops, nbytes)
+
+
+def mbnet_cost(arch, routes) -> Cost:
+    routes = np.asarray(routes).reshape(-1)
+    B = routes.shape[0]
+    c = Cost()
+    r = _osz(arch["image"], 3, 2, 1)
+    so = arch["stem_out"]
+    c.add("stem", 2.0 * B * r * r * 27 * so, B * (3 * arch["image"] ** 2 * 2 + r * r * so * 2))
+    for i, (_ci, _co, s) in enumerate(arch["blocks"]):
+        rin = r
+        r = _osz(r, 3, s, 1)
+        ci, co = arch["cin"][routes, i].astype(np.float64), arch["cout"][routes, i].astype(np.float64)
+        c.add("dwconv", 2.0 * r * r * 9 * ci.sum(), 2.0 * (rin * rin + r * r) * ci.sum())
+        _gemm(c, "gemm", r * r, r * r, 1, ci, co)
+        if i == arch["gate_after"] - 1:
+            c.add("gate", 2.0 * B * (r * r * co[0]), 2.0 * B * r * r * co[0])
+    cl = arch["cout"][routes, -1].astype(np.float64)
+    c.add("head", 2.0 * arch["num_classes"] * cl.sum(), 2.0 * r * r * cl.sum() + 2.0 * arch["num_classes"] * cl.max())
+    return c
+
+
+def resnet_cost(arch, routes) -> Cost:
+    routes = np.asarray(routes).reshape(4, -1)
+    B = routes.shape[1]
+    c = Cost()
+    r1 = _osz(arch["image"], 7, 2, 3)
+    so = arch["stem_out"]
+    c.add("stem", 2.0 * B * r1 * r1 * 147 * so, B * (3 * arch["image"] ** 2 * 2 + r1 * r1 * so * 2))
+    r = _osz(r1, 3, 2, 1)
+    c.add("maxpool", 0.0, 2.0 * B * so * (r1 * r1 + r * r))
+    cprev = np.full(B, so, np.float64)
+    for s, nb in enumerate(arch["blocks"]):
+        mid = arch["mid"][s][routes[s]].astype(np.float64)
+        out = arch["out"][s][routes[s]].astype(np.float64)
+        c.add("gate", 2.0 * r * r * cprev.sum(), 2.0 * r * r * cprev.sum())
+        for b in range(nb):
+            stride = 2 if (b == 0 and s > 0) else 1
+            ro = _osz(r, 3, stride, 1)
+            cin = cprev if b == 0 else out
+            if b == 0:
+                _gemm(c, "gemm", ro * ro, ro * ro, 1, cin, out)      # 1x1 projection reads only the strided pixels
+            _gemm(c, "gemm", r * r, r * r, 1, cin, mid)
+            _gemm(c, "gemm_taps", r * r, ro * ro, 9, mid, mid)
+            _gemm(c, "gemm", ro * ro, ro * ro, 1, mid, out, residual=True)
+            r = ro
+        cprev = out
+    c.add("head", 2.0 * arch["num_classes"] * cprev.sum(),
+          2.0 * r * r * cprev.sum() + 2.0 * arch["num_classes"] * cprev.max())
+    return c
+
+
+def vit_cost(arch, routes) -> Cost:
+    routes = np.asarray(routes).reshape(-1)
+    tab = arch["routes"][routes].astype(np.float64)
+    de, h, hid = tab[:, 0], tab[:, 1], tab[:, 2]
+    hd = h * arch["head_dim"]
+    N, B = arch["tokens"], routes.shape[0]
+    kp = 3 * arch["patch"] ** 2
+    c = Cost()
+    c.add("index", 0.0, 2.0 * 2 * B * (N - 1) * kp)                                 # patch extraction
+    _gemm(c, "gemm", N - 1, N - 1, 1, np.full(B, kp), de)
+    for _ in range(arch["depth"]):
+        c.add("layernorm", 8.0 * N * de.sum(), 4.0 * N * de.sum())
+        k_in, k_out = de, 3 * hd
+        _gemm(c, "gemm", N, N, 1, k_in, k_out)
+        c.add("attention", 4.0 * N * N * hd.sum(), 2.0 * 4 * N * hd.sum())
+        _gemm(c, "gemm", N, N, 1, hd, de, residual=True)
+        c.add("layernorm", 8.0 * N * de.sum(), 4.0 * N * de.sum())
+        _gemm(c, "gemm", N, N, 1, de, hid)
+        _gemm(c, "gemm", N, N, 1, hid, de, residual=True)
+    c.add("layernorm", 8.0 * de.sum(), 4.0 * de.sum())
+    c.add("head", 2.0 * arch["num_classes"] * de.sum(), 2.0 * de.sum() + 2.0 * arch["num_classes"] * de.max())
+    return c

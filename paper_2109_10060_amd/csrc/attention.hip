@@ -132,6 +132,7 @@ int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, b
                             const GroupTable& gt, int32_t B, int32_t N, int32_t H, hipStream_t s) {
     if (B <= 0 || H <= 0) return DS_OK;
     if (N < 1 || N > KEYS) DS_FAIL(DS_EUNSUPPORTED, "attention: sequence length %d outside 1..%d", N, KEYS);
+    ProfScope prof(DS_K_ATTENTION, s);
     hipLaunchKernelGGL(attention_kernel, dim3((unsigned)B, (unsigned)H), dim3(256), 0, s, q, k, v, o, sample_stride,
                        ld, o_ld, o_sample_stride, slot_group, gt, N, 0.125f);
     DS_CHECK_LAUNCH("attention");

@@ -157,3 +157,25 @@ int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, b
 int32_t ds_launch_set_offsets(int32_t* offsets, int32_t B, hipStream_t s);  // offsets[0..1] = {0, B}
 // key[b] = hi[b] * mul + (lo ? lo[b] : 0)
 int32_t ds_launch_make_key(const int32_t* hi, const int32_t* lo, int32_t mul, int32_t* key, int32_t B, hipStream_t s);
+
+// ---- per-kernel timing with HIP events (off unless ds_profile_enable(1)) ---------
+enum {
+    DS_K_GEMM = 0,   // gemm_kernel on linear / 1x1 layers
+    DS_K_GEMM_TAPS,  // gemm_kernel walking KxK taps (implicit-GEMM convolution)
+    DS_K_ATTENTION,
+    DS_K_DWCONV,
+    DS_K_LAYERNORM,
+    DS_K_STEM,
+    DS_K_MAXPOOL,
+    DS_K_HEAD,
+    DS_K_GATE,
+    DS_K_BUCKET,
+    DS_K_MISC,
+    DS_K_COUNT
+};
+struct ProfScope {
+    int rec;
+    hipStream_t s;
+    ProfScope(int kind, hipStream_t stream);
+    ~ProfScope();
+};

@@ -359,6 +359,7 @@ __global__ void make_key_kernel(const int32_t* hi, const int32_t* lo, int mul, i
 }  // namespace
 
 int32_t ds_launch_set_offsets(int32_t* offsets, int32_t B, hipStream_t s) {
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(set_offsets_kernel, dim3(1), dim3(64), 0, s, offsets, B);
     DS_CHECK_LAUNCH("set offsets");
     return DS_OK;
@@ -366,12 +367,14 @@ int32_t ds_launch_set_offsets(int32_t* offsets, int32_t B, hipStream_t s) {
 
 int32_t ds_launch_make_key(const int32_t* hi, const int32_t* lo, int32_t mul, int32_t* key, int32_t B, hipStream_t s) {
     if (B <= 0) return DS_OK;
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(make_key_kernel, dim3((B + 255) / 256), dim3(256), 0, s, hi, lo, mul, key, B);
     DS_CHECK_LAUNCH("make key");
     return DS_OK;
 }
 
 int32_t ds_launch_expand_groups(const int32_t* offsets, int32_t T, int32_t* slot_group, hipStream_t s) {
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(expand_groups_kernel, dim3(1), dim3(256), 0, s, offsets, T, slot_group);
     DS_CHECK_LAUNCH("expand groups");
     return DS_OK;
@@ -387,6 +390,7 @@ int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* sca
     const int64_t n = (int64_t)Ho * Wo * (cmax / 8);
     if (n <= 0) return DS_OK;
     dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    ProfScope prof(DS_K_DWCONV, s);
     hipLaunchKernelGGL(dwconv_kernel, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
                        Ho, Wo, stride, act);
     DS_CHECK_LAUNCH("depthwise conv");
@@ -398,6 +402,7 @@ int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const floa
                             int32_t row0, int32_t n_rows, hipStream_t s) {
     if (B <= 0 || n_rows <= 0) return DS_OK;
     const int64_t total = (int64_t)B * n_rows;
+    ProfScope prof(DS_K_LAYERNORM, s);
     hipLaunchKernelGGL(layernorm_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, x, y, gamma, beta, eps,
                        slot_group, gt, B, rows, row0, n_rows);
     DS_CHECK_LAUNCH("layernorm");
@@ -412,6 +417,7 @@ int32_t ds_launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const
     const int chunks = Cout / 8, ppb = 256 / chunks;
     dim3 grid((unsigned)((Ho * Wo + ppb - 1) / ppb), (unsigned)B);
     const size_t shm = (size_t)K * K * 3 * Cout * sizeof(float);
+    ProfScope prof(DS_K_STEM, s);
     hipLaunchKernelGGL(stem_kernel, grid, dim3(256), shm, s, img, index, y, w, scale, shift, H, W, Ho, Wo, K, stride,
                        pad, Cout);
     DS_CHECK_LAUNCH("stem conv");
@@ -423,6 +429,7 @@ int32_t ds_launch_maxpool(const bf16_t* x, bf16_t* y, int32_t B, int32_t H, int3
     const int Ho = (H + 2 - 3) / 2 + 1, Wo = (W + 2 - 3) / 2 + 1;
     const int64_t n = (int64_t)Ho * Wo * (C / 8);
     dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    ProfScope prof(DS_K_MAXPOOL, s);
     hipLaunchKernelGGL(maxpool_kernel, grid, dim3(256), 0, s, x, y, H, W, Ho, Wo, C);
     DS_CHECK_LAUNCH("maxpool");
     return DS_OK;
@@ -432,6 +439,7 @@ int32_t ds_launch_head(ActView x, int32_t HW, const bf16_t* w, int32_t w_ld, con
                        const int32_t* slot_group, const GroupTable& gt, const int32_t* out_index, float* logits,
                        int32_t B, int32_t C, hipStream_t s) {
     if (B <= 0) return DS_OK;
+    ProfScope prof(DS_K_HEAD, s);
     hipLaunchKernelGGL(head_kernel, dim3((unsigned)B), dim3(256), (size_t)C * sizeof(float), s, x, HW, w, w_ld, bias,
                        n_out, slot_group, gt, out_index, logits);
     DS_CHECK_LAUNCH("classifier head");
@@ -443,6 +451,7 @@ int32_t ds_launch_patchify(const bf16_t* img, const int32_t* index, bf16_t* patc
     if (B <= 0) return DS_OK;
     const int64_t n = (int64_t)(H / P) * (W / P) * (3 * P * P / 8);
     dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(patchify_kernel, grid, dim3(256), 0, s, img, index, patches, H, W, P);
     DS_CHECK_LAUNCH("patchify");
     return DS_OK;
@@ -451,6 +460,7 @@ int32_t ds_launch_patchify(const bf16_t* img, const int32_t* index, bf16_t* patc
 int32_t ds_launch_cls_rows(ActView x, const bf16_t* cls, const bf16_t* pos, const int32_t* slot_group,
                            const GroupTable& gt, int32_t B, hipStream_t s) {
     if (B <= 0) return DS_OK;
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(cls_rows_kernel, dim3((unsigned)B), dim3(128), 0, s, x, cls, pos, slot_group, gt);
     DS_CHECK_LAUNCH("class-token rows");
     return DS_OK;
@@ -467,6 +477,7 @@ int32_t ds_launch_conv_f32_nchw(const float* x, const float* w, const float* sca
     for (int t = 0; t < gt.T; ++t) omax = gt.k_out[t] > omax ? gt.k_out[t] : omax;
     if (omax <= 0) return DS_OK;
     dim3 grid((unsigned)((Ho * Wo + 255) / 256), (unsigned)omax, (unsigned)B);
+    ProfScope prof(DS_K_GEMM_TAPS, s);
     hipLaunchKernelGGL(conv_f32_kernel, grid, dim3(256), 0, s, x, w, scale, shift, tab_ld, residual, y, slot_group,
                        perm, gt, C_I, C_O, H, W, Ho, Wo, K, stride, pad, act);
     DS_CHECK_LAUNCH("fp32 conv");
@@ -475,6 +486,7 @@ int32_t ds_launch_conv_f32_nchw(const float* x, const float* w, const float* sca
 
 int32_t ds_launch_compose_index(const int32_t* inner, const int32_t* outer, int32_t* out, int32_t B, hipStream_t s) {
     if (B <= 0) return DS_OK;
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(compose_index_kernel, dim3((B + 255) / 256), dim3(256), 0, s, inner, outer, out, B);
     DS_CHECK_LAUNCH("compose index");
     return DS_OK;
@@ -482,6 +494,7 @@ int32_t ds_launch_compose_index(const int32_t* inner, const int32_t* outer, int3
 
 int32_t ds_launch_lookup(const int32_t* idx, const GroupTable& gt, int32_t which, int32_t* out, int32_t B, hipStream_t s) {
     if (B <= 0) return DS_OK;
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(lookup_kernel, dim3((B + 255) / 256), dim3(256), 0, s, idx, gt, which, out, B);
     DS_CHECK_LAUNCH("lookup");
     return DS_OK;

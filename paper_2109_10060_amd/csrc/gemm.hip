@@ -206,6 +206,7 @@ size_t ds_mtile_capacity(int32_t B, int32_t rows, int32_t T) {
 }
 
 int32_t ds_build_mtiles(const int32_t* offsets, int32_t T, int32_t rows, void* list, hipStream_t s) {
+    ProfScope prof(DS_K_MISC, s);
     hipLaunchKernelGGL(build_mtiles_kernel, dim3(1), dim3(256), 0, s, offsets, T, rows, (int32_t*)list,
                        (int2*)((char*)list + 16));
     DS_CHECK_LAUNCH("build_mtiles");
@@ -215,6 +216,7 @@ int32_t ds_build_mtiles(const int32_t* offsets, int32_t T, int32_t rows, void* l
 int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
     if (max_mtiles <= 0 || max_kout <= 0) return DS_OK;
     dim3 grid((unsigned)max_mtiles, (unsigned)(a.n_seg * ((max_kout + BN - 1) / BN)));
+    ProfScope prof(a.K > 1 ? DS_K_GEMM_TAPS : DS_K_GEMM, s);
     hipLaunchKernelGGL(gemm_kernel, grid, dim3(NT), 0, s, a);
     DS_CHECK_LAUNCH("sliced gemm");
     return DS_OK;

@@ -1,0 +1,56 @@
+// Optional per-kernel timing: when enabled, every kernel launcher brackets its launch
+// with a pair of HIP events on the launch stream; ds_profile_read sums the elapsed
+// times per kernel class.  Off by default; costs nothing when off.
+#include <vector>
+
+#include "common.h"
+
+namespace {
+struct Rec {
+    hipEvent_t a, b;
+    int kind;
+};
+bool g_on = false;
+std::vector<Rec> g_pool;  // events are created once and reused
+size_t g_used = 0;
+}  // namespace
+
+ProfScope::ProfScope(int kind, hipStream_t stream) : rec(-1), s(stream) {
+    if (!g_on) return;
+    if (g_used == g_pool.size()) {
+        Rec r;
+        if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+        r.kind = kind;
+        g_pool.push_back(r);
+    }
+    rec = (int)g_used++;
+    g_pool[rec].kind = kind;
+    (void)hipEventRecord(g_pool[rec].a, s);
+}
+
+ProfScope::~ProfScope() {
+    if (rec >= 0) (void)hipEventRecord(g_pool[rec].b, s);
+}
+
+extern "C" int32_t ds_profile_enable(int32_t on) {
+    g_on = on != 0;
+    g_used = 0;
+    return DS_OK;
+}
+
+extern "C" int32_t ds_profile_read(int32_t kind, double* total_ms, int64_t* launches) {
+    if (kind < 0 || kind >= DS_K_COUNT || !total_ms || !launches) DS_FAIL(DS_EINVAL, "ds_profile_read: bad argument");
+    double t = 0.0;
+    int64_t n = 0;
+    for (size_t i = 0; i < g_used; ++i) {
+        if (g_pool[i].kind != kind) continue;
+        if (hipEventSynchronize(g_pool[i].b) != hipSuccess) DS_FAIL(DS_EHIP, "ds_profile_read: event sync failed");
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_pool[i].a, g_pool[i].b) != hipSuccess) DS_FAIL(DS_EHIP, "ds_profile_read: elapsed time failed");
+        t += ms;
+        ++n;
+    }
+    *total_ms = t;
+    *launches = n;
+    return DS_OK;
+}

@@ -206,6 +206,7 @@ size_t ds_gate_partial_bytes(int32_t B, int32_t C) { return (size_t)B * C * POOL
 
 int32_t ds_launch_gate(const GateArgs& a, hipStream_t s) {
     if (a.B <= 0) return DS_OK;
+    ProfScope prof(DS_K_GATE, s);
     int splits = 1;
     if (a.x) {
         if (a.layout == DS_NHWC) {
@@ -228,6 +229,7 @@ int32_t ds_launch_gate(const GateArgs& a, hipStream_t s) {
 
 int32_t ds_launch_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
                          int32_t* offsets, int32_t* slot_group, hipStream_t s) {
+    ProfScope prof(DS_K_BUCKET, s);
     hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(1024), 0, s, route, B, T, perm, inv_perm, offsets, slot_group);
     DS_CHECK_LAUNCH("route bucket");
     return DS_OK;
