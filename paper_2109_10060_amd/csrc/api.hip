@@ -56,7 +56,7 @@ extern "C" size_t ds_slot_workspace(int32_t B) { return ds_align_up((size_t)(B >
 
 extern "C" size_t ds_sliced_linear_workspace(int32_t B, int32_t rows, int32_t T) {
     if (B < 0 || rows < 0 || T < 0) return 0;
-    return ds_align_up(16 + ds_mtile_capacity(B, rows, T) * 8, 256);
+    return ds_align_up(16 + ds_mtile_capacity(B, rows, T) * 16, 256);
 }
 
 extern "C" int32_t ds_sliced_linear(const void* x, int64_t x_ld, const void* w, int64_t w_ld, int32_t N_full,
@@ -101,7 +101,7 @@ extern "C" int32_t ds_sliced_linear(const void* x, int64_t x_ld, const void* w, 
 
 extern "C" size_t ds_sliced_conv_workspace(int32_t B, int32_t Ho, int32_t Wo, int32_t T) {
     if (B < 0 || Ho < 0 || Wo < 0 || T < 0) return 0;
-    return ds_align_up(16 + ds_mtile_capacity(B, Ho * Wo, T) * 8, 256) + ds_slot_workspace(B);
+    return ds_align_up(16 + ds_mtile_capacity(B, Ho * Wo, T) * 16, 256) + ds_slot_workspace(B);
 }
 
 extern "C" int32_t ds_sliced_conv(const void* x, int32_t dtype, int32_t layout, int32_t B, int32_t C_I, int32_t H,
@@ -206,7 +206,7 @@ extern "C" int32_t ds_sliced_layernorm(const void* x, int64_t x_ld, const float*
 
 extern "C" size_t ds_sliced_mhsa_workspace(int32_t B, int32_t N, int32_t H, int32_t head_dim, int32_t T) {
     if (B < 0 || N < 0 || H < 0 || head_dim < 0 || T < 0) return 0;
-    return ds_align_up(16 + ds_mtile_capacity(B, N, T) * 8, 256) + ds_slot_workspace(B) +
+    return ds_align_up(16 + ds_mtile_capacity(B, N, T) * 16, 256) + ds_slot_workspace(B) +
            4 * ds_align_up((size_t)B * N * H * head_dim * sizeof(bf16_t), 256);
 }
 
@@ -234,7 +234,7 @@ extern "C" int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D
     hipStream_t s = (hipStream_t)stream;
     char* p = (char*)ws;
     void* mlist = p;
-    p += ds_align_up(16 + ds_mtile_capacity(B, N, g->T) * 8, 256);
+    p += ds_align_up(16 + ds_mtile_capacity(B, N, g->T) * 16, 256);
     int32_t* slot_group = (int32_t*)p;
     p += ds_slot_workspace(B);
     const size_t bufsz = ds_align_up((size_t)B * N * Hd * sizeof(bf16_t), 256);

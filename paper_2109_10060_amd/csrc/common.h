@@ -73,18 +73,18 @@ struct GemmArgs {
     int32_t H, W, Ho, Wo, K, stride, pad, rows;
     // schedule
     const int32_t* offsets;  // device [T+1] slots
-    const int2* mtiles;      // device [(group, first row inside group)]
+    const int4* mtiles;      // device [(group, first row inside group, first slot, rows of group)]
     const int32_t* n_mtiles; // device scalar
     int32_t act, out_f32;
     GroupTable gt;
 };
 
 size_t ds_mtile_capacity(int32_t B, int32_t rows, int32_t T);
-// builds the m-tile list for (offsets, rows); list needs ds_mtile_capacity()*8 + 16 bytes
+// builds the m-tile list for (offsets, rows); list needs ds_mtile_capacity()*16 + 16 bytes
 int32_t ds_build_mtiles(const int32_t* offsets, int32_t T, int32_t rows, void* list, hipStream_t s);
 int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
 
-static inline const int2* ds_mtile_entries(const void* list) { return (const int2*)((const char*)list + 16); }
+static inline const int4* ds_mtile_entries(const void* list) { return (const int4*)((const char*)list + 16); }
 static inline const int32_t* ds_mtile_count(const void* list) { return (const int32_t*)list; }
 
 // ---- routing agent ------------------------------------------------------------
@@ -130,6 +130,9 @@ int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const floa
 int32_t ds_launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
                        const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
                        int32_t pad, int32_t Cout, hipStream_t s);
+int32_t ds_launch_stem_mfma(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
+                            const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
+                            int32_t pad, int32_t Cout, hipStream_t s);
 int32_t ds_launch_maxpool(const bf16_t* x, bf16_t* y, int32_t B, int32_t H, int32_t W, int32_t C, hipStream_t s);
 // classifier: logits[out_index[slot]][o] = sum_c W[o][c] * v[c] + b[o]; v = spatial mean of x (HW > 0) or row 0 (HW == 0)
 int32_t ds_launch_head(ActView x, int32_t HW, const bf16_t* w, int32_t w_ld, const float* bias, int32_t n_out,

@@ -413,6 +413,8 @@ int32_t ds_launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const
                        const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
                        int32_t pad, int32_t Cout, hipStream_t s) {
     if (B <= 0) return DS_OK;
+    const int32_t rc = ds_launch_stem_mfma(img, index, y, w, scale, shift, B, H, W, K, stride, pad, Cout, s);
+    if (rc != DS_EUNSUPPORTED) return rc;
     const int Ho = (H + 2 * pad - K) / stride + 1, Wo = (W + 2 * pad - K) / stride + 1;
     const int chunks = Cout / 8, ppb = 256 / chunks;
     dim3 grid((unsigned)((Ho * Wo + ppb - 1) / ppb), (unsigned)B);

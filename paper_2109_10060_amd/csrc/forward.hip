@@ -144,7 +144,7 @@ void plan_mb(const MbDesc& d, int B, Bump& bp, MbPlan* p) {
         r = (r + 2 - 3) / d.blk[3 * i + 2] + 1;
         const int phase = i >= d.gate_after;
         if (r * r != last_rows || phase != last_phase) {
-            p->lists[p->n_lists++] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, phase ? d.T : 1) * 8);
+            p->lists[p->n_lists++] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, phase ? d.T : 1) * 16);
             last_rows = r * r;
             last_phase = phase;
         }
@@ -288,9 +288,9 @@ void plan_rn(const RnDesc& d, int B, Bump& bp, RnPlan* p) {
     p->slot_c = bp.take<int32_t>(B);
     r = r2;
     for (int s = 0; s < 4; ++s) {
-        p->lists[2 * s] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 8);  // input resolution
+        p->lists[2 * s] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 16);  // input resolution
         if (s > 0) r = (r + 2 - 3) / 2 + 1;
-        p->lists[2 * s + 1] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 8);  // output resolution
+        p->lists[2 * s + 1] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 16);  // output resolution
     }
 }
 
@@ -461,8 +461,8 @@ void plan_vit(const VitDesc& d, int B, Bump& bp, VitPlan* p) {
     p->inv = bp.take<int32_t>(B);
     p->slot_group = bp.take<int32_t>(B);
     p->route = bp.take<int32_t>(B);
-    p->list_p = bp.take<char>(16 + ds_mtile_capacity(B, np, d.T) * 8);
-    p->list_t = bp.take<char>(16 + ds_mtile_capacity(B, d.N, d.T) * 8);
+    p->list_p = bp.take<char>(16 + ds_mtile_capacity(B, np, d.T) * 16);
+    p->list_t = bp.take<char>(16 + ds_mtile_capacity(B, d.N, d.T) * 16);
 }
 
 int32_t linear_gemm(const bf16_t* A, int64_t a_ss, int a_ld, const bf16_t* Wt, int64_t w_ld, const float* bias,
