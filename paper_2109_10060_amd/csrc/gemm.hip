@@ -11,10 +11,11 @@
 //
 // Tiling: 128 x BN output tile per 256-thread workgroup (BN = 64, 128 or 256,
 // chosen from the widest slice of the layer), 4 wavefronts, each holding a grid
-// of v_mfma_f32_32x32x16_bf16 accumulators.  Operands go through LDS in 32-deep
-// slabs (row stride padded to 40 elements: conflict-free 16-byte reads), double
-// buffered, with the next slab's global loads in flight during the matrix
-// instructions and one barrier per slab.  The epilogue (split batch-norm scale and
+// of v_mfma_f32_32x32x16_bf16 accumulators.  Operands go through LDS in 64-deep
+// slabs (128-byte rows, 16-byte chunks XOR-swizzled by row so stores and reads are
+// bank-conflict free); the next slab's global loads are issued into registers
+// before the current slab's 32 matrix instructions per wavefront and stored to
+// LDS after them.  The epilogue (split batch-norm scale and
 // shift or bias, residual, ReLU/GELU, bf16 rounding) re-reads the accumulators
 // through LDS so that every lane stores 4 consecutive channels of one row.
 //
@@ -28,17 +29,25 @@
 
 namespace {
 
-constexpr int BM = DS_GEMM_BM, BK = 32, LDS_LD = BK + 8, NT = 256;
+constexpr int BM = DS_GEMM_BM, NT = 256;
+
+// 16-byte chunk c of LDS row r is stored at chunk position c ^ swz(r): rows are BK * 2 bytes with no
+// padding; the row-major stores and the operand reads (32 consecutive rows, one chunk column) are
+// bank-conflict free for 8- and 16-lane access groups alike
+template <int BK>
+__device__ __forceinline__ int swz(int r) {
+    return BK == 64 ? ((r ^ (r >> 3)) & 7) : (((r >> 1) ^ (r >> 2)) & 3);
+}
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
-template <int WROWS, int WCOLS, int WMT, int WNT>
+template <int WROWS, int WCOLS, int WMT, int WNT, int BK>
 struct Tile {
-    static constexpr int BN = WCOLS * WNT * 32;
+    static constexpr int BN = WCOLS * WNT * 32, LDS_LD = BK;
     static constexpr int COLS = WNT * 32;                      // columns staged per wavefront
-    static constexpr int SROWS = COLS > 64 ? 16 : 32;          // rows staged per pass
+    static constexpr int SROWS = 16;                           // rows staged per pass
     static constexpr int ST_LD = COLS + 4;
-    static constexpr int LOOP_BYTES = 2 * (BM + BN) * LDS_LD * 2;
+    static constexpr int LOOP_BYTES = (BM + BN) * LDS_LD * 2;
     static constexpr int STAGE_BYTES = 4 * SROWS * ST_LD * 4;
     static constexpr int MAIN_BYTES = LOOP_BYTES > STAGE_BYTES ? LOOP_BYTES : STAGE_BYTES;
     static constexpr int TABLE_BYTES = BM * (8 + 8 + 8 + 8);
@@ -46,13 +55,13 @@ struct Tile {
     static_assert(WROWS * WCOLS == 4 && WROWS * WMT * 32 == BM, "4 wavefronts cover a 128-row tile");
 };
 
-template <int WROWS, int WCOLS, int WMT, int WNT>
+template <int WROWS, int WCOLS, int WMT, int WNT, int BK>
 __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
-    using TL = Tile<WROWS, WCOLS, WMT, WNT>;
-    constexpr int BN = TL::BN;
+    using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
+    constexpr int BN = TL::BN, LDS_LD = BK, CPR = BK / 8, RPT = NT / CPR;   // chunks per row, rows per pass
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16_t* As = (bf16_t*)smem;                       // [2][BM][LDS_LD]
-    bf16_t* Bs = As + 2 * BM * LDS_LD;                // [2][BN][LDS_LD]
+    bf16_t* As = (bf16_t*)smem;                       // [BM][BK]
+    bf16_t* Bs = As + BM * LDS_LD;                    // [BN][BK]
     long long* rowA = (long long*)(smem + TL::MAIN_BYTES);
     long long* rowC = rowA + BM;
     long long* rowR = rowC + BM;
@@ -105,48 +114,51 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
     }
     __syncthreads();
 
-    // ---- load assignment: A 2 chunks, B BN/64 chunks of 8 elements per thread ---------
-    constexpr int NB = BN / 64;
-    const int kc8 = (tid & 3) * 8;
-    const int lrow = tid >> 2;
-    long long abase[2];
-    int2 ayx[2];
+    // ---- load assignment: a thread owns chunk (tid % CPR) of rows (tid / CPR) + RPT i ----
+    constexpr int NA = BM / RPT, NB = BN / RPT;
+    const int lchunk = tid % CPR;
+    const int kc8 = lchunk * 8;
+    const int lrow = tid / CPR;
+    long long abase[NA];
+    int2 ayx[NA];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        abase[i] = rowA[lrow + 64 * i];
-        ayx[i] = rowYX[lrow + 64 * i];
+    for (int i = 0; i < NA; ++i) {
+        abase[i] = rowA[lrow + RPT * i];
+        ayx[i] = rowYX[lrow + RPT * i];
     }
-    long long wrow[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        const int n = n0 + lrow + 64 * i;
-        wrow[i] = n < k_out ? (long long)seg * a.w_seg_stride + (long long)n * a.w_ld : -1;
-    }
+    const long long wbase = (long long)seg * a.w_seg_stride + (long long)(n0 + lrow) * a.w_ld;
+    const long long wstep = RPT * a.w_ld;
+    const int wrows = k_out - n0 - lrow;              // B row i is valid while RPT i < wrows
 
-    uint4 ra[2], rb[NB];
+    uint4 ra[NA], rb[NB];
     auto load_global = [&](int tap, int kc) {
         const int u = tap / a.K, v = tap - u * a.K;
         const bool kok = (kc + kc8) < k_in;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NA; ++i) {
             const int iy = ayx[i].x + u, ix = ayx[i].y + v;
             const bool ok = abase[i] >= 0 && kok && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
             ra[i] = make_uint4(0, 0, 0, 0);
             if (ok) ra[i] = *(const uint4*)(a.A + abase[i] + (long long)(iy * a.W + ix) * a_ld + kc + kc8);
         }
+        const bf16_t* wp = a.Wt + wbase + (long long)tap * a.w_tap_stride + kc + kc8;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             rb[i] = make_uint4(0, 0, 0, 0);
-            if (wrow[i] >= 0 && kok) rb[i] = *(const uint4*)(a.Wt + wrow[i] + (long long)tap * a.w_tap_stride + kc + kc8);
+            if (RPT * i < wrows && kok) rb[i] = *(const uint4*)(wp + i * wstep);
         }
     };
-    auto store_lds = [&](int buf) {
-        bf16_t* as = As + buf * BM * LDS_LD;
-        bf16_t* bs = Bs + buf * BN * LDS_LD;
+    auto store_lds = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) *(uint4*)(as + (lrow + 64 * i) * LDS_LD + kc8) = ra[i];
+        for (int i = 0; i < NA; ++i) {
+            const int r = lrow + RPT * i;
+            *(uint4*)(As + r * LDS_LD + ((lchunk ^ swz<BK>(r)) * 8)) = ra[i];
+        }
 #pragma unroll
-        for (int i = 0; i < NB; ++i) *(uint4*)(bs + (lrow + 64 * i) * LDS_LD + kc8) = rb[i];
+        for (int i = 0; i < NB; ++i) {
+            const int r = lrow + RPT * i;
+            *(uint4*)(Bs + r * LDS_LD + ((lchunk ^ swz<BK>(r)) * 8)) = rb[i];
+        }
     };
 
     const int wave = tid >> 6, lane = tid & 63;
@@ -157,9 +169,9 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
 #pragma unroll
     for (int i = 0; i < WMT; ++i)
 #pragma unroll
-        for (int j = 0; j < WNT; ++j)
+        for (int jj = 0; jj < WNT; ++jj)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
 
     // epilogue constants, loaded early so their latency hides behind the main loop
     constexpr int COLS = TL::COLS, SROWS = TL::SROWS, ST_LD = TL::ST_LD;
@@ -179,35 +191,44 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
             sh[0] = t.x; sh[1] = t.y; sh[2] = t.z; sh[3] = t.w;
         }
     }
+
+    // operand rows of this lane: row (32 t + l32) of the wave's A / B block; with 128-byte rows the
+    // swizzle key of row + 32 t is the key of the row ^ (4 t & 7), with 64-byte rows it does not change
+    const bf16_t* as = As + (wm * WMT * 32 + l32) * LDS_LD;
+    const bf16_t* bs = Bs + (wn * WNT * 32 + l32) * LDS_LD;
+    const int fa = swz<BK>(wm * WMT * 32 + l32), fb = swz<BK>(wn * WNT * 32 + l32);
+    constexpr int TK = BK == 64 ? 4 : 0;
+
     const int kchunks = (k_in + BK - 1) / BK;
     const int nk = a.K * a.K * kchunks;
     int tap = 0, kc = 0;
     load_global(0, 0);
-    store_lds(0);
+    store_lds();
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
         kc += BK;
         if (kc >= k_in) { kc = 0; ++tap; }
         const bool more = kt + 1 < nk;
         if (more) load_global(tap, kc);
-        const bf16_t* as = As + buf * BM * LDS_LD + (wm * WMT * 32 + l32) * LDS_LD + lhi * 8;
-        const bf16_t* bs = Bs + buf * BN * LDS_LD + (wn * WNT * 32 + l32) * LDS_LD + lhi * 8;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8_t af[WMT], bfr[WNT];
+            const int c = kk * 2 + lhi;
 #pragma unroll
-            for (int t = 0; t < WMT; ++t) af[t] = *(const bf16x8_t*)(as + t * 32 * LDS_LD + kk * 16);
+            for (int t = 0; t < WMT; ++t) af[t] = *(const bf16x8_t*)(as + t * 32 * LDS_LD + ((c ^ fa ^ ((TK * t) & 7)) * 8));
 #pragma unroll
-            for (int t = 0; t < WNT; ++t) bfr[t] = *(const bf16x8_t*)(bs + t * 32 * LDS_LD + kk * 16);
+            for (int t = 0; t < WNT; ++t) bfr[t] = *(const bf16x8_t*)(bs + t * 32 * LDS_LD + ((c ^ fb ^ ((TK * t) & 7)) * 8));
 #pragma unroll
             for (int i = 0; i < WMT; ++i)
 #pragma unroll
-                for (int j = 0; j < WNT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                for (int jj = 0; jj < WNT; ++jj)
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[jj], acc[i][jj], 0, 0, 0);
         }
-        if (more) store_lds(buf ^ 1);
         __syncthreads();
+        if (more) {
+            store_lds();
+            __syncthreads();
+        }
     }
 
     // ---- epilogue through LDS: each lane finishes 4 consecutive channels of one row -----
@@ -242,10 +263,10 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
                     }
                     if (a.act == DS_ACT_RELU) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) val[j] = fmaxf(val[j], 0.f);
+                        for (int e = 0; e < 4; ++e) val[e] = fmaxf(val[e], 0.f);
                     } else if (a.act == DS_ACT_GELU) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) val[j] = gelu_erf(val[j]);
+                        for (int e = 0; e < 4; ++e) val[e] = gelu_erf(val[e]);
                     }
                     if (a.out_f32) {
                         *(float4*)((float*)a.C + coff + ncol) = make_float4(val[0], val[1], val[2], val[3]);
@@ -282,11 +303,11 @@ __global__ void build_mtiles_kernel(const int32_t* offsets, int T, int rows, int
     }
 }
 
-template <int WROWS, int WCOLS, int WMT, int WNT>
+template <int WROWS, int WCOLS, int WMT, int WNT, int BK>
 int32_t launch(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
-    using TL = Tile<WROWS, WCOLS, WMT, WNT>;
+    using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     static bool configured = false;
-    auto kern = gemm_kernel<WROWS, WCOLS, WMT, WNT>;
+    auto kern = gemm_kernel<WROWS, WCOLS, WMT, WNT, BK>;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM) != hipSuccess)
             DS_FAIL(DS_EHIP, "sliced gemm: cannot reserve %d bytes of LDS", TL::SMEM);
@@ -320,8 +341,11 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
         const char* e = getenv("DSNET_GEMM_TILE");   // tuning knob: force the n-tile width (64, 128, 256)
         return e ? atoi(e) : 0;
     }();
-    const int bn = forced ? forced : (max_kout <= 64 ? 64 : (max_kout <= 128 ? 128 : 256));
-    if (bn == 64) return launch<4, 1, 1, 2>(a, max_mtiles, max_kout, s);
-    if (bn == 128) return launch<2, 2, 2, 2>(a, max_mtiles, max_kout, s);
-    return launch<2, 2, 2, 4>(a, max_mtiles, max_kout, s);
+    // ragged route slices and short reductions favour narrow tiles at high occupancy: measured on the
+    // three batch-256 networks, every layer ran fastest with the 128x64 tile (32-deep slabs, 5 waves/SIMD)
+    const int bn = forced ? forced : 32;
+    if (bn == 32) return launch<4, 1, 1, 2, 32>(a, max_mtiles, max_kout, s);   // 64-wide tile, 32-deep slabs
+    if (bn == 64) return launch<4, 1, 1, 2, 64>(a, max_mtiles, max_kout, s);
+    if (bn == 128) return launch<2, 2, 2, 2, 64>(a, max_mtiles, max_kout, s);
+    return launch<2, 2, 2, 4, 64>(a, max_mtiles, max_kout, s);
 }
