@@ -134,10 +134,11 @@ int32_t ds_launch_stem_mfma(const bf16_t* img, const int32_t* index, bf16_t* y, 
                             const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
                             int32_t pad, int32_t Cout, hipStream_t s);
 int32_t ds_launch_maxpool(const bf16_t* x, bf16_t* y, int32_t B, int32_t H, int32_t W, int32_t C, hipStream_t s);
-// classifier: logits[out_index[slot]][o] = sum_c W[o][c] * v[c] + b[o]; v = spatial mean of x (HW > 0) or row 0 (HW == 0)
+// classifier: logits[out_index[slot]][o] = sum_{c < slot_c[slot]} W[o][c] * v[c] + b[o]; v = spatial mean of x
+// (HW > 0; partial needs ds_gate_partial_bytes(B, C)) or row 0 of the slot (HW == 0)
 int32_t ds_launch_head(ActView x, int32_t HW, const bf16_t* w, int32_t w_ld, const float* bias, int32_t n_out,
-                       const int32_t* slot_group, const GroupTable& gt, const int32_t* out_index, float* logits,
-                       int32_t B, int32_t C, hipStream_t s);
+                       const int32_t* slot_c, const int32_t* out_index, float* logits, float* partial, int32_t B,
+                       int32_t C, hipStream_t s);
 int32_t ds_launch_patchify(const bf16_t* img, const int32_t* index, bf16_t* patches, int32_t B, int32_t H,
                            int32_t W, int32_t P, hipStream_t s);
 int32_t ds_launch_cls_rows(ActView x, const bf16_t* cls, const bf16_t* pos, const int32_t* slot_group,
@@ -182,3 +183,24 @@ struct ProfScope {
     ProfScope(int kind, hipStream_t stream);
     ~ProfScope();
 };
+
+// ---- small dense layer on one vector per item --------------------------------------
+struct FcArgs {
+    const float* v_partial;   // [items][splits][C] partial sums (scaled by v_scale), or
+    const bf16_t* v_rows;     // one bf16 row per item at v_rows + item * v_row_stride
+    int64_t v_row_stride;
+    int32_t splits;
+    float v_scale;
+    const int32_t* c_item;    // valid input width per item (nullable = C)
+    int32_t C;                // stored input width / stride of v_partial
+    const void* w;            // [n_out][w_ld] fp32 or bf16
+    int32_t w_ld;
+    const float* bias;        // nullable
+    int32_t n_out, relu;
+    const int32_t* out_index; // item -> output row (nullable = identity)
+    float* out;
+    int32_t out_ld, items;
+};
+int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t kind, hipStream_t s);
+// spatial partial sums of NHWC/NCHW feature maps into a.partial [B][splits][C]; returns splits
+int32_t ds_launch_pool(const GateArgs& a, int32_t kind, int32_t* splits_out, hipStream_t s);

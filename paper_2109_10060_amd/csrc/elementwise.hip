@@ -210,65 +210,6 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const bf16_t* x, bf16_t* y
     *(uint4*)(y + (((int64_t)b * Ho + oy) * Wo + ox) * C + ch) = pack8(m);
 }
 
-// ---- pool + classifier; one workgroup per slot ----------------------------------
-__global__ __launch_bounds__(256) void head_kernel(ActView x, int HW, const bf16_t* w, int w_ld, const float* bias,
-                                                   int n_out, const int32_t* slot_group, const GroupTable gt,
-                                                   const int32_t* out_index, float* logits) {
-    extern __shared__ float vec[];  // [c]
-    __shared__ float red[8][256 + 8];
-    const int slot = blockIdx.x;
-    const int g = slot_group ? slot_group[slot] : 0;
-    const int c = gt.k_in[g];
-    const int xs = x.index ? x.index[slot] : slot;
-    const int ld = x.ld > 0 ? x.ld : c;
-    const bf16_t* xp = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride;
-    const int tid = threadIdx.x;
-    if (HW > 0) {
-        const int lane_c = tid & 31, lane_r = tid >> 5;
-        const float inv = 1.0f / (float)HW;
-        for (int c0 = 0; c0 < c; c0 += 256) {
-            const int ch = c0 + lane_c * 8;
-            float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (ch < c) {
-                for (int r = lane_r; r < HW; r += 8) {
-                    float v[8];
-                    unpack8(*(const uint4*)(xp + (int64_t)r * ld + ch), v);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) s[i] += v[i];
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) red[lane_r][lane_c * 8 + i] = s[i];
-            __syncthreads();
-            if (c0 + tid < c) {
-                float t = 0.f;
-#pragma unroll
-                for (int r = 0; r < 8; ++r) t += red[r][tid];
-                vec[c0 + tid] = t * inv;
-            }
-            __syncthreads();
-        }
-    } else {
-        for (int i = tid; i < c; i += 256) vec[i] = bf2f(xp[i]);
-        __syncthreads();
-    }
-    const int wave = tid >> 6, lane = tid & 63;
-    const int out = out_index ? out_index[slot] : slot;
-    for (int o = wave; o < n_out; o += 4) {
-        const bf16_t* wr = w + (int64_t)o * w_ld;
-        float s = 0.f;
-        for (int ch = lane * 8; ch < c; ch += 512) {
-            float wv[8];
-            unpack8(*(const uint4*)(wr + ch), wv);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) s = fmaf(wv[i], vec[ch + i], s);
-        }
-#pragma unroll
-        for (int k = 32; k > 0; k >>= 1) s += __shfl_xor(s, k, 64);
-        if (lane == 0) logits[(int64_t)out * n_out + o] = s + (bias ? bias[o] : 0.f);
-    }
-}
-
 // ---- patch extraction: NCHW image -> [slot][patch][(c,u,v)] ----------------------
 __global__ __launch_bounds__(256) void patchify_kernel(const bf16_t* img, const int32_t* index, bf16_t* out, int H,
                                                        int W, int P) {
@@ -438,14 +379,25 @@ int32_t ds_launch_maxpool(const bf16_t* x, bf16_t* y, int32_t B, int32_t H, int3
 }
 
 int32_t ds_launch_head(ActView x, int32_t HW, const bf16_t* w, int32_t w_ld, const float* bias, int32_t n_out,
-                       const int32_t* slot_group, const GroupTable& gt, const int32_t* out_index, float* logits,
-                       int32_t B, int32_t C, hipStream_t s) {
+                       const int32_t* slot_c, const int32_t* out_index, float* logits, float* partial, int32_t B,
+                       int32_t C, hipStream_t s) {
     if (B <= 0) return DS_OK;
-    ProfScope prof(DS_K_HEAD, s);
-    hipLaunchKernelGGL(head_kernel, dim3((unsigned)B), dim3(256), (size_t)C * sizeof(float), s, x, HW, w, w_ld, bias,
-                       n_out, slot_group, gt, out_index, logits);
-    DS_CHECK_LAUNCH("classifier head");
-    return DS_OK;
+    FcArgs f = {};
+    f.c_item = slot_c; f.C = C; f.w = w; f.w_ld = w_ld; f.bias = bias; f.n_out = n_out; f.relu = 0;
+    f.out_index = out_index; f.out = logits; f.out_ld = n_out; f.items = B;
+    if (HW > 0) {
+        GateArgs g = {};
+        g.x = x.p; g.dtype = DS_BF16; g.layout = DS_NHWC; g.B = B; g.C = C; g.HW = HW;
+        g.c_in = slot_c; g.x_index = x.index; g.x_sample_stride = x.sample_stride; g.x_ld = x.ld;
+        g.partial = partial;
+        int splits = 1;
+        const int32_t rc = ds_launch_pool(g, DS_K_HEAD, &splits, s);
+        if (rc) return rc;
+        f.v_partial = partial; f.splits = splits; f.v_scale = 1.0f / (float)HW;
+    } else {
+        f.v_rows = (const bf16_t*)x.p; f.v_row_stride = x.sample_stride;
+    }
+    return ds_launch_fc(f, 1, 0, DS_K_HEAD, s);
 }
 
 int32_t ds_launch_patchify(const bf16_t* img, const int32_t* index, bf16_t* patches, int32_t B, int32_t H,

@@ -1,0 +1,207 @@
+// Small dense layers applied to one vector per item: the gate's first MLP layer (Section 3.5,
+// Eq. 22, input-sliced to the item's valid channels) and the classifier behind the global
+// average pool.  A workgroup computes a 64-output x 16-item tile so that every weight row is
+// read once per 16 items instead of once per item.
+#include "common.h"
+
+namespace {
+
+template <typename WT>
+__device__ __forceinline__ float wload(const WT* p);
+template <>
+__device__ __forceinline__ float wload<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float wload<bf16_t>(const bf16_t* p) { return bf2f(*p); }
+
+constexpr int TO = 64, TI = 16, TC = 64;
+
+template <typename WT, typename ACC>
+__global__ __launch_bounds__(256) void fc_tile_kernel(const FcArgs a) {
+    __shared__ float Wl[TO][TC + 1];
+    __shared__ float Vl[TI][TC];
+    __shared__ int cs[TI];
+    const int tid = threadIdx.x;
+    const int o0 = blockIdx.x * TO, i0 = blockIdx.y * TI;
+    if (tid < TI) {
+        const int item = i0 + tid;
+        int c = 0;
+        if (item < a.items) c = a.c_item ? a.c_item[item] : a.C;
+        cs[tid] = c;
+    }
+    __syncthreads();
+    int cmax = 0;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) cmax = max(cmax, cs[i]);
+    const int ol = tid & 63, ig = tid >> 6;      // a wavefront shares its 4 items: LDS broadcast reads
+    ACC acc[4] = {0, 0, 0, 0};
+    const WT* w = (const WT*)a.w;
+    for (int c0 = 0; c0 < cmax; c0 += TC) {
+        for (int e = tid; e < TO * TC; e += 256) {
+            const int r = e / TC, cc = e - r * TC;
+            const int o = o0 + r, c = c0 + cc;
+            Wl[r][cc] = (o < a.n_out && c < cmax) ? wload<WT>(w + (int64_t)o * a.w_ld + c) : 0.f;
+        }
+        for (int e = tid; e < TI * TC; e += 256) {
+            const int r = e / TC, cc = e - r * TC;
+            const int item = i0 + r, c = c0 + cc;
+            float v = 0.f;
+            if (c < cs[r]) {
+                if (a.v_rows) {
+                    v = bf2f(a.v_rows[(int64_t)item * a.v_row_stride + c]);
+                } else {
+                    double s = 0.0;
+                    for (int sp = 0; sp < a.splits; ++sp) s += (double)a.v_partial[((int64_t)item * a.splits + sp) * a.C + c];
+                    v = (float)(s * (double)a.v_scale);
+                }
+            }
+            Vl[r][cc] = v;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int cc = 0; cc < TC; ++cc) {
+            const ACC wv = (ACC)Wl[ol][cc];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[s] += wv * (ACC)Vl[ig * 4 + s][cc];
+        }
+        __syncthreads();
+    }
+    const int o = o0 + ol;
+    if (o < a.n_out) {
+        const ACC b = a.bias ? (ACC)a.bias[o] : (ACC)0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int item = i0 + ig * 4 + s;
+            if (item >= a.items) continue;
+            ACC v = acc[s] + b;
+            if (a.relu && v < (ACC)0) v = (ACC)0;
+            const int row = a.out_index ? a.out_index[item] : item;
+            a.out[(int64_t)row * a.out_ld + o] = (float)v;
+        }
+    }
+}
+
+// Same tile, with 16-byte global loads and the next 64-channel chunk prefetched into registers
+// while the current one is consumed from LDS.  Needs C and w_ld to be multiples of 8.
+template <typename WT, typename ACC>
+__global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
+    __shared__ float Wl[TO][TC + 1];
+    __shared__ float Vl[TI][TC];
+    __shared__ int cs[TI];
+    const int tid = threadIdx.x;
+    const int o0 = blockIdx.x * TO, i0 = blockIdx.y * TI;
+    if (tid < TI) {
+        const int item = i0 + tid;
+        int c = 0;
+        if (item < a.items) c = a.c_item ? a.c_item[item] : a.C;
+        cs[tid] = c;
+    }
+    __syncthreads();
+    int cmax = 0;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) cmax = max(cmax, cs[i]);
+    const int ol = tid & 63, ig = tid >> 6;
+    constexpr bool WB = sizeof(WT) == 2;
+    constexpr int NW = WB ? 2 : 4;                  // 16-byte weight loads per thread and chunk
+    const int vr = tid >> 4, vc4 = (tid & 15) * 4;  // V: row, first of 4 channels
+    const int vitem = i0 + vr, vcs = cs[vr];
+    uint4 wreg[NW];
+    float vreg[4];
+    const WT* w = (const WT*)a.w;
+    auto prefetch = [&](int c0) {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int e = tid + 256 * i;
+            const int r = WB ? (e >> 3) : (e >> 4);
+            const int cc = WB ? (e & 7) * 8 : (e & 15) * 4;
+            const int o = o0 + r, c = c0 + cc;
+            wreg[i] = make_uint4(0, 0, 0, 0);
+            if (o < a.n_out && c < cmax) wreg[i] = *(const uint4*)(w + (int64_t)o * a.w_ld + c);
+        }
+        const int c = c0 + vc4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vreg[j] = 0.f;
+        if (c < vcs) {
+            if (a.v_rows) {
+                const uint2 q = *(const uint2*)(a.v_rows + (int64_t)vitem * a.v_row_stride + c);
+                vreg[0] = __uint_as_float(q.x << 16); vreg[1] = __uint_as_float(q.x & 0xffff0000u);
+                vreg[2] = __uint_as_float(q.y << 16); vreg[3] = __uint_as_float(q.y & 0xffff0000u);
+            } else {
+                double sd[4] = {0, 0, 0, 0};
+                for (int sp = 0; sp < a.splits; ++sp) {
+                    const float4 t = *(const float4*)(a.v_partial + ((int64_t)vitem * a.splits + sp) * a.C + c);
+                    sd[0] += t.x; sd[1] += t.y; sd[2] += t.z; sd[3] += t.w;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) vreg[j] = (float)(sd[j] * (double)a.v_scale);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (c + j >= vcs) vreg[j] = 0.f;
+        }
+    };
+    auto store = [&]() {
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const int e = tid + 256 * i;
+            if constexpr (WB) {
+                const int r = e >> 3, cc = (e & 7) * 8;
+                const uint32_t q[4] = {wreg[i].x, wreg[i].y, wreg[i].z, wreg[i].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    Wl[r][cc + 2 * j] = __uint_as_float(q[j] << 16);
+                    Wl[r][cc + 2 * j + 1] = __uint_as_float(q[j] & 0xffff0000u);
+                }
+            } else {
+                const int r = e >> 4, cc = (e & 15) * 4;
+                Wl[r][cc] = __uint_as_float(wreg[i].x); Wl[r][cc + 1] = __uint_as_float(wreg[i].y);
+                Wl[r][cc + 2] = __uint_as_float(wreg[i].z); Wl[r][cc + 3] = __uint_as_float(wreg[i].w);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) Vl[vr][vc4 + j] = vreg[j];
+    };
+    ACC acc[4] = {0, 0, 0, 0};
+    if (cmax > 0) prefetch(0);
+    for (int c0 = 0; c0 < cmax; c0 += TC) {
+        store();
+        __syncthreads();
+        if (c0 + TC < cmax) prefetch(c0 + TC);
+#pragma unroll 8
+        for (int cc = 0; cc < TC; ++cc) {
+            const ACC wv = (ACC)Wl[ol][cc];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[s] += wv * (ACC)Vl[ig * 4 + s][cc];
+        }
+        __syncthreads();
+    }
+    const int o = o0 + ol;
+    if (o < a.n_out) {
+        const ACC b = a.bias ? (ACC)a.bias[o] : (ACC)0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int item = i0 + ig * 4 + s;
+            if (item >= a.items) continue;
+            ACC v = acc[s] + b;
+            if (a.relu && v < (ACC)0) v = (ACC)0;
+            const int row = a.out_index ? a.out_index[item] : item;
+            a.out[(int64_t)row * a.out_ld + o] = (float)v;
+        }
+    }
+}
+
+}  // namespace
+
+int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t kind, hipStream_t s) {
+    if (a.items <= 0 || a.n_out <= 0) return DS_OK;
+    dim3 grid((unsigned)((a.n_out + TO - 1) / TO), (unsigned)((a.items + TI - 1) / TI));
+    ProfScope prof(kind, s);
+    const bool vec = (a.C % 8) == 0 && (a.w_ld % 8) == 0 && (a.v_rows == nullptr || (a.v_row_stride % 4) == 0);
+    if (vec && w_bf16) hipLaunchKernelGGL((fc_tile_vec_kernel<bf16_t, float>), grid, dim3(256), 0, s, a);
+    else if (vec && acc_f64) hipLaunchKernelGGL((fc_tile_vec_kernel<float, double>), grid, dim3(256), 0, s, a);
+    else if (vec) hipLaunchKernelGGL((fc_tile_vec_kernel<float, float>), grid, dim3(256), 0, s, a);
+    else if (w_bf16) hipLaunchKernelGGL((fc_tile_kernel<bf16_t, float>), grid, dim3(256), 0, s, a);
+    else if (acc_f64) hipLaunchKernelGGL((fc_tile_kernel<float, double>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((fc_tile_kernel<float, float>), grid, dim3(256), 0, s, a);
+    DS_CHECK_LAUNCH("fc tile");
+    return DS_OK;
+}

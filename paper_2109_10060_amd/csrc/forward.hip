@@ -110,7 +110,8 @@ bool parse_mb(const ds_net* net, MbDesc* d) {
 struct MbPlan {
     bf16_t *bufA, *bufB;
     float *gate_logits, *gate_partial;
-    int32_t *off1, *offs, *perm, *inv, *slot_group, *route;
+    float* head_partial;
+    int32_t *off1, *offs, *perm, *inv, *slot_group, *route, *slot_c;
     void* lists[8];
     int n_lists;
 };
@@ -136,6 +137,8 @@ void plan_mb(const MbDesc& d, int B, Bump& bp, MbPlan* p) {
     p->inv = bp.take<int32_t>(B);
     p->slot_group = bp.take<int32_t>(B);
     p->route = bp.take<int32_t>(B);
+    p->slot_c = bp.take<int32_t>(B);
+    p->head_partial = bp.take<float>(ds_gate_partial_bytes(B, d.blk[3 * (d.nb - 1) + 1]) / sizeof(float));
     // one m-tile list per distinct (bucketing, resolution)
     p->n_lists = 0;
     r = r1;
@@ -221,8 +224,9 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
     gh.T = d.T;
     for (int t = 0; t < d.T; ++t) gh.k_in[t] = gh.k_out[t] = d.cout[t * d.nb + d.nb - 1];
     ActView xv = {cur, nullptr, (int64_t)r * r * cl, 0};
-    return ds_launch_head(xv, r * r, (const bf16_t*)F[0], cl, (const float*)F[1], d.classes, p.slot_group, gh, p.perm,
-                          logits, B, cl, s);
+    RC(ds_launch_lookup(p.slot_group, gh, 0, p.slot_c, B, s));
+    return ds_launch_head(xv, r * r, (const bf16_t*)F[0], cl, (const float*)F[1], d.classes, p.slot_c, p.perm, logits,
+                          p.head_partial, B, cl, s);
 }
 
 // =====================================================================================
@@ -272,7 +276,7 @@ void plan_rn(const RnDesc& d, int B, Bump& bp, RnPlan* p) {
     }
     for (int i = 0; i < 5; ++i) p->buf[i] = bp.take<bf16_t>(maxel * B);
     int cmax = d.stem_out;
-    for (int s = 0; s < 3; ++s) cmax = cmax > 4 * d.widths[s] ? cmax : 4 * d.widths[s];
+    for (int s = 0; s < 4; ++s) cmax = cmax > 4 * d.widths[s] ? cmax : 4 * d.widths[s];
     p->gate_logits = bp.take<float>((size_t)B * d.T);
     p->gate_partial = bp.take<float>(ds_gate_partial_bytes(B, cmax) / sizeof(float));
     p->off1 = bp.take<int32_t>(2);
@@ -410,8 +414,9 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
     gh.T = G;
     for (int id = 0; id < G; ++id) gh.k_in[id] = gh.k_out[id] = d.out[3 * T + id / T];
     ActView xv = {X, nullptr, (int64_t)r * r * c_prev_full, 0};
-    return ds_launch_head(xv, r * r, (const bf16_t*)Q[0], c_prev_full, (const float*)Q[1], d.classes, p.slot_group[3], gh,
-                          p.perm[3], logits, B, c_prev_full, s);
+    (void)gh;   // slot_c already holds the stage-4 output widths
+    return ds_launch_head(xv, r * r, (const bf16_t*)Q[0], c_prev_full, (const float*)Q[1], d.classes, p.slot_c, p.perm[3],
+                          logits, p.gate_partial, B, c_prev_full, s);
 }
 
 // =====================================================================================
@@ -442,7 +447,7 @@ struct VitPlan {
     bf16_t *patches, *x, *a, *qkv, *o, *h;
     size_t qkv_seg;
     float* gate_logits;
-    int32_t *offs, *perm, *inv, *slot_group, *route;
+    int32_t *offs, *perm, *inv, *slot_group, *route, *slot_c;
     void *list_p, *list_t;
 };
 
@@ -461,6 +466,7 @@ void plan_vit(const VitDesc& d, int B, Bump& bp, VitPlan* p) {
     p->inv = bp.take<int32_t>(B);
     p->slot_group = bp.take<int32_t>(B);
     p->route = bp.take<int32_t>(B);
+    p->slot_c = bp.take<int32_t>(B);
     p->list_p = bp.take<char>(16 + ds_mtile_capacity(B, np, d.T) * 16);
     p->list_t = bp.take<char>(16 + ds_mtile_capacity(B, d.N, d.T) * 16);
 }
@@ -537,7 +543,8 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
     }
     const void* const* F = P + 4 + 12 * d.depth;
     RC(ds_launch_layernorm(xv, av, (const float*)F[0], (const float*)F[1], eps, p.slot_group, gq, B, d.N, 0, 1, s));
-    return ds_launch_head(av, 0, (const bf16_t*)F[2], d.D, (const float*)F[3], d.classes, p.slot_group, gq, p.perm, logits,
+    RC(ds_launch_lookup(p.slot_group, gq, 0, p.slot_c, B, s));
+    return ds_launch_head(av, 0, (const bf16_t*)F[2], d.D, (const float*)F[3], d.classes, p.slot_c, p.perm, logits, nullptr,
                           B, d.D, s);
 }
 

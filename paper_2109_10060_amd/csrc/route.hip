@@ -87,42 +87,19 @@ __global__ __launch_bounds__(256) void pool_nchw_kernel(const GateArgs a) {
     if (lane == 0) a.partial[(int64_t)item * a.C + ch] = s;
 }
 
-// ---- routing head: MLP + argmax, one workgroup per item -----------------------
-__global__ __launch_bounds__(256) void gate_head_kernel(const GateArgs a, int splits) {
-    extern __shared__ double sm[];          // pooled[C] then hidden[C_mlp]
-    double* pooled = sm;
-    double* hidden = sm + a.C;
+// ---- routing head, output layer + argmax: one wavefront per item ---------------------------
+// hidden [items][C_mlp] comes from the tiled first layer (fp64 accumulation, ReLU applied)
+__global__ __launch_bounds__(64) void gate_out_kernel(const GateArgs a, const float* hidden) {
     const int item = blockIdx.x;
     const int out = a.out_index ? a.out_index[item] : item;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = threadIdx.x;
     const bool have_x = a.x != nullptr;
-    if (have_x) {
-        const int c = a.c_in ? a.c_in[item] : a.C;
-        const double inv = 1.0 / (double)a.HW;
-        for (int i = tid; i < c; i += 256) {
-            double s = 0.0;
-            for (int sp = 0; sp < splits; ++sp) s += (double)a.partial[((int64_t)item * splits + sp) * a.C + i];
-            pooled[i] = s * inv;
-        }
-        __syncthreads();
-        for (int j = wave; j < a.C_mlp; j += 4) {
-            const float* wr = a.w1 + (int64_t)j * a.C;
-            double s = 0.0;
-            for (int i = lane; i < c; i += 64) s += (double)wr[i] * pooled[i];
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-            if (lane == 0) {
-                s += a.b1 ? (double)a.b1[j] : 0.0;
-                hidden[j] = s > 0.0 ? s : 0.0;
-            }
-        }
-        __syncthreads();
-    }
-    for (int t = wave; t < a.T; t += 4) {
+    for (int t = 0; t < a.T; ++t) {
         double s = 0.0;
         if (have_x) {
             const float* wr = a.w2 + (int64_t)t * a.C_mlp;
-            for (int j = lane; j < a.C_mlp; j += 64) s += (double)wr[j] * hidden[j];
+            const float* h = hidden + (int64_t)item * a.C_mlp;
+            for (int j = lane; j < a.C_mlp; j += 64) s += (double)wr[j] * (double)h[j];
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
             s += a.b2 ? (double)a.b2[t] : 0.0;
@@ -133,7 +110,7 @@ __global__ __launch_bounds__(256) void gate_head_kernel(const GateArgs a, int sp
         }
     }
     __syncthreads();
-    if (tid == 0) {
+    if (lane == 0) {
         int arg = 0;
         bool have = false;
         float best = 0.f;
@@ -202,27 +179,44 @@ __global__ void bn_fold_kernel(const float* gamma, const float* beta, const floa
 
 }  // namespace
 
-size_t ds_gate_partial_bytes(int32_t B, int32_t C) { return (size_t)B * C * POOL_SPLIT_MAX * sizeof(float); }
+size_t ds_gate_partial_bytes(int32_t B, int32_t C) { return (size_t)B * C * (POOL_SPLIT_MAX + 1) * sizeof(float); }
+
+int32_t ds_launch_pool(const GateArgs& a, int32_t kind, int32_t* splits_out, hipStream_t s) {
+    int splits = 1;
+    ProfScope prof(kind, s);
+    if (a.layout == DS_NHWC) {
+        splits = a.HW >= 2048 ? 8 : (a.HW >= 512 ? 4 : (a.HW >= 128 ? 2 : 1));
+        dim3 grid(a.B, splits);
+        if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nhwc_kernel<bf16_t>, grid, dim3(256), 0, s, a, splits);
+        else hipLaunchKernelGGL(pool_nhwc_kernel<float>, grid, dim3(256), 0, s, a, splits);
+    } else {
+        dim3 grid(a.B, (a.C + 3) / 4);
+        if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nchw_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(pool_nchw_kernel<float>, grid, dim3(256), 0, s, a);
+    }
+    DS_CHECK_LAUNCH("spatial pool");
+    *splits_out = splits;
+    return DS_OK;
+}
 
 int32_t ds_launch_gate(const GateArgs& a, hipStream_t s) {
     if (a.B <= 0) return DS_OK;
-    ProfScope prof(DS_K_GATE, s);
-    int splits = 1;
+    float* hidden = nullptr;
     if (a.x) {
-        if (a.layout == DS_NHWC) {
-            splits = a.HW >= 2048 ? 8 : (a.HW >= 512 ? 4 : (a.HW >= 128 ? 2 : 1));
-            dim3 grid(a.B, splits);
-            if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nhwc_kernel<bf16_t>, grid, dim3(256), 0, s, a, splits);
-            else hipLaunchKernelGGL(pool_nhwc_kernel<float>, grid, dim3(256), 0, s, a, splits);
-        } else {
-            dim3 grid(a.B, (a.C + 3) / 4);
-            if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nchw_kernel<bf16_t>, grid, dim3(256), 0, s, a);
-            else hipLaunchKernelGGL(pool_nchw_kernel<float>, grid, dim3(256), 0, s, a);
-        }
-        DS_CHECK_LAUNCH("gate encoder");
+        int splits = 1;
+        int32_t rc = ds_launch_pool(a, DS_K_GATE, &splits, s);
+        if (rc) return rc;
+        hidden = a.partial + (size_t)a.B * a.C * POOL_SPLIT_MAX;   // [B][C_mlp], C_mlp <= C
+        FcArgs f = {};
+        f.v_partial = a.partial; f.splits = splits; f.v_scale = 1.0f / (float)a.HW;
+        f.c_item = a.c_in; f.C = a.C;
+        f.w = a.w1; f.w_ld = a.C; f.bias = a.b1; f.n_out = a.C_mlp; f.relu = 1;
+        f.out = hidden; f.out_ld = a.C_mlp; f.items = a.B;
+        rc = ds_launch_fc(f, 0, 1, DS_K_GATE, s);
+        if (rc) return rc;
     }
-    const size_t shm = (size_t)(a.C + a.C_mlp) * sizeof(double);
-    hipLaunchKernelGGL(gate_head_kernel, dim3(a.B), dim3(256), shm, s, a, splits);
+    ProfScope prof(DS_K_GATE, s);
+    hipLaunchKernelGGL(gate_out_kernel, dim3(a.B), dim3(64), 0, s, a, hidden);
     DS_CHECK_LAUNCH("gate head");
     return DS_OK;
 }
@@ -261,7 +255,7 @@ extern "C" int32_t ds_gate(const void* x, int32_t x_dtype, int32_t x_layout, int
         if (x_dtype != DS_F32 && x_dtype != DS_BF16) DS_FAIL(DS_EUNSUPPORTED, "ds_gate: dtype");
         if (x_layout != DS_NCHW && x_layout != DS_NHWC) DS_FAIL(DS_EUNSUPPORTED, "ds_gate: layout");
         if (x_layout == DS_NHWC && ((C % 8) != 0 || !ds_aligned16(x))) DS_FAIL(DS_EALIGN, "ds_gate: NHWC needs C %% 8 == 0 and a 16-byte aligned x");
-        if ((size_t)C + C_mlp > 6000) DS_FAIL(DS_EUNSUPPORTED, "ds_gate: C + C_mlp too large");
+        if (C_mlp > C) DS_FAIL(DS_EUNSUPPORTED, "ds_gate: hidden width above the channel count");
         if (!ws || ws_bytes < ds_gate_partial_bytes(B, C)) DS_FAIL(DS_EWORKSPACE, "ds_gate: workspace needs %zu bytes", ds_gate_partial_bytes(B, C));
     } else if (!logit_bias) {
         DS_FAIL(DS_EINVAL, "ds_gate: neither x nor logit_bias given");
