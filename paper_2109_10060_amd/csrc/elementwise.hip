@@ -81,6 +81,76 @@ __global__ __launch_bounds__(256) void dwconv_kernel(ActView x, ActView y, const
     *(uint4*)((bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)pix * yld + ch) = pack8(acc);
 }
 
+// Same layer, 4 consecutive output pixels of a row per thread: the 3 x (3 + 3 STRIDE) input window
+// and the 9 filter chunks are loaded once for 4 outputs, which cuts the load instructions per
+// output from 18 to 6.75 (stride 1) / 9 (stride 2); the kernel is bound by load issue, not HBM.
+// grid (ceil(Ho * ceil(Wo/4) * C/8 / 256), B)
+template <int STRIDE>
+__global__ __launch_bounds__(256) void dwconv4_kernel(ActView x, ActView y, const bf16_t* w, const float* scale,
+                                                      const float* shift, int tab_ld, const int32_t* slot_group,
+                                                      const GroupTable gt, int C, int H, int W, int Ho, int Wo,
+                                                      int act) {
+    constexpr int PX = 4, NCOL = (PX - 1) * STRIDE + 3;
+    const int slot = blockIdx.y;
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int c = gt.k_in[g];
+    const int chunks = c >> 3;
+    const int xgroups = (Wo + PX - 1) / PX;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= Ho * xgroups * chunks) return;
+    const int pg = idx / chunks, ch = (idx - pg * chunks) * 8;
+    const int oy = pg / xgroups, ox0 = (pg - oy * xgroups) * PX;
+    const int xs = x.index ? x.index[slot] : slot;
+    const int ys = y.index ? y.index[slot] : slot;
+    const int xld = x.ld > 0 ? x.ld : c, yld = y.ld > 0 ? y.ld : c;
+    const bf16_t* xp = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride + ch;
+    float acc[PX][8];
+#pragma unroll
+    for (int p = 0; p < PX; ++p)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[p][i] = 0.f;
+    const int ix0 = ox0 * STRIDE - 1;
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+        const int iy = oy * STRIDE + u - 1;
+        if (iy < 0 || iy >= H) continue;
+        float wv[3][8];
+#pragma unroll
+        for (int v = 0; v < 3; ++v) unpack8(*(const uint4*)(w + (u * 3 + v) * C + ch), wv[v]);
+        const bf16_t* xr = xp + (int64_t)iy * W * xld;
+#pragma unroll
+        for (int col = 0; col < NCOL; ++col) {
+            const int ix = ix0 + col;
+            if (ix < 0 || ix >= W) continue;
+            float xv[8];
+            unpack8(*(const uint4*)(xr + (int64_t)ix * xld), xv);
+#pragma unroll
+            for (int p = 0; p < PX; ++p) {
+                const int v = col - p * STRIDE;      // filter column this input column meets for output p
+                if (v >= 0 && v < 3) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[p][i] = fmaf(xv[i], wv[v][i], acc[p][i]);
+                }
+            }
+        }
+    }
+    const int64_t ti = (int64_t)gt.row[g] * tab_ld + ch;
+    float sc[8], sh[8];
+    loadf8(scale + ti, sc);
+    loadf8(shift + ti, sh);
+    bf16_t* yp = (bf16_t*)y.p + (int64_t)ys * y.sample_stride + ((int64_t)oy * Wo + ox0) * yld + ch;
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+        if (ox0 + p >= Wo) break;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            acc[p][i] = acc[p][i] * sc[i] + sh[i];
+            if (act == DS_ACT_RELU) acc[p][i] = fmaxf(acc[p][i], 0.f);
+        }
+        *(uint4*)(yp + (int64_t)p * yld) = pack8(acc[p]);
+    }
+}
+
 // ---- LayerNorm over the valid slice; one wavefront per row ----------------------
 __global__ __launch_bounds__(256) void layernorm_kernel(ActView x, ActView y, const float* gamma,
                                                         const float* beta, float eps, const int32_t* slot_group,
@@ -328,12 +398,16 @@ int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* sca
     const int Ho = (H + 2 - 3) / stride + 1, Wo = (W + 2 - 3) / stride + 1;
     int cmax = 0;
     for (int t = 0; t < gt.T; ++t) cmax = gt.k_in[t] > cmax ? gt.k_in[t] : cmax;
-    const int64_t n = (int64_t)Ho * Wo * (cmax / 8);
+    const int64_t n = (int64_t)Ho * ((Wo + 3) / 4) * (cmax / 8);
     if (n <= 0) return DS_OK;
     dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
     ProfScope prof(DS_K_DWCONV, s);
-    hipLaunchKernelGGL(dwconv_kernel, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
-                       Ho, Wo, stride, act);
+    if (stride == 1)
+        hipLaunchKernelGGL(dwconv4_kernel<1>, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
+                           Ho, Wo, act);
+    else
+        hipLaunchKernelGGL(dwconv4_kernel<2>, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
+                           Ho, Wo, act);
     DS_CHECK_LAUNCH("depthwise conv");
     return DS_OK;
 }

@@ -50,22 +50,28 @@ struct Tile {
     static constexpr int LOOP_BYTES = (BM + BN) * LDS_LD * 2;
     static constexpr int STAGE_BYTES = 4 * SROWS * ST_LD * 4;
     static constexpr int MAIN_BYTES = LOOP_BYTES > STAGE_BYTES ? LOOP_BYTES : STAGE_BYTES;
-    static constexpr int TABLE_BYTES = BM * (8 + 8 + 8 + 8);
+    static constexpr int TABLE_BYTES = BM * (4 + 8 + 8 + 8);
     static constexpr int SMEM = MAIN_BYTES + TABLE_BYTES;
     static_assert(WROWS * WCOLS == 4 && WROWS * WMT * 32 == BM, "4 wavefronts cover a 128-row tile");
 };
 
-template <int WROWS, int WCOLS, int WMT, int WNT, int BK>
+template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV>
 __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     constexpr int BN = TL::BN, LDS_LD = BK, CPR = BK / 8, RPT = NT / CPR;   // chunks per row, rows per pass
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t* As = (bf16_t*)smem;                       // [BM][BK]
     bf16_t* Bs = As + BM * LDS_LD;                    // [BN][BK]
-    long long* rowA = (long long*)(smem + TL::MAIN_BYTES);
-    long long* rowC = rowA + BM;
+    long long* rowC = (long long*)(smem + TL::MAIN_BYTES);
     long long* rowR = rowC + BM;
     int2* rowYX = (int2*)(rowR + BM);
+    uint32_t* rowA = (uint32_t*)(rowYX + BM);
+    // operands are fetched with buffer loads: 32-bit byte offsets against a uniform base, and an
+    // offset beyond the descriptor's range returns zeros, which supplies every tail (rows beyond
+    // the group, channels beyond the slice, taps outside the image) without branches
+    constexpr uint32_t OOB = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.Wt, 0, 0x7fffffff, 0x00020000);
 
     // ---- work item ------------------------------------------------------------------
     // m-tiles are dealt to the 8 XCDs round-robin; on one XCD consecutive blocks walk the n-tiles
@@ -92,7 +98,8 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
     // ---- per-row table: where each of the 128 rows lives --------------------------------
     if (tid < BM) {
         const int m = grow0 + tid;
-        long long ra = -1, rc = -1, rr = 0;
+        long long rc = -1, rr = 0;
+        uint32_t ra = OOB;
         int2 yx = make_int2(0, 0);
         if (m < rows_g) {
             const int sl = m / a.rows;
@@ -101,7 +108,8 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
             const int sa = a.a_index ? a.a_index[slot] : slot;
             const int cs = a.c_index ? a.c_index[slot] : slot;
             const int oy = p / a.Wo, ox = p - oy * a.Wo;
-            ra = (long long)sa * a.a_sample_stride;
+            // byte offset of the sample (convolution) or of the row itself (linear layers)
+            ra = (uint32_t)(((long long)sa * a.a_sample_stride + (CONV ? 0 : (long long)p * a_ld)) * 2);
             yx = make_int2(oy * a.stride - a.pad, ox * a.stride - a.pad);
             const long long pc = p + a.c_row0;
             rc = (long long)cs * a.c_sample_stride + pc * c_ld + (long long)seg * a.c_seg_stride;
@@ -119,33 +127,46 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
     const int lchunk = tid % CPR;
     const int kc8 = lchunk * 8;
     const int lrow = tid / CPR;
-    long long abase[NA];
+    uint32_t aoff[NA], apix[NA], woff[NB];
     int2 ayx[NA];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        abase[i] = rowA[lrow + RPT * i];
+        aoff[i] = rowA[lrow + RPT * i];
         ayx[i] = rowYX[lrow + RPT * i];
+        apix[i] = aoff[i] == OOB ? OOB : aoff[i] + kc8 * 2;
     }
-    const long long wbase = (long long)seg * a.w_seg_stride + (long long)(n0 + lrow) * a.w_ld;
-    const long long wstep = RPT * a.w_ld;
-    const int wrows = k_out - n0 - lrow;              // B row i is valid while RPT i < wrows
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int n = n0 + lrow + RPT * i;
+        woff[i] = n < k_out ? (uint32_t)(((long long)seg * a.w_seg_stride + (long long)n * a.w_ld + kc8) * 2) : OOB;
+    }
+    // per filter tap: byte offset of the input pixel each owned row reads (OOB outside the image)
+    auto set_tap = [&](int tap) {
+        if constexpr (CONV) {
+            const int u = tap / a.K, v = tap - u * a.K;
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                const int iy = ayx[i].x + u, ix = ayx[i].y + v;
+                const bool ok = aoff[i] != OOB && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+                apix[i] = ok ? aoff[i] + (uint32_t)(((iy * a.W + ix) * a_ld + kc8) * 2) : OOB;
+            }
+        }
+    };
 
     uint4 ra[NA], rb[NB];
     auto load_global = [&](int tap, int kc) {
-        const int u = tap / a.K, v = tap - u * a.K;
         const bool kok = (kc + kc8) < k_in;
+        const int soff_a = kc * 2;
+        const int soff_w = (int)((tap * a.w_tap_stride + kc) * 2);
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            const int iy = ayx[i].x + u, ix = ayx[i].y + v;
-            const bool ok = abase[i] >= 0 && kok && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
-            ra[i] = make_uint4(0, 0, 0, 0);
-            if (ok) ra[i] = *(const uint4*)(a.A + abase[i] + (long long)(iy * a.W + ix) * a_ld + kc + kc8);
+            const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, (int)(kok ? apix[i] : OOB), soff_a, 0);
+            ra[i] = make_uint4(t[0], t[1], t[2], t[3]);
         }
-        const bf16_t* wp = a.Wt + wbase + (long long)tap * a.w_tap_stride + kc + kc8;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            rb[i] = make_uint4(0, 0, 0, 0);
-            if (RPT * i < wrows && kok) rb[i] = *(const uint4*)(wp + i * wstep);
+            const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)(kok ? woff[i] : OOB), soff_w, 0);
+            rb[i] = make_uint4(t[0], t[1], t[2], t[3]);
         }
     };
     auto store_lds = [&]() {
@@ -202,12 +223,17 @@ __global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny
     const int kchunks = (k_in + BK - 1) / BK;
     const int nk = a.K * a.K * kchunks;
     int tap = 0, kc = 0;
+    set_tap(0);
     load_global(0, 0);
     store_lds();
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         kc += BK;
-        if (kc >= k_in) { kc = 0; ++tap; }
+        if (kc >= k_in) {
+            kc = 0;
+            ++tap;
+            if (kt + 1 < nk) set_tap(tap);
+        }
         const bool more = kt + 1 < nk;
         if (more) load_global(tap, kc);
 #pragma unroll
@@ -303,11 +329,11 @@ __global__ void build_mtiles_kernel(const int32_t* offsets, int T, int rows, int
     }
 }
 
-template <int WROWS, int WCOLS, int WMT, int WNT, int BK>
+template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV>
 int32_t launch(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     static bool configured = false;
-    auto kern = gemm_kernel<WROWS, WCOLS, WMT, WNT, BK>;
+    auto kern = gemm_kernel<WROWS, WCOLS, WMT, WNT, BK, CONV>;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM) != hipSuccess)
             DS_FAIL(DS_EHIP, "sliced gemm: cannot reserve %d bytes of LDS", TL::SMEM);
@@ -344,8 +370,15 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     // ragged route slices and short reductions favour narrow tiles at high occupancy: measured on the
     // three batch-256 networks, every layer ran fastest with the 128x64 tile (32-deep slabs, 5 waves/SIMD)
     const int bn = forced ? forced : 32;
-    if (bn == 32) return launch<4, 1, 1, 2, 32>(a, max_mtiles, max_kout, s);   // 64-wide tile, 32-deep slabs
-    if (bn == 64) return launch<4, 1, 1, 2, 64>(a, max_mtiles, max_kout, s);
-    if (bn == 128) return launch<2, 2, 2, 2, 64>(a, max_mtiles, max_kout, s);
-    return launch<2, 2, 2, 4, 64>(a, max_mtiles, max_kout, s);
+    // 32-bit byte offsets inside the kernel: the operands must span less than 2 GiB
+    const long long slots = (long long)max_mtiles * BM / (a.rows > 0 ? a.rows : 1) + 1;
+    if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL)
+        DS_FAIL(DS_EUNSUPPORTED, "sliced gemm: activation tensor spans 2 GiB or more");
+    const bool conv = a.K > 1 || a.stride > 1 || a.pad > 0;
+#define DS_GEMM_DISPATCH(...) (conv ? launch<__VA_ARGS__, true>(a, max_mtiles, max_kout, s) : launch<__VA_ARGS__, false>(a, max_mtiles, max_kout, s))
+    if (bn == 32) return DS_GEMM_DISPATCH(4, 1, 1, 2, 32);   // 64-wide tile, 32-deep slabs
+    if (bn == 64) return DS_GEMM_DISPATCH(4, 1, 1, 2, 64);
+    if (bn == 128) return DS_GEMM_DISPATCH(2, 2, 2, 2, 64);
+    return DS_GEMM_DISPATCH(2, 2, 2, 4, 64);
+#undef DS_GEMM_DISPATCH
 }
