@@ -56,7 +56,7 @@ struct Tile {
 };
 
 template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV>
-__global__ __launch_bounds__(NT) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
+__global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? 6 : 1) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     constexpr int BN = TL::BN, LDS_LD = BK, CPR = BK / 8, RPT = NT / CPR;   // chunks per row, rows per pass
     extern __shared__ __attribute__((aligned(16))) char smem[];
