@@ -68,23 +68,26 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
                 sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kt], 0, 0, 0);
             }
         }
+        // softmax over the keys of this lane's query: p = 2^((s - max) * scale * log2(e)); the masked
+        // keys get -inf.  The scale is positive, so the maximum is taken on the raw scores.
         float m = -INFINITY;
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int key = kt * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
-                const float s = key < N ? sacc[kt][e] * scale : -INFINITY;
-                sacc[kt][e] = s;
-                m = fmaxf(m, s);
+                const float sv = key < N ? sacc[kt][e] : -INFINITY;
+                sacc[kt][e] = sv;
+                m = fmaxf(m, sv);
             }
         m = fmaxf(m, __shfl_xor(m, 32, 64));
+        const float c2 = scale * 1.44269504088896340736f, mc = m * c2;
         float sum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __expf(sacc[kt][e] - m);
+                const float p = exp2f(fmaf(sacc[kt][e], c2, -mc));
                 sacc[kt][e] = p;
                 sum += p;
             }
@@ -100,9 +103,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
         for (int kt = 0; kt < NKT; ++kt) {
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                union { uint16_t u[8]; bf16x8_t v; } pf;
+                union { uint32_t u[4]; bf16x8_t v; } pf;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf.u[e] = f2bf(sacc[kt][8 * half + e] * inv);
+                for (int e = 0; e < 4; ++e)
+                    pf.u[e] = f2bf2(sacc[kt][8 * half + 2 * e] * inv, sacc[kt][8 * half + 2 * e + 1] * inv);
 #pragma unroll
                 for (int dt = 0; dt < 2; ++dt) {
                     const bf16_t* vp = Vt + (dt * 32 + l32) * V_LD + kt * 32 + 16 * half + 4 * lhi;

@@ -20,7 +20,7 @@ __device__ __forceinline__ void unpack8(const uint4 q, float* v) {
 __device__ __forceinline__ uint4 pack8(const float* v) {
     uint32_t w[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) w[i] = f2bf2(v[2 * i], v[2 * i + 1]);
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 __device__ __forceinline__ void loadf8(const float* p, float* v) {
@@ -200,6 +200,66 @@ __global__ __launch_bounds__(256) void layernorm_kernel(ActView x, ActView y, co
     for (int k = 0; k < MAXC; ++k) {
         const int ch = (k * 64 + lane) * 8;
         if (ch < d) {
+            float gm[8], bt[8], o8[8];
+            loadf8(gamma + ch, gm);
+            loadf8(beta + ch, bt);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o8[i] = (v[k][i] - mu) * rstd * gm[i] + bt[i];
+            *(uint4*)(yr + ch) = pack8(o8);
+        }
+    }
+}
+
+// Narrow rows (d <= 512): 16 lanes per row, 4 rows per wavefront, so a wavefront keeps four
+// independent rows of loads in flight and the reductions take 4 exchange steps instead of 6.
+__global__ __launch_bounds__(256) void layernorm16_kernel(ActView x, ActView y, const float* gamma,
+                                                          const float* beta, float eps, const int32_t* slot_group,
+                                                          const GroupTable gt, int B, int row0, int n_rows) {
+    const int r = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int l16 = threadIdx.x & 15;
+    const bool live = r < B * n_rows;
+    const int rr = live ? r : 0;
+    const int slot = rr / n_rows, p = row0 + (rr - slot * n_rows);
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int d = gt.k_in[g];
+    const int xs = x.index ? x.index[slot] : slot, ys = y.index ? y.index[slot] : slot;
+    const int xld = x.ld > 0 ? x.ld : d, yld = y.ld > 0 ? y.ld : d;
+    const bf16_t* xr = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride + (int64_t)p * xld;
+    bf16_t* yr = (bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)p * yld;
+    constexpr int MAXC = 4;
+    float v[MAXC][8];
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        const int ch = (k * 16 + l16) * 8;
+        if (live && ch < d) {
+            unpack8(*(const uint4*)(xr + ch), v[k]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += v[k][i];
+        }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 16);
+    const float mu = s / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        const int ch = (k * 16 + l16) * 8;
+        if (live && ch < d) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float t = v[k][i] - mu;
+                q += t * t;
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) q += __shfl_xor(q, o, 16);
+    const float rstd = 1.0f / sqrtf(q / (float)d + eps);
+#pragma unroll
+    for (int k = 0; k < MAXC; ++k) {
+        const int ch = (k * 16 + l16) * 8;
+        if (live && ch < d) {
             float gm[8], bt[8], o8[8];
             loadf8(gamma + ch, gm);
             loadf8(beta + ch, bt);
@@ -418,6 +478,14 @@ int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const floa
     if (B <= 0 || n_rows <= 0) return DS_OK;
     const int64_t total = (int64_t)B * n_rows;
     ProfScope prof(DS_K_LAYERNORM, s);
+    int dmax = 0;
+    for (int t = 0; t < gt.T; ++t) dmax = gt.k_in[t] > dmax ? gt.k_in[t] : dmax;
+    if (dmax <= 512) {
+        hipLaunchKernelGGL(layernorm16_kernel, dim3((unsigned)((total + 15) / 16)), dim3(256), 0, s, x, y, gamma, beta, eps,
+                           slot_group, gt, B, row0, n_rows);
+        DS_CHECK_LAUNCH("layernorm");
+        return DS_OK;
+    }
     hipLaunchKernelGGL(layernorm_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, x, y, gamma, beta, eps,
                        slot_group, gt, B, rows, row0, n_rows);
     DS_CHECK_LAUNCH("layernorm");

@@ -298,8 +298,8 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? 6 : 1) 
                         *(float4*)((float*)a.C + coff + ncol) = make_float4(val[0], val[1], val[2], val[3]);
                     } else {
                         uint2 q;
-                        q.x = (uint32_t)f2bf(val[0]) | ((uint32_t)f2bf(val[1]) << 16);
-                        q.y = (uint32_t)f2bf(val[2]) | ((uint32_t)f2bf(val[3]) << 16);
+                        q.x = f2bf2(val[0], val[1]);
+                        q.y = f2bf2(val[2], val[3]);
                         *(uint2*)((bf16_t*)a.C + coff + ncol) = q;
                     }
                 }

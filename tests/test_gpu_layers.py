@@ -149,6 +149,22 @@ def test_sliced_linear_one_bucket_gets_everything_and_empty_batch(gpu_lib):
     assert y0.shape[0] == 0
 
 
+def test_bf16_storage_rounding_is_nearest_even_bit_exact(gpu_lib):
+    """With zero weights the layer stores bf16(bias): the storage rounding itself, ties included."""
+    K, N, B, rows = 32, 512, 2, 3
+    ulp = 2.0 ** -7
+    special = [1.0 + ulp / 2, 1.0 + 3 * ulp / 2, 1.0 + ulp / 2 + 2.0 ** -20, -(1.0 + ulp / 2), 3.0e-5, 1234.567, -0.3333333]
+    bias = (np.random.default_rng(3).standard_normal(N) * 3).astype(np.float32)
+    bias[:len(special)] = np.array(special, np.float32)
+    off = torch.tensor([0, B], dtype=torch.int32, device=DEV)
+    g = gpu_lib.make_groups(off, None, [K], [N])
+    x = torch.randn(B, rows, K, device=DEV).to(torch.bfloat16)
+    w = torch.zeros(N, K, dtype=torch.bfloat16, device=DEV)
+    y = gpu_lib.ds_sliced_linear(x, w, dev(bias), g)
+    want = O.bf16_round(bias.astype(np.float64))
+    assert np.array_equal(host(y)[1, 2], want)
+
+
 # ------------------------------------------------------------------ config 1: gate + sliced conv + split BN + ReLU, fp32
 def _config1_block(gpu_lib, c, forced=None):
     B, T = c["B"], c["T"]
