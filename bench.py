@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernel launches with HIP events (roofline is then null)")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class table to stderr")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of MIB mebibytes 5 times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
@@ -94,6 +96,15 @@ def main():
 
     ds.load()
     dev = "cuda:0"
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": n, "repeats": 5}))
+        return
     B = args.batch
     arch, params, imgs, lb, label = build_workload(args.workload, B)
     net = {"mbnet": ds.build_mbnet, "resnet": ds.build_resnet, "vit": ds.build_vit}[args.workload](arch, params, dev)

@@ -2,12 +2,12 @@
 // heads at or beyond the slot's head count exit at once.  Head dimension 64,
 // sequence length up to 224 (7 key tiles of 32).
 //
-// K and V^T of the head live in LDS.  Each wavefront takes 32-query tiles:
+// K and V^T of the head live in LDS.  One wavefront per 32-query tile (up to 7 per workgroup):
 //   S^T[key][q] = K . Q^T   (v_mfma_f32_32x32x16_bf16; A = K rows from LDS, B = Q rows from global)
 // so that one lane owns a fixed query column and half of its keys: the row
 // maximum and sum of the softmax are in-lane reductions plus one exchange with
 // lane^32.  The normalised probabilities are rounded to bf16 in registers and fed
-// straight back as the A operand of  O = P . V ; the key order an accumulator
+// straight back as the B operand of  O^T = V^T . P^T ; the key order an accumulator
 // holds (runs of 4 keys) is reproduced on the V^T side with two 8-byte LDS reads,
 // so no shuffle or LDS round trip of P is needed.
 #include "common.h"
@@ -16,7 +16,7 @@ namespace {
 
 constexpr int DH = 64, NKT = 7, KEYS = NKT * 32, K_LD = DH + 8, V_LD = KEYS + 8;
 
-__global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                         int64_t sample_stride, int ld, int o_ld,
                                                         int64_t o_sample_stride, const int32_t* slot_group,
@@ -29,7 +29,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)slot * sample_stride + head * DH;
 
-    for (int c = tid; c < KEYS * 8; c += 256) {
+    const int nthreads = blockDim.x;          // one wavefront per 32-query tile
+    for (int c = tid; c < KEYS * 8; c += nthreads) {
         const int row = c >> 3, ch = (c & 7) * 8;
         uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
         if (row < N) {
@@ -47,8 +48,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
     __syncthreads();
 
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
-    const int nqt = (N + 31) / 32;
-    for (int qt = wave; qt < nqt; qt += 4) {
+    {
+        const int qt = wave;
         const int qrow = qt * 32 + l32;
         bf16x8_t qf[4];
 #pragma unroll
@@ -72,14 +73,17 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
         // keys get -inf.  The scale is positive, so the maximum is taken on the raw scores.
         float m = -INFINITY;
 #pragma unroll
-        for (int kt = 0; kt < NKT; ++kt)
+        for (int kt = 0; kt < NKT; ++kt) {
+            if (kt * 32 + 32 > N) {               // only the tiles that reach past the sequence need the mask
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = kt * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
-                const float sv = key < N ? sacc[kt][e] : -INFINITY;
-                sacc[kt][e] = sv;
-                m = fmaxf(m, sv);
+                for (int e = 0; e < 16; ++e) {
+                    const int key = kt * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
+                    if (key >= N) sacc[kt][e] = -INFINITY;
+                }
             }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) m = fmaxf(m, sacc[kt][e]);
+        }
         m = fmaxf(m, __shfl_xor(m, 32, 64));
         const float c2 = scale * 1.44269504088896340736f, mc = m * c2;
         float sum = 0.f;
@@ -113,18 +117,22 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
                     union { uint2 h[2]; bf16x8_t v; } vf;
                     vf.h[0] = *(const uint2*)vp;
                     vf.h[1] = *(const uint2*)(vp + 8);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf.v, vf.v, oacc[dt], 0, 0, 0);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, oacc[dt], 0, 0, 0);
                 }
             }
         }
+        // oacc[dt][e] = O[q = l32][d = dt*32 + 8*(e>>2) + 4*lhi + (e&3)]: 4 consecutive channels per store
+        if (qrow < N) {
+            bf16_t* op = o + (int64_t)slot * o_sample_stride + (int64_t)qrow * o_ld + head * DH + 4 * lhi;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int qr = qt * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
-            if (qr < N) {
-                bf16_t* op = o + (int64_t)slot * o_sample_stride + (int64_t)qr * o_ld + head * DH + l32;
-                op[0] = f2bf(oacc[0][e]);
-                op[32] = f2bf(oacc[1][e]);
-            }
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    uint2 w;
+                    w.x = f2bf2(oacc[dt][4 * g4], oacc[dt][4 * g4 + 1]);
+                    w.y = f2bf2(oacc[dt][4 * g4 + 2], oacc[dt][4 * g4 + 3]);
+                    *(uint2*)(op + dt * 32 + 8 * g4) = w;
+                }
         }
     }
 }
@@ -137,7 +145,7 @@ int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, b
     if (B <= 0 || H <= 0) return DS_OK;
     if (N < 1 || N > KEYS) DS_FAIL(DS_EUNSUPPORTED, "attention: sequence length %d outside 1..%d", N, KEYS);
     ProfScope prof(DS_K_ATTENTION, s);
-    hipLaunchKernelGGL(attention_kernel, dim3((unsigned)B, (unsigned)H), dim3(256), 0, s, q, k, v, o, sample_stride,
+    hipLaunchKernelGGL(attention_kernel, dim3((unsigned)B, (unsigned)H), dim3(64 * ((N + 31) / 32)), 0, s, q, k, v, o, sample_stride,
                        ld, o_ld, o_sample_stride, slot_group, gt, N, 0.125f);
     DS_CHECK_LAUNCH("attention");
     return DS_OK;

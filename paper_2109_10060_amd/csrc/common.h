@@ -113,6 +113,15 @@ struct GateArgs {
 };
 size_t ds_gate_partial_bytes(int32_t B, int32_t C);
 int32_t ds_launch_gate(const GateArgs& a, hipStream_t s);
+struct BucketArgs {
+    const int32_t* route;     // [B]
+    const int32_t* lo;        // nullable: key = route * mul + lo
+    int32_t mul, B, T;
+    int32_t *perm, *inv_perm, *offsets, *slot_group;   // inv_perm, slot_group nullable
+    const int32_t* inv_prev;  // with src_index: src_index[slot] = inv_prev ? inv_prev[sample] : sample
+    int32_t* src_index;       // nullable
+};
+int32_t ds_launch_bucket_ex(const BucketArgs& a, hipStream_t s);
 int32_t ds_launch_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
                          int32_t* offsets, int32_t* slot_group, hipStream_t s);
 

@@ -333,13 +333,13 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         Q += 4;
         // ---- bucket by (this stage's route, previous stage's route)
         const int32_t* route_prev = st > 0 ? (routes_out ? routes_out + (size_t)(st - 1) * B : p.route[st - 1]) : nullptr;
-        RC(ds_launch_make_key(route, route_prev, T, p.key, B, s));
-        RC(ds_launch_bucket(p.key, B, G, p.perm[st], p.inv[st], p.offs[st], p.slot_group[st], s));
-        const int32_t* src = p.perm[st];
-        if (st > 0) {
-            RC(ds_launch_compose_index(p.inv[st - 1], p.perm[st], p.src_index, B, s));
-            src = p.src_index;
-        }
+        BucketArgs ba = {};
+        ba.route = route; ba.lo = route_prev; ba.mul = T; ba.B = B; ba.T = G;
+        ba.perm = p.perm[st]; ba.inv_perm = p.inv[st]; ba.offsets = p.offs[st]; ba.slot_group = p.slot_group[st];
+        ba.inv_prev = st > 0 ? p.inv[st - 1] : nullptr;
+        ba.src_index = p.src_index;          // slot of this stage -> slot of the previous stage's layout
+        RC(ds_launch_bucket_ex(ba, s));
+        const int32_t* src = p.src_index;
         MList ml_in = {p.lists[2 * st], (int)ds_mtile_capacity(B, rin * rin, G), rin * rin};
         MList ml_out = {p.lists[2 * st + 1], (int)ds_mtile_capacity(B, rout * rout, G), rout * rout};
         RC(ds_build_mtiles(p.offs[st], G, rin * rin, ml_in.list, s));

@@ -125,45 +125,53 @@ __global__ __launch_bounds__(64) void gate_out_kernel(const GateArgs a, const fl
 }
 
 // ---- bucketing ----------------------------------------------------------------
-__global__ __launch_bounds__(1024) void bucket_kernel(const int32_t* route, int B, int T, int32_t* perm,
-                                                      int32_t* inv_perm, int32_t* offsets, int32_t* slot_group) {
-    __shared__ int hist[1024 + 1];
+// One workgroup.  key[b] = route[b] * mul + (lo ? lo[b] : 0).  Histogram and exclusive scan give the
+// group offsets; then, 1024 samples at a time, every thread ranks its own sample among the earlier
+// samples of the chunk with the same key (stable), so the scatter is parallel over samples.
+__global__ __launch_bounds__(1024) void bucket_kernel(const BucketArgs a) {
+    __shared__ int base[1024 + 1];
     __shared__ int chunk[1024];
     const int tid = threadIdx.x;
-    for (int t = tid; t <= T; t += 1024) hist[t] = 0;
+    const int B = a.B, T = a.T;
+    auto key_of = [&](int b) {
+        const int k = a.route[b] * a.mul + (a.lo ? a.lo[b] : 0);
+        return (k >= 0 && k < T) ? k : -1;
+    };
+    for (int t = tid; t <= T; t += 1024) base[t] = 0;
     __syncthreads();
     for (int b = tid; b < B; b += 1024) {
-        const int r = route[b];
-        if (r >= 0 && r < T) atomicAdd(&hist[r], 1);
+        const int k = key_of(b);
+        if (k >= 0) atomicAdd(&base[k], 1);
     }
     __syncthreads();
     if (tid == 0) {
         int acc = 0;
         for (int t = 0; t < T; ++t) {
-            const int h = hist[t];
-            hist[t] = acc;
+            const int h = base[t];
+            base[t] = acc;
             acc += h;
         }
-        hist[T] = acc;
+        base[T] = acc;
     }
     __syncthreads();
-    for (int t = tid; t <= T; t += 1024) offsets[t] = hist[t];
-    int pos = tid < T ? hist[tid] : 0;
+    for (int t = tid; t <= T; t += 1024) a.offsets[t] = base[t];
     for (int b0 = 0; b0 < B; b0 += 1024) {
         __syncthreads();
-        if (b0 + tid < B) chunk[tid] = route[b0 + tid];
+        const int b = b0 + tid;
+        const int k = b < B ? key_of(b) : -1;
+        chunk[tid] = k;
         __syncthreads();
-        if (tid < T) {
-            const int n = min(1024, B - b0);
-            for (int i = 0; i < n; ++i) {
-                if (chunk[i] == tid) {
-                    perm[pos] = b0 + i;
-                    if (inv_perm) inv_perm[b0 + i] = pos;
-                    if (slot_group) slot_group[pos] = tid;
-                    ++pos;
-                }
-            }
+        if (k >= 0) {
+            int rank = 0;
+            for (int i = 0; i < tid; ++i) rank += chunk[i] == k;
+            const int pos = base[k] + rank;
+            a.perm[pos] = b;
+            if (a.inv_perm) a.inv_perm[b] = pos;
+            if (a.slot_group) a.slot_group[pos] = k;
+            if (a.src_index) a.src_index[pos] = a.inv_prev ? a.inv_prev[b] : b;
         }
+        __syncthreads();
+        if (k >= 0) atomicAdd(&base[k], 1);
     }
 }
 
@@ -221,12 +229,19 @@ int32_t ds_launch_gate(const GateArgs& a, hipStream_t s) {
     return DS_OK;
 }
 
-int32_t ds_launch_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
-                         int32_t* offsets, int32_t* slot_group, hipStream_t s) {
+int32_t ds_launch_bucket_ex(const BucketArgs& a, hipStream_t s) {
     ProfScope prof(DS_K_BUCKET, s);
-    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(1024), 0, s, route, B, T, perm, inv_perm, offsets, slot_group);
+    hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(1024), 0, s, a);
     DS_CHECK_LAUNCH("route bucket");
     return DS_OK;
+}
+
+int32_t ds_launch_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
+                         int32_t* offsets, int32_t* slot_group, hipStream_t s) {
+    BucketArgs a = {};
+    a.route = route; a.mul = 1; a.B = B; a.T = T;
+    a.perm = perm; a.inv_perm = inv_perm; a.offsets = offsets; a.slot_group = slot_group;
+    return ds_launch_bucket_ex(a, s);
 }
 
 extern "C" int32_t ds_bn_fold(const float* gamma, const float* beta, const float* mean, const float* var,
