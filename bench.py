@@ -144,11 +144,19 @@ def main():
         n = prof["gemm"][1] + prof["gemm_taps"][1]
         flops = (cost["gemm"]["flops"] + cost["gemm_taps"]["flops"]) * args.steps
         nbytes = (cost["gemm"]["bytes"] + cost["gemm_taps"]["bytes"]) * args.steps
+        traffic = None
+        tfile = os.path.join(ROOT, "profiles", f"gemm_traffic_{args.workload}_b256.json")
+        if os.path.exists(tfile) and B == 256:
+            from paper_2109_10060_amd.profiling import kernel_source_hash
+            t = json.load(open(tfile))
+            if t.get("source_hash") == kernel_source_hash():   # stale once the kernel changes
+                traffic = t["hbm_bytes_per_launch"]
         if n and ms > 0:
             tf = flops / (ms * 1e-3) / 1e12
             gbs = nbytes / (ms * 1e-3) / 1e9
             roofline = {"kernel": "gemm_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS,
-                        "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_BF16_TFLOPS, "traffic": None,
+                        "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_BF16_TFLOPS, "traffic": traffic,
+                        "algorithmic_bytes_per_launch": nbytes / n,
                         "launches_per_step": n / args.steps, "avg_launch_us": ms * 1e3 / n,
                         "share_of_step": ms / (ms_per_step * args.steps),
                         "hbm_view": {"achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}}

@@ -162,8 +162,33 @@ int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D_e, const v
  * logit_bias: device fp32 [n_gates, B, T] or NULL; logits: device fp32
  * [B, num_classes] in the original sample order; routes_out: device int32
  * [n_gates, B]. */
+/* DS_ARCH_MBNET: MobileNetV1-shaped net, one gate after block `gate_after` (Section 5.2, DS-MBNet).
+ *   ints:   image, stem_out, n_blocks, gate_after, gate_hidden, T, num_classes,
+ *           n_blocks x (C_in, C_out, stride), cin[T][n_blocks], cout[T][n_blocks] (valid widths per route)
+ *   params: stem.w bf16 [3*3*3][stem_out] (tap-major, input channel, then filters), stem.scale, stem.shift,
+ *           per block: dw.w bf16 [3][3][C_in], dw.scale, dw.shift fp32 [Tb][C_in], pw.w bf16 [C_out][C_in],
+ *           pw.scale, pw.shift fp32 [Tb][C_out] (Tb = 1 before the gate, T after),
+ *           gate.w1 [gate_hidden][C], gate.b1, gate.w2 [T][gate_hidden], gate.b2 (fp32),
+ *           fc.w bf16 [num_classes][C_last], fc.b fp32. */
 #define DS_ARCH_MBNET  1
+/* DS_ARCH_RESNET: bottleneck ResNet, a gate in the first block of each of 4 stages (DS-ResNet).
+ *   ints:   image, stem_out, T, num_classes, widths[4], blocks[4], gate_hidden[4], mid[4][T], out[4][T]
+ *   params: stem.w bf16 [7*7*3][stem_out], stem.scale, stem.shift,
+ *           per stage: gate.w1, gate.b1, gate.w2, gate.b2 (fp32), then per block
+ *             c1.w bf16 [w][1][1][C_in], c1.scale, c1.shift fp32 [T][w],
+ *             c2.w bf16 [w][3][3][w], c2.scale, c2.shift, c3.w bf16 [4w][1][1][w], c3.scale, c3.shift [T][4w],
+ *             first block only: proj.w bf16 [4w][1][1][C_in], proj.scale, proj.shift,
+ *           fc.w bf16 [num_classes][4*w_last], fc.b fp32. */
 #define DS_ARCH_RESNET 2
+/* DS_ARCH_VIT: pre-LN vision transformer, one route per image chosen before the patch embedding (DS-ViT).
+ *   ints:   image, patch, embed, heads, head_dim, mlp, depth, tokens, T, num_classes,
+ *           routes[T][3] = (d_e, heads, hidden)
+ *   params: embed.w bf16 [embed][3*patch*patch], embed.b, cls bf16 [embed], pos bf16 [tokens][embed],
+ *           per layer: ln1.g, ln1.b, wqkv bf16 [3][heads*head_dim][embed], bqkv fp32 [3][heads*head_dim],
+ *             wproj bf16 [embed][heads*head_dim], bproj, ln2.g, ln2.b, fc1.w bf16 [mlp][embed], fc1.b,
+ *             fc2.w bf16 [embed][mlp], fc2.b,
+ *           ln.g, ln.b, head.w bf16 [num_classes][embed], head.b.
+ *   Routes come from logit_bias (argmax) or route_override; one of them is required. */
 #define DS_ARCH_VIT    3
 typedef struct ds_net {
     int32_t arch;
