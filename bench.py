@@ -145,7 +145,7 @@ def main():
         flops = (cost["gemm"]["flops"] + cost["gemm_taps"]["flops"]) * args.steps
         nbytes = (cost["gemm"]["bytes"] + cost["gemm_taps"]["bytes"]) * args.steps
         traffic = None
-        tfile = os.path.join(ROOT, "profiles", f"gemm_traffic_{args.workload}_b256.json")
+        tfile = os.path.join(ROOT, "profiles", f"gemm_traffic_{args.workload}_b256.txt")
         if os.path.exists(tfile) and B == 256:
             from paper_2109_10060_amd.profiling import kernel_source_hash
             t = json.load(open(tfile))
