@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernel launches with HIP events (roofline is then null)")
+    ap.add_argument("--event-every", type=int, default=5,
+                    help="bracket the kernels of every N-th timed step with HIP events (1 = every step)")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class table to stderr")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB mebibytes 5 times (reference for the HBM byte counters)")
@@ -120,20 +122,30 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ds.ds_profile_enable(not args.no_kernel_events)
+    # per-kernel HIP events are recorded on a sample of the timed steps (every --event-every-th):
+    # the event packets keep consecutive kernels from overlapping, so bracketing every step would
+    # lower the throughput being measured
+    ds.ds_profile_reset()
+    every = max(1, args.event_every)
+    sampled = 0
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        on = (not args.no_kernel_events) and i % every == every // 2
+        if on:
+            ds.ds_profile_enable(True)
+            sampled += 1
         step()
+        if on:
+            ds.ds_profile_enable(False)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = e0.elapsed_time(e1)
     ms_per_step = max(wall_ms, gpu_ms) / args.steps
-    prof = ds.ds_profile_read() if not args.no_kernel_events else {}
-    ds.ds_profile_enable(False)
+    prof = ds.ds_profile_read() if sampled else {}
 
     rt = routes.cpu().numpy()
     cost = {"mbnet": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost}[args.workload](arch, rt)
@@ -142,8 +154,8 @@ def main():
         # dominant kernel: the grouped GEMM (all its launches: linear/1x1 and tap-walking)
         ms = prof["gemm"][0] + prof["gemm_taps"][0]
         n = prof["gemm"][1] + prof["gemm_taps"][1]
-        flops = (cost["gemm"]["flops"] + cost["gemm_taps"]["flops"]) * args.steps
-        nbytes = (cost["gemm"]["bytes"] + cost["gemm_taps"]["bytes"]) * args.steps
+        flops = (cost["gemm"]["flops"] + cost["gemm_taps"]["flops"]) * sampled
+        nbytes = (cost["gemm"]["bytes"] + cost["gemm_taps"]["bytes"]) * sampled
         traffic = None
         tfile = os.path.join(ROOT, "profiles", f"gemm_traffic_{args.workload}_b256.txt")
         if os.path.exists(tfile) and B == 256:
@@ -157,17 +169,17 @@ def main():
             roofline = {"kernel": "gemm_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS,
                         "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_BF16_TFLOPS, "traffic": traffic,
                         "algorithmic_bytes_per_launch": nbytes / n,
-                        "launches_per_step": n / args.steps, "avg_launch_us": ms * 1e3 / n,
-                        "share_of_step": ms / (ms_per_step * args.steps),
+                        "launches_per_step": n / sampled, "avg_launch_us": ms * 1e3 / n,
+                        "steps_sampled": sampled, "share_of_step": ms / (ms_per_step * sampled),
                         "hbm_view": {"achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}}
         if args.breakdown:
             for k, (t, cnt) in prof.items():
                 if not cnt:
                     continue
                 c = cost.get(k, {"flops": 0.0, "bytes": 0.0})
-                sys.stderr.write(f"{k:10s} {t / args.steps:8.3f} ms/step {cnt // args.steps:4d} launches  "
-                                 f"{c['flops'] / (t / args.steps * 1e-3) / 1e12 if t else 0:8.1f} TFLOP/s "
-                                 f"{c['bytes'] / (t / args.steps * 1e-3) / 1e9 if t else 0:8.0f} GB/s\n")
+                sys.stderr.write(f"{k:10s} {t / sampled:8.3f} ms/step {cnt // sampled:4d} launches  "
+                                 f"{c['flops'] / (t / sampled * 1e-3) / 1e12 if t else 0:8.1f} TFLOP/s "
+                                 f"{c['bytes'] / (t / sampled * 1e-3) / 1e9 if t else 0:8.0f} GB/s\n")
 
     out = {
         "metric": "images/sec at batch 256 (mixed gate widths)", "value": B / (ms_per_step * 1e-3), "unit": "images/s",

@@ -202,13 +202,17 @@ int32_t ds_forward(const ds_net* net, const void* images, int32_t B, const int32
                    const float* logit_bias, float* logits, int32_t* routes_out, void* ws,
                    size_t ws_bytes, void* stream);
 
-/* Instrumentation: with ds_profile_enable(1) every kernel launch is bracketed by HIP
- * events on its stream (enable also clears earlier records); ds_profile_read waits for
- * the recorded events and returns the summed milliseconds and launch count of one
- * kernel class: 0 grouped GEMM on linear/1x1 layers, 1 grouped GEMM walking KxK taps,
- * 2 attention, 3 depthwise conv, 4 LayerNorm, 5 stem conv, 6 max-pool, 7 pool+classifier,
- * 8 gate, 9 bucket, 10 index helpers.  Not thread-safe; host pointers. */
+/* Instrumentation: while recording is on, every kernel launch is bracketed by a pair of HIP
+ * events on its stream.  The event packets keep consecutive kernels from overlapping their
+ * launch and drain phases (10-15 % on the batch-256 networks), so a caller that wants both a
+ * throughput figure and kernel durations switches recording on for a sample of its steps only:
+ * ds_profile_enable(1) resumes recording, ds_profile_enable(0) pauses it, records accumulate until
+ * ds_profile_reset().  ds_profile_read waits for the recorded events and returns the summed
+ * milliseconds and launch count of one kernel class: 0 grouped GEMM on linear/1x1 layers,
+ * 1 grouped GEMM walking KxK taps, 2 attention, 3 depthwise conv, 4 LayerNorm, 5 stem conv,
+ * 6 max-pool, 7 pool+classifier, 8 gate, 9 bucket, 10 index helpers.  Not thread-safe; host pointers. */
 int32_t ds_profile_enable(int32_t on);
+int32_t ds_profile_reset(void);
 int32_t ds_profile_read(int32_t kind, double* total_ms, int64_t* launches);
 
 #ifdef __cplusplus

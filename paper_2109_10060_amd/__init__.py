@@ -32,7 +32,7 @@ EXPORTS = [
     "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
     "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
-    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_profile_enable", "ds_profile_read",
+    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
 ]
 
 
@@ -258,6 +258,10 @@ KERNEL_CLASSES = ["gemm", "gemm_taps", "attention", "dwconv", "layernorm", "stem
 
 def ds_profile_enable(on: bool):
     _chk(load().ds_profile_enable(1 if on else 0))
+
+
+def ds_profile_reset():
+    _chk(load().ds_profile_reset())
 
 
 def ds_profile_read() -> dict:

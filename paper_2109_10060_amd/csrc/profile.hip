@@ -1,6 +1,7 @@
-// Optional per-kernel timing: when enabled, every kernel launcher brackets its launch
+// Optional per-kernel timing: while recording, every kernel launcher brackets its launch
 // with a pair of HIP events on the launch stream; ds_profile_read sums the elapsed
-// times per kernel class.  Off by default; costs nothing when off.
+// times per kernel class.  Off by default; costs nothing when off.  Recording can be
+// paused and resumed (records accumulate) so that a caller samples some of its steps.
 #include <vector>
 
 #include "common.h"
@@ -34,6 +35,10 @@ ProfScope::~ProfScope() {
 
 extern "C" int32_t ds_profile_enable(int32_t on) {
     g_on = on != 0;
+    return DS_OK;
+}
+
+extern "C" int32_t ds_profile_reset(void) {
     g_used = 0;
     return DS_OK;
 }
