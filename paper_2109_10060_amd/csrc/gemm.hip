@@ -309,12 +309,16 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? 6 : 1) 
     }
 }
 
+// The list walks the groups from the last to the first: route tables are ordered from the narrowest
+// to the widest slice, so the longest work items are dispatched first and the short ones fill the
+// tail of the launch.
 __global__ void build_mtiles_kernel(const int32_t* offsets, int T, int rows, int32_t* count, int4* entries) {
     __shared__ int pre[DS_MAX_GROUPS + 1];
     if (threadIdx.x == 0) {
         int acc = 0;
-        for (int g = 0; g < T; ++g) {
-            pre[g] = acc;
+        for (int q = 0; q < T; ++q) {
+            const int g = T - 1 - q;
+            pre[q] = acc;
             const int rg = (offsets[g + 1] - offsets[g]) * rows;
             acc += (rg + BM - 1) / BM;
         }
@@ -322,10 +326,11 @@ __global__ void build_mtiles_kernel(const int32_t* offsets, int T, int rows, int
         *count = acc;
     }
     __syncthreads();
-    for (int g = 0; g < T; ++g) {
-        const int n = pre[g + 1] - pre[g];
+    for (int q = 0; q < T; ++q) {
+        const int g = T - 1 - q;
+        const int n = pre[q + 1] - pre[q];
         const int slot0 = offsets[g], rg = (offsets[g + 1] - slot0) * rows;
-        for (int i = threadIdx.x; i < n; i += blockDim.x) entries[pre[g] + i] = make_int4(g, i * BM, slot0, rg);
+        for (int i = threadIdx.x; i < n; i += blockDim.x) entries[pre[q] + i] = make_int4(g, i * BM, slot0, rg);
     }
 }
 
