@@ -55,8 +55,8 @@ struct Tile {
     static_assert(WROWS * WCOLS == 4 && WROWS * WMT * 32 == BM, "4 wavefronts cover a 128-row tile");
 };
 
-template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV>
-__global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? 6 : 1) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
+template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV, bool HASR>
+__global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ? 5 : 6) : 1) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     constexpr int BN = TL::BN, LDS_LD = BK, CPR = BK / 8, RPT = NT / CPR;   // chunks per row, rows per pass
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -213,6 +213,23 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? 6 : 1) 
         }
     }
 
+    // the residual rows this lane will add are fetched now, so that their latency hides behind the
+    // main loop instead of sitting between the last matrix instruction and the stores
+    uint2 rres[HASR ? WMT * PASSES * (SROWS / RPP) : 1];
+    if constexpr (HASR) {
+#pragma unroll
+        for (int tm = 0; tm < WMT; ++tm)
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps)
+#pragma unroll
+                for (int q = 0; q < SROWS / RPP; ++q) {
+                    const int r = wm * WMT * 32 + tm * 32 + ps * SROWS + rr0 + q * RPP;
+                    uint2 t = make_uint2(0, 0);
+                    if (nok && rowC[r] >= 0) t = *(const uint2*)(a.R + rowR[r] + ncol);
+                    rres[(tm * PASSES + ps) * (SROWS / RPP) + q] = t;
+                }
+    }
+
     // operand rows of this lane: row (32 t + l32) of the wave's A / B block; with 128-byte rows the
     // swizzle key of row + 32 t is the key of the row ^ (4 t & 7), with 64-byte rows it does not change
     const bf16_t* as = As + (wm * WMT * 32 + l32) * LDS_LD;
@@ -280,8 +297,8 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? 6 : 1) 
                     if (coff < 0) continue;
                     const float4 t = *(const float4*)(st + rr * ST_LD + cg * 4);
                     float val[4] = {t.x * sc[0] + sh[0], t.y * sc[1] + sh[1], t.z * sc[2] + sh[2], t.w * sc[3] + sh[3]};
-                    if (a.R) {
-                        const uint2 q = *(const uint2*)(a.R + rowR[r] + ncol);
+                    if constexpr (HASR) {
+                        const uint2 q = rres[(tm * PASSES + ps) * (SROWS / RPP) + (rr - rr0) / RPP];
                         val[0] += __uint_as_float(q.x << 16);
                         val[1] += __uint_as_float(q.x & 0xffff0000u);
                         val[2] += __uint_as_float(q.y << 16);
@@ -334,11 +351,11 @@ __global__ void build_mtiles_kernel(const int32_t* offsets, int T, int rows, int
     }
 }
 
-template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV>
+template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV, bool HASR>
 int32_t launch(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     static bool configured = false;
-    auto kern = gemm_kernel<WROWS, WCOLS, WMT, WNT, BK, CONV>;
+    auto kern = gemm_kernel<WROWS, WCOLS, WMT, WNT, BK, CONV, HASR>;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM) != hipSuccess)
             DS_FAIL(DS_EHIP, "sliced gemm: cannot reserve %d bytes of LDS", TL::SMEM);
@@ -380,7 +397,11 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL)
         DS_FAIL(DS_EUNSUPPORTED, "sliced gemm: activation tensor spans 2 GiB or more");
     const bool conv = a.K > 1 || a.stride > 1 || a.pad > 0;
-#define DS_GEMM_DISPATCH(...) (conv ? launch<__VA_ARGS__, true>(a, max_mtiles, max_kout, s) : launch<__VA_ARGS__, false>(a, max_mtiles, max_kout, s))
+#define DS_GEMM_DISPATCH(...)                                                                          \
+    (conv ? (a.R ? launch<__VA_ARGS__, true, true>(a, max_mtiles, max_kout, s)                         \
+                 : launch<__VA_ARGS__, true, false>(a, max_mtiles, max_kout, s))                       \
+          : (a.R ? launch<__VA_ARGS__, false, true>(a, max_mtiles, max_kout, s)                        \
+                 : launch<__VA_ARGS__, false, false>(a, max_mtiles, max_kout, s)))
     if (bn == 32) return DS_GEMM_DISPATCH(4, 1, 1, 2, 32);   // 64-wide tile, 32-deep slabs
     if (bn == 64) return DS_GEMM_DISPATCH(4, 1, 1, 2, 64);
     if (bn == 128) return DS_GEMM_DISPATCH(2, 2, 2, 2, 64);
