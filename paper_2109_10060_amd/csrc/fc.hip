@@ -80,15 +80,23 @@ __global__ __launch_bounds__(256) void fc_tile_kernel(const FcArgs a) {
     }
 }
 
-// Same tile, with 16-byte global loads and the next 64-channel chunk prefetched into registers
-// while the current one is consumed from LDS.  Needs C and w_ld to be multiples of 8.
-template <typename WT, typename ACC>
+// Vector variant: 16-byte global loads, the next PF 64-channel chunks travelling in registers while
+// the current one is consumed from LDS, and the LDS tiles held in the accumulation type, so that the
+// inner loop has no conversions (a float -> double conversion per operand read made the double-
+// accumulating gate layer conversion-bound).  TO outputs x 16 items per workgroup: 64 outputs for
+// wide layers, 16 when the launch would otherwise have too few workgroups to cover the chip.
+// Needs C and w_ld to be multiples of 8.
+constexpr int PF = 4;
+
+template <typename WT, typename ACC, int TOV>
 __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
-    __shared__ float Wl[TO][TC + 1];
-    __shared__ float Vl[TI][TC];
+    constexpr int IPT = TI * TOV / 256;                 // items per thread
+    static_assert(IPT >= 1 && TI * TOV % 256 == 0, "tile shape");
+    __shared__ ACC Wl[TOV][TC + 1];
+    __shared__ ACC Vl[TI][TC];
     __shared__ int cs[TI];
     const int tid = threadIdx.x;
-    const int o0 = blockIdx.x * TO, i0 = blockIdx.y * TI;
+    const int o0 = blockIdx.x * TOV, i0 = blockIdx.y * TI;
     if (tid < TI) {
         const int item = i0 + tid;
         int c = 0;
@@ -99,23 +107,24 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
     int cmax = 0;
 #pragma unroll
     for (int i = 0; i < TI; ++i) cmax = max(cmax, cs[i]);
-    const int ol = tid & 63, ig = tid >> 6;
+    const int ol = tid % TOV, ig = tid / TOV;
     constexpr bool WB = sizeof(WT) == 2;
-    constexpr int NW = WB ? 2 : 4;                  // 16-byte weight loads per thread and chunk
-    const int vr = tid >> 4, vc4 = (tid & 15) * 4;  // V: row, first of 4 channels
+    constexpr int EPL = WB ? 8 : 4;                     // weight elements per 16-byte load
+    constexpr int WCH = TOV * TC / EPL;                 // 16-byte weight loads per chunk
+    constexpr int NW = (WCH + 255) / 256;
+    const int vr = tid >> 4, vc4 = (tid & 15) * 4;      // V: row, first of 4 channels
     const int vitem = i0 + vr, vcs = cs[vr];
-    uint4 wreg[NW];
-    float vreg[4];
+    uint4 wregs[PF][NW];
+    float vregs[PF][4];
     const WT* w = (const WT*)a.w;
-    auto prefetch = [&](int c0) {
+    auto prefetch = [&](uint4 (&wreg)[NW], float (&vreg)[4], int c0) {
 #pragma unroll
         for (int i = 0; i < NW; ++i) {
             const int e = tid + 256 * i;
-            const int r = WB ? (e >> 3) : (e >> 4);
-            const int cc = WB ? (e & 7) * 8 : (e & 15) * 4;
+            const int r = e / (TC / EPL), cc = (e % (TC / EPL)) * EPL;
             const int o = o0 + r, c = c0 + cc;
             wreg[i] = make_uint4(0, 0, 0, 0);
-            if (o < a.n_out && c < cmax) wreg[i] = *(const uint4*)(w + (int64_t)o * a.w_ld + c);
+            if (e < WCH && o < a.n_out && c < cmax) wreg[i] = *(const uint4*)(w + (int64_t)o * a.w_ld + c);
         }
         const int c = c0 + vc4;
 #pragma unroll
@@ -139,47 +148,57 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
                 if (c + j >= vcs) vreg[j] = 0.f;
         }
     };
-    auto store = [&]() {
+    auto store = [&](const uint4 (&wreg)[NW], const float (&vreg)[4]) {
 #pragma unroll
         for (int i = 0; i < NW; ++i) {
             const int e = tid + 256 * i;
+            if (e >= WCH) continue;
+            const int r = e / (TC / EPL), cc = (e % (TC / EPL)) * EPL;
+            const uint32_t q[4] = {wreg[i].x, wreg[i].y, wreg[i].z, wreg[i].w};
             if constexpr (WB) {
-                const int r = e >> 3, cc = (e & 7) * 8;
-                const uint32_t q[4] = {wreg[i].x, wreg[i].y, wreg[i].z, wreg[i].w};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    Wl[r][cc + 2 * j] = __uint_as_float(q[j] << 16);
-                    Wl[r][cc + 2 * j + 1] = __uint_as_float(q[j] & 0xffff0000u);
+                    Wl[r][cc + 2 * j] = (ACC)__uint_as_float(q[j] << 16);
+                    Wl[r][cc + 2 * j + 1] = (ACC)__uint_as_float(q[j] & 0xffff0000u);
                 }
             } else {
-                const int r = e >> 4, cc = (e & 15) * 4;
-                Wl[r][cc] = __uint_as_float(wreg[i].x); Wl[r][cc + 1] = __uint_as_float(wreg[i].y);
-                Wl[r][cc + 2] = __uint_as_float(wreg[i].z); Wl[r][cc + 3] = __uint_as_float(wreg[i].w);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) Wl[r][cc + j] = (ACC)__uint_as_float(q[j]);
             }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) Vl[vr][vc4 + j] = vreg[j];
+        for (int j = 0; j < 4; ++j) Vl[vr][vc4 + j] = (ACC)vreg[j];
     };
-    ACC acc[4] = {0, 0, 0, 0};
-    if (cmax > 0) prefetch(0);
-    for (int c0 = 0; c0 < cmax; c0 += TC) {
-        store();
-        __syncthreads();
-        if (c0 + TC < cmax) prefetch(c0 + TC);
-#pragma unroll 8
-        for (int cc = 0; cc < TC; ++cc) {
-            const ACC wv = (ACC)Wl[ol][cc];
+    ACC acc[IPT];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc[s] += wv * (ACC)Vl[ig * 4 + s][cc];
+    for (int s = 0; s < IPT; ++s) acc[s] = 0;
+#pragma unroll
+    for (int st = 0; st < PF; ++st)
+        if (st * TC < cmax) prefetch(wregs[st], vregs[st], st * TC);
+    for (int cb = 0; cb < cmax; cb += PF * TC) {
+#pragma unroll
+        for (int st = 0; st < PF; ++st) {
+            const int c0 = cb + st * TC;
+            if (c0 < cmax) {                       // uniform over the workgroup
+                store(wregs[st], vregs[st]);
+                __syncthreads();
+                if (c0 + PF * TC < cmax) prefetch(wregs[st], vregs[st], c0 + PF * TC);
+#pragma unroll 8
+                for (int cc = 0; cc < TC; ++cc) {
+                    const ACC wv = Wl[ol][cc];
+#pragma unroll
+                    for (int s = 0; s < IPT; ++s) acc[s] += wv * Vl[ig * IPT + s][cc];
+                }
+                __syncthreads();
+            }
         }
-        __syncthreads();
     }
     const int o = o0 + ol;
     if (o < a.n_out) {
         const ACC b = a.bias ? (ACC)a.bias[o] : (ACC)0;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int item = i0 + ig * 4 + s;
+        for (int s = 0; s < IPT; ++s) {
+            const int item = i0 + ig * IPT + s;
             if (item >= a.items) continue;
             ACC v = acc[s] + b;
             if (a.relu && v < (ACC)0) v = (ACC)0;
@@ -193,15 +212,28 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
 
 int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t kind, hipStream_t s) {
     if (a.items <= 0 || a.n_out <= 0) return DS_OK;
-    dim3 grid((unsigned)((a.n_out + TO - 1) / TO), (unsigned)((a.items + TI - 1) / TI));
+    const unsigned gy = (unsigned)((a.items + TI - 1) / TI);
     ProfScope prof(kind, s);
     const bool vec = (a.C % 8) == 0 && (a.w_ld % 8) == 0 && (a.v_rows == nullptr || (a.v_row_stride % 4) == 0);
-    if (vec && w_bf16) hipLaunchKernelGGL((fc_tile_vec_kernel<bf16_t, float>), grid, dim3(256), 0, s, a);
-    else if (vec && acc_f64) hipLaunchKernelGGL((fc_tile_vec_kernel<float, double>), grid, dim3(256), 0, s, a);
-    else if (vec) hipLaunchKernelGGL((fc_tile_vec_kernel<float, float>), grid, dim3(256), 0, s, a);
-    else if (w_bf16) hipLaunchKernelGGL((fc_tile_kernel<bf16_t, float>), grid, dim3(256), 0, s, a);
-    else if (acc_f64) hipLaunchKernelGGL((fc_tile_kernel<float, double>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((fc_tile_kernel<float, float>), grid, dim3(256), 0, s, a);
+    if (vec) {
+        // narrow output tiles when 64-wide ones would leave most compute units without a workgroup
+        const bool narrow = (long long)((a.n_out + 63) / 64) * gy < 256;
+        const dim3 grid((unsigned)((a.n_out + (narrow ? 15 : 63)) / (narrow ? 16 : 64)), gy);
+#define DS_FC_LAUNCH(WT, ACC)                                                                               \
+    do {                                                                                                    \
+        if (narrow) hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 16>), grid, dim3(256), 0, s, a);         \
+        else hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 64>), grid, dim3(256), 0, s, a);                \
+    } while (0)
+        if (w_bf16) DS_FC_LAUNCH(bf16_t, float);
+        else if (acc_f64) DS_FC_LAUNCH(float, double);
+        else DS_FC_LAUNCH(float, float);
+#undef DS_FC_LAUNCH
+    } else {
+        const dim3 grid((unsigned)((a.n_out + TO - 1) / TO), gy);
+        if (w_bf16) hipLaunchKernelGGL((fc_tile_kernel<bf16_t, float>), grid, dim3(256), 0, s, a);
+        else if (acc_f64) hipLaunchKernelGGL((fc_tile_kernel<float, double>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((fc_tile_kernel<float, float>), grid, dim3(256), 0, s, a);
+    }
     DS_CHECK_LAUNCH("fc tile");
     return DS_OK;
 }
