@@ -29,6 +29,17 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)slot * sample_stride + head * DH;
 
+    // this lane's query row, fetched first so that its latency overlaps the staging of K and V
+    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    const int qrow = wave * 32 + l32;
+    bf16x8_t qf[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        uint4 t = make_uint4(0, 0, 0, 0);
+        if (qrow < N) t = *(const uint4*)(q + base + (int64_t)qrow * ld + kk * 16 + lhi * 8);
+        qf[kk] = *(bf16x8_t*)&t;
+    }
+
     const int nthreads = blockDim.x;          // one wavefront per 32-query tile
     for (int c = tid; c < KEYS * 8; c += nthreads) {
         const int row = c >> 3, ch = (c & 7) * 8;
@@ -47,17 +58,7 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
     }
     __syncthreads();
 
-    const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     {
-        const int qt = wave;
-        const int qrow = qt * 32 + l32;
-        bf16x8_t qf[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            uint4 t = make_uint4(0, 0, 0, 0);
-            if (qrow < N) t = *(const uint4*)(q + base + (int64_t)qrow * ld + kk * 16 + lhi * 8);
-            qf[kk] = *(bf16x8_t*)&t;
-        }
         f32x16_t sacc[NKT];
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
         for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = exp2f(fmaf(sacc[kt][e], c2, -mc));
+                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kt][e], c2, -mc));   // argument <= 0; results below 2^-126 flush to 0
                 sacc[kt][e] = p;
                 sum += p;
             }
