@@ -89,6 +89,8 @@ size_t ds_mtile_capacity(int32_t B, int32_t rows, int32_t T);
 // builds the m-tile list for (offsets, rows); list needs ds_mtile_capacity()*16 + 16 bytes
 int32_t ds_build_mtiles(const int32_t* offsets, int32_t T, int32_t rows, void* list, hipStream_t s);
 int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
+// 3x3 stride-1 padding-1 layers on maps up to 59 pixels wide; DS_EUNSUPPORTED for any other shape
+int32_t ds_launch_conv3(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
 
 static inline const int4* ds_mtile_entries(const void* list) { return (const int4*)((const char*)list + 16); }
 static inline const int32_t* ds_mtile_count(const void* list) { return (const int32_t*)list; }

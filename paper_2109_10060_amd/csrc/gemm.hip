@@ -397,6 +397,14 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL)
         DS_FAIL(DS_EUNSUPPORTED, "sliced gemm: activation tensor spans 2 GiB or more");
     const bool conv = a.K > 1 || a.stride > 1 || a.pad > 0;
+    static const int conv3 = [] {
+        const char* e = getenv("DSNET_CONV3");       // tuning knob: 0 sends 3x3 layers through the tap-walking kernel
+        return e ? atoi(e) : 1;
+    }();
+    if (conv && conv3 && !forced) {
+        const int32_t rc = ds_launch_conv3(a, max_mtiles, max_kout, s);
+        if (rc != DS_EUNSUPPORTED) return rc;
+    }
 #define DS_GEMM_DISPATCH(...)                                                                          \
     (conv ? (a.R ? launch<__VA_ARGS__, true, true>(a, max_mtiles, max_kout, s)                         \
                  : launch<__VA_ARGS__, true, false>(a, max_mtiles, max_kout, s))                       \
