@@ -151,7 +151,7 @@ def main():
     cost = {"mbnet": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost}[args.workload](arch, rt)
     roofline = None
     if prof:
-        # dominant kernel: the grouped GEMM (all its launches: linear/1x1 and tap-walking)
+        # dominant kernel: the grouped GEMM (all its launches: linear/1x1, tap-walking and patch-staged 3x3)
         ms = prof["gemm"][0] + prof["gemm_taps"][0]
         n = prof["gemm"][1] + prof["gemm_taps"][1]
         flops = (cost["gemm"]["flops"] + cost["gemm_taps"]["flops"]) * sampled
@@ -166,7 +166,7 @@ def main():
         if n and ms > 0:
             tf = flops / (ms * 1e-3) / 1e12
             gbs = nbytes / (ms * 1e-3) / 1e9
-            roofline = {"kernel": "gemm_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS,
+            roofline = {"kernel": "gemm_kernel+conv3_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS,
                         "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_BF16_TFLOPS, "traffic": traffic,
                         "algorithmic_bytes_per_launch": nbytes / n,
                         "launches_per_step": n / sampled, "avg_launch_us": ms * 1e3 / n,

@@ -18,7 +18,9 @@ namespace {
 constexpr int BM = DS_GEMM_BM, BN = 64, NT = 256;
 constexpr int RMAX = 248;                      // patch rows: 128 + 2 (W + 1), so W <= 59
 constexpr int ZROW = RMAX;                     // one more row, all zeros
-constexpr int A_BYTES = (RMAX + 1) * 64, B_BYTES = 3 * BN * 64;
+constexpr int TPP = 3;                         // taps staged per phase: 3 (one filter row) or 9 (the whole filter)
+constexpr int PPC = 9 / TPP;                   // phases per channel chunk
+constexpr int A_BYTES = (RMAX + 1) * 64, B_BYTES = TPP * BN * 64;
 constexpr int SROWS = 16, ST_LD = BN + 4, STAGE_BYTES = 4 * SROWS * ST_LD * 4;
 constexpr int MAIN_BYTES = A_BYTES + B_BYTES > STAGE_BYTES ? A_BYTES + B_BYTES : STAGE_BYTES;
 constexpr int TABLE_BYTES = BM * 16;
@@ -34,7 +36,7 @@ template <bool HASR>
 __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* As = smem;                                   // [RMAX + 1][32] bf16
-    char* Bs = smem + A_BYTES;                         // [3][BN][32] bf16
+    char* Bs = smem + A_BYTES;                         // [TPP][BN][32] bf16
     long long* rowC = (long long*)(smem + MAIN_BYTES);
     long long* rowR = rowC + BM;
     constexpr uint32_t OOB = 0x80000000u;
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
     const int wn_row = tid >> 2;
     const uint32_t woff = (n0 + wn_row) < k_out ? (uint32_t)(((long long)(n0 + wn_row) * a.w_ld + lchunk * 8) * 2) : OOB;
 
-    uint4 ra[NR], rb[3];
+    uint4 ra[NR], rb[TPP];
     auto load_phase = [&](int c, int u) {
         const int kc = c * 32;
         const bool kok = kc + lchunk * 8 < k_in;
@@ -109,8 +111,8 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
             }
         }
 #pragma unroll
-        for (int v = 0; v < 3; ++v) {
-            const int soff = (int)(((u * 3 + v) * a.w_tap_stride + kc) * 2);
+        for (int v = 0; v < TPP; ++v) {
+            const int soff = (int)(((u * TPP + v) * a.w_tap_stride + kc) * 2);
             const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (int)(kok ? woff : OOB), soff, 0);
             rb[v] = make_uint4(t[0], t[1], t[2], t[3]);
         }
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
             }
         }
 #pragma unroll
-        for (int v = 0; v < 3; ++v) *(uint4*)(Bs + (v * BN + wn_row) * 64 + ((lchunk ^ sw(wn_row)) * 16)) = rb[v];
+        for (int v = 0; v < TPP; ++v) *(uint4*)(Bs + (v * BN + wn_row) * 64 + ((lchunk ^ sw(wn_row)) * 16)) = rb[v];
     };
 
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
@@ -183,23 +185,24 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
             }
     }
 
-    const int nph = ((k_in + 31) / 32) * 3;
+    const int nph = ((k_in + 31) / 32) * PPC;
     load_phase(0, 0);
     store_phase(0);
     __syncthreads();
     int c = 0, u = 0;
     for (int ph = 0; ph < nph; ++ph) {
         int cn = c, un = u + 1;
-        if (un == 3) {
+        if (un == PPC) {
             un = 0;
             ++cn;
         }
         const bool more = ph + 1 < nph;
         if (more) load_phase(cn, un);
 #pragma unroll
-        for (int v = 0; v < 3; ++v) {
-            const int tap = u * 3 + v;
-            const int arow = ((tapmask >> tap) & 1) ? trow + halo + (u - 1) * W + (v - 1) : ZROW;
+        for (int v = 0; v < TPP; ++v) {
+            const int tap = u * TPP + v;
+            const int tu = tap / 3, tv = tap - tu * 3;
+            const int arow = ((tapmask >> tap) & 1) ? trow + halo + (tu - 1) * W + (tv - 1) : ZROW;
             const char* ap = As + arow * 64;
             const int fa = sw(arow);
 #pragma unroll

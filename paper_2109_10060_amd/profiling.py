@@ -18,7 +18,10 @@ import os
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-KERNEL_SOURCES = ["csrc/gemm.hip", "csrc/common.h"]
+KERNEL_SOURCES = ["csrc/gemm.hip", "csrc/conv3.hip", "csrc/common.h"]
+# the grouped GEMM is two kernels: gemm_kernel (linear, 1x1, strided and KxK layers) and conv3_kernel
+# (3x3 stride-1 layers); the summaries treat them as one kernel class, as bench.py does
+GEMM_KERNELS = ("gemm_kernel", "conv3_kernel")
 
 
 def kernel_source_hash() -> str:
@@ -30,8 +33,9 @@ def kernel_source_hash() -> str:
 
 def _short(name: str) -> str:
     name = name.replace("(anonymous namespace)::", "")
-    if "gemm_kernel" in name:
-        return "gemm_kernel"
+    for k in GEMM_KERNELS:
+        if k in name:
+            return k
     name = name.split("(")[0]
     return name[-60:]
 
@@ -51,8 +55,9 @@ def stats(csv_path, out_path, title, command, top=14):
 
 
 def _per_launch(csv_path, counter, match):
+    match = (match,) if isinstance(match, str) else match
     vals = [float(r["Counter_Value"]) for r in csv.DictReader(open(csv_path))
-            if r["Counter_Name"] == counter and match in r["Kernel_Name"]]
+            if r["Counter_Name"] == counter and any(m in r["Kernel_Name"] for m in match)]
     return sum(vals) / len(vals), len(vals)
 
 
@@ -61,9 +66,9 @@ def traffic(fetch_csv, write_csv, copy_fetch_csv, copy_write_csv, copy_bytes, ou
     cf, _ = _per_launch(copy_fetch_csv, "FETCH_SIZE", "copyBuffer")
     cw, _ = _per_launch(copy_write_csv, "WRITE_SIZE", "copyBuffer")
     ff, fw = copy_kib / cf, copy_kib / cw
-    gf, n = _per_launch(fetch_csv, "FETCH_SIZE", "gemm_kernel")
-    gw, _ = _per_launch(write_csv, "WRITE_SIZE", "gemm_kernel")
-    out = {"kernel": "gemm_kernel", "source_hash": kernel_source_hash(), "launches_sampled": n,
+    gf, n = _per_launch(fetch_csv, "FETCH_SIZE", GEMM_KERNELS)
+    gw, _ = _per_launch(write_csv, "WRITE_SIZE", GEMM_KERNELS)
+    out = {"kernel": "gemm_kernel+conv3_kernel", "source_hash": kernel_source_hash(), "launches_sampled": n,
            "fetch_kib_per_launch": gf, "write_kib_per_launch": gw, "fetch_factor": ff, "write_factor": fw,
            "hbm_bytes_per_launch": (gf * ff + gw * fw) * 1024.0, "commands": commands}
     json.dump(out, open(out_json, "w"), indent=1)

@@ -215,7 +215,11 @@ def test_config1_forced_routes_cover_all_ratios(gpu_lib):
 # ------------------------------------------------------------------ bf16 NHWC conv (implicit GEMM)
 @pytest.mark.parametrize("K,stride,pad,H,CI,CO,res", [(3, 1, 1, 14, 64, 64, False), (3, 2, 1, 15, 48, 80, False),
                                                        (1, 1, 0, 9, 96, 40, True), (1, 2, 0, 14, 64, 128, False),
-                                                       (3, 1, 1, 7, 136, 24, True)])
+                                                       (3, 1, 1, 7, 136, 24, True),
+                                                       # 3x3 stride 1 on wide maps: the patch-staged kernel up to 59 pixels,
+                                                       # the tap-walking kernel beyond
+                                                       (3, 1, 1, 56, 32, 72, False), (3, 1, 1, 59, 32, 16, True),
+                                                       (3, 1, 1, 60, 32, 16, False)])
 def test_sliced_conv_bf16_nhwc(gpu_lib, K, stride, pad, H, CI, CO, res):
     B, T = 11, 4
     d = WL.nets.Draw(1000 + K * 10 + stride + CI)
