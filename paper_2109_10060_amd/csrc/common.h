@@ -151,6 +151,10 @@ int32_t ds_launch_stem_mfma(const bf16_t* img, const int32_t* index, bf16_t* y, 
                             const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
                             int32_t pad, int32_t Cout, hipStream_t s);
 int32_t ds_launch_maxpool(const bf16_t* x, bf16_t* y, int32_t B, int32_t H, int32_t W, int32_t C, hipStream_t s);
+// fused 7x7/2 stem (64 filters) + 3x3/2 max-pool; DS_EUNSUPPORTED for other shapes
+int32_t ds_launch_stem_pool(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
+                            const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
+                            int32_t pad, int32_t Cout, hipStream_t s);
 // classifier: logits[out_index[slot]][o] = sum_{c < slot_c[slot]} W[o][c] * v[c] + b[o]; v = spatial mean of x
 // (HW > 0; partial needs ds_gate_partial_bytes(B, C)) or row 0 of the slot (HW == 0)
 int32_t ds_launch_head(ActView x, int32_t HW, const bf16_t* w, int32_t w_ld, const float* bias, int32_t n_out,

@@ -304,9 +304,16 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
     const int T = d.T, G = T * T;
     const int r1 = (d.image + 6 - 7) / 2 + 1;
     int r = (r1 + 2 - 3) / 2 + 1;
-    RC(ds_launch_stem(images, nullptr, p.buf[0], (const bf16_t*)P[0], (const float*)P[1], (const float*)P[2], B, d.image,
-                      d.image, 7, 2, 3, d.stem_out, s));
-    RC(ds_launch_maxpool(p.buf[0], p.buf[1], B, r1, r1, d.stem_out, s));
+    // stem and max-pool in one kernel where the shape allows, else one after the other
+    int32_t fused = ds_launch_stem_pool(images, nullptr, p.buf[1], (const bf16_t*)P[0], (const float*)P[1],
+                                        (const float*)P[2], B, d.image, d.image, 7, 2, 3, d.stem_out, s);
+    if (fused == DS_EUNSUPPORTED) {
+        RC(ds_launch_stem(images, nullptr, p.buf[0], (const bf16_t*)P[0], (const float*)P[1], (const float*)P[2], B,
+                          d.image, d.image, 7, 2, 3, d.stem_out, s));
+        RC(ds_launch_maxpool(p.buf[0], p.buf[1], B, r1, r1, d.stem_out, s));
+    } else {
+        RC(fused);
+    }
     bf16_t* X = p.buf[1];          // stage input, slot order of the previous stage
     int xi = 1;                    // index of X in buf[]
     int c_prev_full = d.stem_out;
