@@ -80,6 +80,37 @@ def gate_logits(pooled, w1, b1, w2, b2, logit_bias=None):
     return z
 
 
+def gate_hidden(pooled, w1, b1):
+    """Hidden vector shared by the two heads of the gate: relu(W1[:, :c] . pooled + b1)."""
+    pooled = np.asarray(pooled, F64)
+    c = pooled.shape[0]
+    h = np.asarray(w1, F64)[:, :c] @ pooled
+    if b1 is not None:
+        h = h + np.asarray(b1, F64)
+    return np.maximum(h, 0.0)
+
+
+def gate_attention_scale(x, w1, b1, w3, b3=None):
+    """Channel-attention head of the double-headed gate (Section 3.5, Eq. 23): the hidden vector of
+    the routing MLP is projected back to the channels by a third matrix W3 [C_I, C_mlp] and passed
+    through delta(s) = 1 + tanh(s).  x: [c, H, W] with c valid channels; W1 is input-sliced to its
+    first c columns and W3 output-sliced to its first c rows (both are dynamic layers of the
+    sample's width).  Returns the per-channel factor [c]."""
+    x = np.asarray(x, F64)
+    c = x.shape[0]
+    h = gate_hidden(gate_encoder(x), w1, b1)
+    s = np.asarray(w3, F64)[:c] @ h
+    if b3 is not None:
+        s = s + np.asarray(b3, F64)[:c]
+    return 1.0 + np.tanh(s)
+
+
+def gate_attention(x, w1, b1, w3, b3=None):
+    """Eq. 23: the re-weighted feature map X * delta(...), broadcast over the pixels."""
+    x = np.asarray(x, F64)
+    return x * gate_attention_scale(x, w1, b1, w3, b3)[:, None, None]
+
+
 def gate_route(z):
     """Inference-time routing: index of the largest score (softmax is monotone, so
     it is skipped).  Ties go to the lowest index, i.e. the smaller sub-network; a

@@ -324,3 +324,65 @@ def test_patchify_order_matches_strided_conv():
     want = F.conv2d(t64(img)[None], t64(w), stride=P_)[0].reshape(D, -1).T.numpy()
     got = O.patchify(img, P_) @ w.reshape(D, -1).T
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ attention head of the gate (Eq. 23)
+def _attn_params(seed, C, hid):
+    rng = np.random.default_rng(seed)
+    return (rng.normal(size=(hid, C)) / np.sqrt(C), rng.normal(size=hid) * 0.1,
+            rng.normal(size=(C, hid)) / np.sqrt(hid), rng.normal(size=C) * 0.1)
+
+
+def test_attention_head_zero_projection_is_identity():
+    # W3 = 0 and b3 = 0 give delta(0) = 1: the feature map passes through unchanged
+    rng = np.random.default_rng(3)
+    x = rng.normal(size=(12, 5, 7))
+    w1, b1, w3, b3 = _attn_params(4, 12, 6)
+    out = O.gate_attention(x, w1, b1, np.zeros_like(w3), np.zeros_like(b3))
+    np.testing.assert_array_equal(out, x)
+
+
+def test_attention_head_brute_force_and_bounds():
+    rng = np.random.default_rng(5)
+    C, hid, H, W = 10, 4, 3, 6
+    x = rng.normal(size=(C, H, W))
+    w1, b1, w3, b3 = _attn_params(6, C, hid)
+    pooled = [sum(x[c, i, j] for i in range(H) for j in range(W)) / (H * W) for c in range(C)]
+    hidden = [max(0.0, sum(w1[k, c] * pooled[c] for c in range(C)) + b1[k]) for k in range(hid)]
+    scale = [1.0 + math.tanh(sum(w3[c, k] * hidden[k] for k in range(hid)) + b3[c]) for c in range(C)]
+    got = O.gate_attention_scale(x, w1, b1, w3, b3)
+    np.testing.assert_allclose(got, scale, rtol=1e-12, atol=1e-12)
+    assert np.all(got > 0.0) and np.all(got < 2.0)          # delta = 1 + tanh lies in (0, 2)
+    want = np.stack([x[c] * scale[c] for c in range(C)])
+    np.testing.assert_allclose(O.gate_attention(x, w1, b1, w3, b3), want, rtol=1e-12, atol=1e-12)
+
+
+def test_attention_head_against_torch_squeeze_excite_form():
+    # the same computation written with library layers: pool -> linear -> relu -> linear -> 1 + tanh
+    rng = np.random.default_rng(7)
+    C, hid = 24, 8
+    x = rng.normal(size=(C, 9, 9))
+    w1, b1, w3, b3 = _attn_params(8, C, hid)
+    xt = torch.from_numpy(x)[None]
+    pooled = torch.nn.functional.adaptive_avg_pool2d(xt, 1).flatten(1)
+    h = torch.relu(torch.nn.functional.linear(pooled, torch.from_numpy(w1), torch.from_numpy(b1)))
+    s = torch.nn.functional.linear(h, torch.from_numpy(w3), torch.from_numpy(b3))
+    want = (xt * (1.0 + torch.tanh(s))[:, :, None, None])[0].numpy()
+    np.testing.assert_allclose(O.gate_attention(x, w1, b1, w3, b3), want, rtol=1e-12, atol=1e-12)
+
+
+def test_attention_head_slice_equals_masked_full_width():
+    # a sample of c valid channels: slicing W1's columns and W3's rows equals running the full-width
+    # head on the feature map with the other channels zeroed, read on the first c channels (Eq. 7 vs 8)
+    rng = np.random.default_rng(9)
+    C, hid, c = 32, 8, 16
+    x = rng.normal(size=(C, 4, 4))
+    w1, b1, w3, b3 = _attn_params(10, C, hid)
+    masked = x.copy()
+    masked[c:] = 0.0
+    full = O.gate_attention(masked, w1, b1, w3, b3)
+    sliced = O.gate_attention(x[:c], w1, b1, w3, b3)
+    np.testing.assert_allclose(sliced, full[:c], rtol=1e-12, atol=1e-12)
+    # and the hidden vector is the one the routing head uses
+    np.testing.assert_allclose(O.gate_hidden(O.gate_encoder(x[:c]), w1, b1),
+                               np.maximum(w1[:, :c] @ x[:c].mean(axis=(1, 2)) + b1, 0.0), rtol=1e-12)
