@@ -93,6 +93,23 @@ int32_t ds_gate(const void* x, int32_t x_dtype, int32_t x_layout, int32_t B, int
                 const float* w2, const float* b2, int32_t T, const float* logit_bias,
                 float* logits_out, int32_t* route_out, void* ws, size_t ws_bytes, void* stream);
 
+/* Double-headed gate (Section 3.5, Eq. 23): the encoder and the hidden vector
+ * h = relu(W1[:, :c_in[b]] . pooled + b1) are computed once and feed both heads.
+ * Routing head (skipped when w2 == NULL): as ds_gate, logits_out [B,T], route_out [B].
+ * Attention head: factor[b,c] = 1 + tanh(W3[c, :] . h + b3[c]) for c < c_in[b], and
+ * y[b] = x[b] * factor[b] broadcast over the pixels; y has the type and layout of x
+ * (y == x re-weights in place); elements of channels >= c_in[b] are not written.
+ * w3 [C, C_mlp], b3 [C] nullable: device fp32, output-sliced to the sample's width.
+ * Factors and hidden vectors are accumulated in fp64 and kept in fp32; a bf16 y is
+ * rounded once (nearest even) from the fp32 product.  ws: at least
+ * ds_gate_double_workspace(B, C) bytes. */
+size_t ds_gate_double_workspace(int32_t B, int32_t C);
+int32_t ds_gate_double(const void* x, int32_t x_dtype, int32_t x_layout, int32_t B, int32_t C, int32_t HW,
+                       const int32_t* c_in, const float* w1, const float* b1, int32_t C_mlp,
+                       const float* w2, const float* b2, int32_t T, const float* logit_bias,
+                       const float* w3, const float* b3, float* logits_out, int32_t* route_out, void* y,
+                       void* ws, size_t ws_bytes, void* stream);
+
 /* Bucket a batch by route: offsets[t] = #samples with route < t (offsets[T] counts
  * the samples with a valid id, so offsets[T] != B flags an id outside [0,T));
  * perm lists samples bucket by bucket, ascending inside a bucket (stable);

@@ -29,7 +29,8 @@ DS_MAX_GROUPS = 64
 DS_ARCH_MBNET, DS_ARCH_RESNET, DS_ARCH_VIT = 1, 2, 3
 
 EXPORTS = [
-    "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_route_bucket",
+    "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_gate_double_workspace",
+    "ds_gate_double", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
     "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
     "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
@@ -68,7 +69,7 @@ def load(path: Optional[str] = None):
     lib = ctypes.CDLL(path)
     lib.ds_last_error.restype = ctypes.c_char_p
     for name in ("ds_gate_workspace", "ds_sliced_linear_workspace", "ds_sliced_conv_workspace",
-                 "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace"):
+                 "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace", "ds_gate_double_workspace"):
         getattr(lib, name).restype = ctypes.c_size_t
     _lib = lib
     return lib
@@ -146,6 +147,29 @@ def ds_gate(x, layout, w1, b1, w2, b2, T: int, logit_bias=None, c_in=None, B: Op
     _chk(lib.ds_gate(_ptr(x), dt, layout, B, C, HW, _ptr(c_in), _ptr(w1), _ptr(b1), C_mlp, _ptr(w2), _ptr(b2), T,
                      _ptr(logit_bias), _ptr(logits), _ptr(route), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
     return logits, route
+
+
+def ds_gate_double(x, layout, w1, b1, w3, b3=None, w2=None, b2=None, T: int = 0, logit_bias=None, c_in=None, y=None):
+    """Double-headed gate.  Returns (y, logits or None, route or None); y = x * (1 + tanh(W3 h + b3))."""
+    lib = load()
+    B = x.shape[0]
+    if layout == DS_NCHW:
+        C, HW = x.shape[1], x.shape[2] * x.shape[3]
+    else:
+        C, HW = x.shape[-1], x.numel() // (x.shape[0] * x.shape[-1])
+    dt = DS_BF16 if x.dtype == torch.bfloat16 else DS_F32
+    C_mlp = w1.shape[0]
+    if y is None:
+        y = torch.empty_like(x)
+    logits = route = None
+    if w2 is not None:
+        logits = torch.empty((B, T), dtype=torch.float32, device=x.device)
+        route = torch.empty((B,), dtype=torch.int32, device=x.device)
+    ws = _ws(lib.ds_gate_double_workspace(B, C), x)
+    _chk(lib.ds_gate_double(_ptr(x), dt, layout, B, C, HW, _ptr(c_in), _ptr(w1), _ptr(b1), C_mlp, _ptr(w2), _ptr(b2), T,
+                            _ptr(logit_bias), _ptr(w3), _ptr(b3), _ptr(logits), _ptr(route), _ptr(y), _ptr(ws),
+                            ctypes.c_size_t(ws.numel()), _stream()))
+    return y, logits, route
 
 
 def ds_route_bucket(route: torch.Tensor, T: int):

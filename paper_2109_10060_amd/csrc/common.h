@@ -115,6 +115,9 @@ struct GateArgs {
 };
 size_t ds_gate_partial_bytes(int32_t B, int32_t C);
 int32_t ds_launch_gate(const GateArgs& a, hipStream_t s);
+// y[b][p][c] = x[b][p][c] * scale[b][c] on the valid channels (NHWC) / y[b][c][p] (NCHW); fp32 or bf16
+int32_t ds_launch_channel_scale(const void* x, void* y, const float* scale, const int32_t* c_in, int32_t dtype,
+                                int32_t layout, int32_t B, int32_t C, int32_t HW, hipStream_t s);
 struct BucketArgs {
     const int32_t* route;     // [B]
     const int32_t* lo;        // nullable: key = route * mul + lo
@@ -217,7 +220,7 @@ struct FcArgs {
     const void* w;            // [n_out][w_ld] fp32 or bf16
     int32_t w_ld;
     const float* bias;        // nullable
-    int32_t n_out, relu;
+    int32_t n_out, relu;      // relu: 0 none, 1 ReLU, 2 one plus tanh (attention head of the gate)
     const int32_t* out_index; // item -> output row (nullable = identity)
     float* out;
     int32_t out_ld, items;

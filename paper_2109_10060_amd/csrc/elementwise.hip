@@ -151,6 +151,48 @@ __global__ __launch_bounds__(256) void dwconv4_kernel(ActView x, ActView y, cons
     }
 }
 
+// ---- channel re-weighting by the attention head of the gate (Section 3.5, Eq. 23) ---------
+// NHWC bf16: 8 channels per thread; channels at or beyond the sample's width are not touched
+__global__ __launch_bounds__(256) void channel_scale_nhwc_bf16_kernel(const bf16_t* x, bf16_t* y, const float* scale,
+                                                                      const int32_t* c_in, int C, int HW) {
+    const int b = blockIdx.y;
+    const int c = c_in ? c_in[b] : C;
+    const int chunks = c >> 3;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= HW * chunks) return;
+    const int p = idx / chunks, ch = (idx - p * chunks) * 8;
+    const int64_t off = ((int64_t)b * HW + p) * C + ch;
+    float v[8], f[8];
+    unpack8(*(const uint4*)(x + off), v);
+    loadf8(scale + (int64_t)b * C + ch, f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= f[i];
+    *(uint4*)(y + off) = pack8(v);
+}
+
+template <typename T>
+__device__ __forceinline__ float ld_as_float(const T* p);
+template <>
+__device__ __forceinline__ float ld_as_float<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float ld_as_float<bf16_t>(const bf16_t* p) { return bf2f(*p); }
+__device__ __forceinline__ void st_from_float(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_from_float(bf16_t* p, float v) { *p = f2bf(v); }
+
+// any other layout / type: one element per thread; grid (ceil(C*HW/256), B)
+template <typename T, bool NHWC>
+__global__ __launch_bounds__(256) void channel_scale_kernel(const T* x, T* y, const float* scale, const int32_t* c_in,
+                                                            int C, int HW) {
+    const int b = blockIdx.y;
+    const int c = c_in ? c_in[b] : C;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= C * HW) return;
+    const int ch = NHWC ? idx % C : idx / HW;
+    if (ch >= c) return;
+    const int64_t off = (int64_t)b * C * HW + idx;
+    st_from_float(y + off, ld_as_float<T>(x + off) * scale[(int64_t)b * C + ch]);
+}
+
 // ---- LayerNorm over the valid slice; one wavefront per row ----------------------
 __global__ __launch_bounds__(256) void layernorm_kernel(ActView x, ActView y, const float* gamma,
                                                         const float* beta, float eps, const int32_t* slot_group,
@@ -469,6 +511,29 @@ int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* sca
         hipLaunchKernelGGL(dwconv4_kernel<2>, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
                            Ho, Wo, act);
     DS_CHECK_LAUNCH("depthwise conv");
+    return DS_OK;
+}
+
+int32_t ds_launch_channel_scale(const void* x, void* y, const float* scale, const int32_t* c_in, int32_t dtype,
+                                int32_t layout, int32_t B, int32_t C, int32_t HW, hipStream_t s) {
+    if (B <= 0 || C <= 0 || HW <= 0) return DS_OK;
+    ProfScope prof(DS_K_GATE, s);
+    if (layout == DS_NHWC && dtype == DS_BF16 && (C % 8) == 0) {
+        dim3 grid((unsigned)(((int64_t)HW * (C / 8) + 255) / 256), (unsigned)B);
+        hipLaunchKernelGGL(channel_scale_nhwc_bf16_kernel, grid, dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, scale, c_in, C,
+                           HW);
+    } else {
+        dim3 grid((unsigned)(((int64_t)C * HW + 255) / 256), (unsigned)B);
+        if (dtype == DS_BF16 && layout == DS_NHWC)
+            hipLaunchKernelGGL((channel_scale_kernel<bf16_t, true>), grid, dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, scale, c_in, C, HW);
+        else if (dtype == DS_BF16)
+            hipLaunchKernelGGL((channel_scale_kernel<bf16_t, false>), grid, dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, scale, c_in, C, HW);
+        else if (layout == DS_NHWC)
+            hipLaunchKernelGGL((channel_scale_kernel<float, true>), grid, dim3(256), 0, s, (const float*)x, (float*)y, scale, c_in, C, HW);
+        else
+            hipLaunchKernelGGL((channel_scale_kernel<float, false>), grid, dim3(256), 0, s, (const float*)x, (float*)y, scale, c_in, C, HW);
+    }
+    DS_CHECK_LAUNCH("channel scale");
     return DS_OK;
 }
 

@@ -73,7 +73,8 @@ __global__ __launch_bounds__(256) void fc_tile_kernel(const FcArgs a) {
             const int item = i0 + ig * 4 + s;
             if (item >= a.items) continue;
             ACC v = acc[s] + b;
-            if (a.relu && v < (ACC)0) v = (ACC)0;
+            if (a.relu == 1 && v < (ACC)0) v = (ACC)0;
+            else if (a.relu == 2) v = (ACC)1 + (ACC)tanh((double)v);   // delta(s) = 1 + tanh(s), Eq. 23
             const int row = a.out_index ? a.out_index[item] : item;
             a.out[(int64_t)row * a.out_ld + o] = (float)v;
         }
@@ -201,7 +202,8 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
             const int item = i0 + ig * IPT + s;
             if (item >= a.items) continue;
             ACC v = acc[s] + b;
-            if (a.relu && v < (ACC)0) v = (ACC)0;
+            if (a.relu == 1 && v < (ACC)0) v = (ACC)0;
+            else if (a.relu == 2) v = (ACC)1 + (ACC)tanh((double)v);   // delta(s) = 1 + tanh(s), Eq. 23
             const int row = a.out_index ? a.out_index[item] : item;
             a.out[(int64_t)row * a.out_ld + o] = (float)v;
         }

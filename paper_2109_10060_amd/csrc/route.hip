@@ -285,6 +285,63 @@ extern "C" int32_t ds_gate(const void* x, int32_t x_dtype, int32_t x_layout, int
     return ds_launch_gate(a, (hipStream_t)stream);
 }
 
+// workspace: encoder partial sums + hidden vectors (as ds_gate) followed by the channel factors [B][C]
+extern "C" size_t ds_gate_double_workspace(int32_t B, int32_t C) {
+    if (B <= 0 || C <= 0) return 0;
+    return ds_align_up(ds_gate_partial_bytes(B, C), 256) + (size_t)B * C * sizeof(float);
+}
+
+extern "C" int32_t ds_gate_double(const void* x, int32_t x_dtype, int32_t x_layout, int32_t B, int32_t C, int32_t HW,
+                                  const int32_t* c_in, const float* w1, const float* b1, int32_t C_mlp,
+                                  const float* w2, const float* b2, int32_t T, const float* logit_bias,
+                                  const float* w3, const float* b3, float* logits_out, int32_t* route_out, void* y,
+                                  void* ws, size_t ws_bytes, void* stream) {
+    if (B < 0) DS_FAIL(DS_EINVAL, "ds_gate_double: B < 0");
+    if (B == 0) return DS_OK;
+    if (!x || !y || !w1 || !w3) DS_FAIL(DS_EINVAL, "ds_gate_double: null pointer");
+    if (C < 1 || HW < 1 || C_mlp < 1 || C_mlp > C) DS_FAIL(DS_EINVAL, "ds_gate_double: bad C/HW/C_mlp");
+    if (x_dtype != DS_F32 && x_dtype != DS_BF16) DS_FAIL(DS_EUNSUPPORTED, "ds_gate_double: dtype");
+    if (x_layout != DS_NCHW && x_layout != DS_NHWC) DS_FAIL(DS_EUNSUPPORTED, "ds_gate_double: layout");
+    if (x_layout == DS_NHWC && ((C % 8) != 0 || !ds_aligned16(x) || !ds_aligned16(y)))
+        DS_FAIL(DS_EALIGN, "ds_gate_double: NHWC needs C %% 8 == 0 and 16-byte aligned x, y");
+    const bool routing = w2 != nullptr;
+    if (routing && (T < 1 || !logits_out || !route_out)) DS_FAIL(DS_EINVAL, "ds_gate_double: routing head needs T >= 1 and outputs");
+    if (!ws || ws_bytes < ds_gate_double_workspace(B, C))
+        DS_FAIL(DS_EWORKSPACE, "ds_gate_double: workspace needs %zu bytes", ds_gate_double_workspace(B, C));
+    hipStream_t s = (hipStream_t)stream;
+    GateArgs a = {};
+    a.x = x; a.dtype = x_dtype; a.layout = x_layout; a.B = B; a.C = C; a.HW = HW;
+    a.c_in = c_in; a.x_sample_stride = (int64_t)C * HW; a.x_ld = C;
+    a.w1 = w1; a.b1 = b1; a.w2 = w2; a.b2 = b2; a.C_mlp = C_mlp; a.T = T;
+    a.logit_bias = logit_bias; a.logits = logits_out; a.route = route_out; a.partial = (float*)ws;
+    // encoder and hidden vector once, shared by both heads
+    int splits = 1;
+    int32_t rc = ds_launch_pool(a, DS_K_GATE, &splits, s);
+    if (rc) return rc;
+    float* hidden = a.partial + (size_t)B * C * POOL_SPLIT_MAX;
+    FcArgs f = {};
+    f.v_partial = a.partial; f.splits = splits; f.v_scale = 1.0f / (float)HW;
+    f.c_item = c_in; f.C = C; f.w = w1; f.w_ld = C; f.bias = b1; f.n_out = C_mlp; f.relu = 1;
+    f.out = hidden; f.out_ld = C_mlp; f.items = B;
+    rc = ds_launch_fc(f, 0, 1, DS_K_GATE, s);
+    if (rc) return rc;
+    if (routing) {
+        ProfScope prof(DS_K_GATE, s);
+        hipLaunchKernelGGL(gate_out_kernel, dim3(B), dim3(64), 0, s, a, (const float*)hidden);
+        DS_CHECK_LAUNCH("gate head");
+    }
+    // attention head: factor[b][c] = 1 + tanh(W3[c, :] . hidden[b] + b3[c]); rows beyond the
+    // sample's width are computed too and never used
+    float* factor = (float*)((char*)ws + ds_align_up(ds_gate_partial_bytes(B, C), 256));
+    FcArgs h = {};
+    h.v_partial = hidden; h.splits = 1; h.v_scale = 1.0f; h.c_item = nullptr; h.C = C_mlp;
+    h.w = w3; h.w_ld = C_mlp; h.bias = b3; h.n_out = C; h.relu = 2;
+    h.out = factor; h.out_ld = C; h.items = B;
+    rc = ds_launch_fc(h, 0, 1, DS_K_GATE, s);
+    if (rc) return rc;
+    return ds_launch_channel_scale(x, y, factor, c_in, x_dtype, x_layout, B, C, HW, s);
+}
+
 extern "C" int32_t ds_route_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,
                                    int32_t* offsets, void* stream) {
     if (B < 0 || T < 1 || T > 1024) DS_FAIL(DS_EINVAL, "ds_route_bucket: need B >= 0 and 1 <= T <= 1024");

@@ -94,6 +94,52 @@ def test_gate_argmax_only_ties_and_nan(gpu_lib):
     assert np.array_equal(logits.cpu().numpy(), lb, equal_nan=True)
 
 
+# ------------------------------------------------------------------ double-headed gate (Eq. 23)
+@pytest.mark.parametrize("C,HW,hid,T,B", [(256, 784, 64, 14, 19), (64, 3136, 16, 4, 5), (1024, 49, 256, 4, 9)])
+def test_gate_double_bf16_nhwc_sliced(gpu_lib, C, HW, hid, T, B):
+    d = WL.nets.Draw(300 + C)
+    x = WL.nets.as_bf16_values(d.normal((B, HW, C)))
+    w1, b1 = d.normal((hid, C), std=C ** -0.5), d.normal((hid,), std=0.1)
+    w2, b2 = d.normal((T, hid), std=hid ** -0.5), d.normal((T,), std=0.1)
+    w3, b3 = d.normal((C, hid), std=hid ** -0.5), d.normal((C,), std=0.1)
+    lb = WL.seeded_logit_bias(11, B, T)
+    c_in = (8 * d.randint(B, C // 8) + 8).astype(np.int32)
+    y0 = torch.full((B, HW, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+    y, logits, route = gpu_lib.ds_gate_double(dev(x, torch.bfloat16), gpu_lib.DS_NHWC, dev(w1), dev(b1), dev(w3), dev(b3),
+                                              w2=dev(w2), b2=dev(b2), T=T, logit_bias=dev(lb),
+                                              c_in=dev(c_in, torch.int32), y=y0)
+    yh = host(y)
+    want_logits = []
+    for b in range(B):
+        c = int(c_in[b])
+        xb = x[b].T[:c].reshape(c, HW, 1)
+        want = O.bf16_round(O.gate_attention(xb, w1, b1, w3, b3))[:, :, 0].T          # [HW, c]
+        assert relerr(yh[b, :, :c], want) < TOL_BF16
+        # a single rounding of an fp32 product: at most one bf16 step away from the oracle anywhere
+        assert np.max(np.abs(yh[b, :, :c] - want) / np.maximum(np.abs(want), 1e-30)) <= 2.0 ** -7
+        assert np.all(np.isnan(yh[b, :, c:])), "channels beyond the sample's width were written"
+        want_logits.append(O.gate_logits(O.gate_encoder(xb), w1, b1, w2, b2, lb[b]))
+    want_logits = np.stack(want_logits)
+    assert relerr(host(logits), want_logits) < TOL_F32
+    _check_routes(route.cpu().numpy(), want_logits)
+
+
+def test_gate_double_fp32_nchw_attention_only_in_place(gpu_lib):
+    c = WL.config1()
+    d = WL.nets.Draw(77)
+    C, hid = c["x"].shape[1], c["gate.w1"].shape[0]
+    w3, b3 = d.normal((C, hid), std=hid ** -0.5), d.normal((C,), std=0.1)
+    x = dev(c["x"]).clone()
+    y, logits, route = gpu_lib.ds_gate_double(x, gpu_lib.DS_NCHW, dev(c["gate.w1"]), dev(c["gate.b1"]), dev(w3), dev(b3), y=x)
+    assert logits is None and route is None and y.data_ptr() == x.data_ptr()
+    want = np.stack([O.gate_attention(c["x"][b], c["gate.w1"], c["gate.b1"], w3, b3) for b in range(c["B"])])
+    assert relerr(host(y), want) < TOL_F32
+    # zero projection: the feature map passes through bit for bit
+    x2 = dev(c["x"])
+    y2, _, _ = gpu_lib.ds_gate_double(x2, gpu_lib.DS_NCHW, dev(c["gate.w1"]), dev(c["gate.b1"]), dev(np.zeros_like(w3)), None)
+    assert np.array_equal(host(y2), c["x"].astype(np.float32))
+
+
 # ------------------------------------------------------------------ sliced linear (config 2)
 def _linear_case(gpu_lib, c, y_dtype, act=0, with_res=False):
     B, N, K = c["B"], c["N"], c["K"]
