@@ -150,6 +150,7 @@ def main():
     rt = routes.cpu().numpy()
     cost = {"mbnet": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost}[args.workload](arch, rt)
     roofline = None
+    kernels = {}
     if prof:
         # dominant kernel: the grouped GEMM (all its launches: linear/1x1, tap-walking and patch-staged 3x3)
         ms = prof["gemm"][0] + prof["gemm_taps"][0]
@@ -172,6 +173,15 @@ def main():
                         "launches_per_step": n / sampled, "avg_launch_us": ms * 1e3 / n,
                         "steps_sampled": sampled, "share_of_step": ms / (ms_per_step * sampled),
                         "hbm_view": {"achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}}
+        # every kernel class with its algorithmic rates (same events, same sampled steps)
+        for k, (t, cnt) in prof.items():
+            if not cnt:
+                continue
+            c = cost.get(k, {"flops": 0.0, "bytes": 0.0})
+            per_step_s = t / sampled * 1e-3
+            kernels[k] = {"ms_per_step": t / sampled, "launches_per_step": cnt / sampled,
+                          "tflops": c["flops"] / per_step_s / 1e12 if t else 0.0,
+                          "algorithmic_gbs": c["bytes"] / per_step_s / 1e9 if t else 0.0}
         if args.breakdown:
             for k, (t, cnt) in prof.items():
                 if not cnt:
@@ -188,6 +198,7 @@ def main():
         "config": {"workload": label, "batch": B, "image": arch["image"],
                    "route_histogram": [np.bincount(r, minlength=net.T).tolist() for r in rt]},
         "roofline": roofline,
+        "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload, arch, params, imgs, lb)
