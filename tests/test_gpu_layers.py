@@ -298,7 +298,7 @@ def test_sliced_conv_bf16_nhwc(gpu_lib, K, stride, pad, H, CI, CO, res):
 
 
 # ------------------------------------------------------------------ depthwise conv
-@pytest.mark.parametrize("stride,H,C", [(1, 14, 64), (2, 14, 96), (2, 7, 40), (1, 9, 264)])
+@pytest.mark.parametrize("stride,H,C", [(1, 14, 64), (2, 14, 96), (2, 7, 40), (1, 9, 264), (1, 57, 32), (2, 56, 24)])
 def test_sliced_dwconv(gpu_lib, stride, H, C):
     B, T = 9, 5
     d = WL.nets.Draw(2000 + stride + C)
@@ -344,7 +344,8 @@ def test_sliced_layernorm(gpu_lib):
 
 
 # ------------------------------------------------------------------ MHSA
-@pytest.mark.parametrize("N,B", [(197, 10), (17, 7), (64, 5)])
+# 224 tokens is the longest sequence the attention kernel takes, 1 token the degenerate softmax, 33 a ragged tile
+@pytest.mark.parametrize("N,B", [(197, 10), (17, 7), (64, 5), (224, 4), (1, 6), (33, 3)])
 def test_sliced_mhsa(gpu_lib, N, B):
     D, H, dh = 384, 6, 64
     d = WL.nets.Draw(4000 + N)
@@ -368,3 +369,64 @@ def test_sliced_mhsa(gpu_lib, N, B):
         want = O.bf16_round(x[b, :, :de] + att)
         assert relerr(yh[b, :, :de], want) < TOL_BF16
         assert np.all(np.isnan(yh[b, :, de:]))
+
+
+def test_sliced_mhsa_rejects_sequences_beyond_224(gpu_lib):
+    D, H, dh, B, N = 128, 2, 64, 2, 225
+    x = torch.zeros((B, N, D), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((3, H * dh, D), dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros((3, H * dh), dtype=torch.float32, device=DEV)
+    wp, bp = torch.zeros((D, H * dh), dtype=torch.bfloat16, device=DEV), torch.zeros((D,), dtype=torch.float32, device=DEV)
+    off = torch.tensor([0, B], dtype=torch.int32, device=DEV)
+    g = gpu_lib.make_groups(off, None, [D], [H * dh])
+    with pytest.raises(gpu_lib.DsError):
+        gpu_lib.ds_sliced_mhsa(x, w, b, wp, bp, H, dh, g, residual=x, y=torch.empty_like(x))
+
+
+def test_sliced_layernorm_wide_rows_and_empty_group(gpu_lib):
+    # rows wider than 512 take the wavefront-per-row kernel; group 1 is left without samples
+    B, N, D, T = 6, 5, 1024, 3
+    d = WL.nets.Draw(3100)
+    x = WL.nets.as_bf16_values(d.normal((B, N, D), std=1.5, mean=-0.25))
+    gm, bt = 1.0 + d.normal((D,), std=0.1), d.normal((D,), std=0.1)
+    route = np.array([0, 2, 2, 0, 2, 0], np.int32)
+    ks = [520, 768, 1024]
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    g = gpu_lib.make_groups(off, perm, ks)
+    y = torch.full((B, N, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    gpu_lib.ds_sliced_layernorm(dev(x, torch.bfloat16), dev(gm), dev(bt), 1e-6, g, y=y)
+    yh = host(y)
+    for b in range(B):
+        k = ks[route[b]]
+        want = O.bf16_round(O.layernorm_sliced(x[b, :, :k], gm, bt, 1e-6))
+        assert relerr(yh[b, :, :k], want) < TOL_BF16
+        assert np.all(np.isnan(yh[b, :, k:]))
+
+
+def test_sliced_conv_and_dwconv_with_an_empty_group_and_one_sample(gpu_lib):
+    # one sample, three of four groups empty: grids sized for the widest group must not write anything else
+    B, T, H, CI, CO = 1, 4, 10, 64, 96
+    d = WL.nets.Draw(5200)
+    x = WL.nets.as_bf16_values(d.normal((B, CI, H, H)))
+    w = WL.nets.as_bf16_values(d.normal((CO, CI, 3, 3), std=(2.0 / (CI * 9)) ** 0.5))
+    wd = WL.nets.as_bf16_values(d.normal((CI, 1, 3, 3), std=0.3))
+    bn, bnd = WL.bn_tables(d, T, CO), WL.bn_tables(d, T, CI)
+    route = np.array([2], np.int32)
+    c_in, c_out = [16, 32, 48, 64], [24, 48, 72, 96]
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    scale, shift = gpu_lib.ds_bn_fold(dev(bn["gamma"]), dev(bn["beta"]), dev(bn["mean"]), dev(bn["var"]), 1e-5)
+    g = gpu_lib.make_groups(off, perm, c_in, c_out)
+    y = torch.full((B, H, H, CO), float("nan"), dtype=torch.bfloat16, device=DEV)
+    gpu_lib.ds_sliced_conv(dev(x.transpose(0, 2, 3, 1), torch.bfloat16), dev(w.transpose(0, 2, 3, 1), torch.bfloat16), scale,
+                           shift, g, 1, 1, act=gpu_lib.DS_ACT_RELU, y=y)
+    yh = host(y).transpose(0, 3, 1, 2)
+    want = O.bf16_round(O.relu(O.re_sbn(O.sliced_conv2d(x[0, :48], w, 72, 1, 1), bn, 2, 1e-5)))
+    assert relerr(yh[0, :72], want) < TOL_BF16 and np.all(np.isnan(yh[0, 72:]))
+    sd, hd = gpu_lib.ds_bn_fold(dev(bnd["gamma"]), dev(bnd["beta"]), dev(bnd["mean"]), dev(bnd["var"]), 1e-5)
+    gd = gpu_lib.make_groups(off, perm, c_in)
+    yd = torch.full((B, H, H, CI), float("nan"), dtype=torch.bfloat16, device=DEV)
+    gpu_lib.ds_sliced_dwconv(dev(x.transpose(0, 2, 3, 1), torch.bfloat16), dev(wd[:, 0].transpose(1, 2, 0), torch.bfloat16), sd, hd,
+                             gd, 1, act=gpu_lib.DS_ACT_RELU, y=yd)
+    ydh = host(yd).transpose(0, 3, 1, 2)
+    wantd = O.bf16_round(O.relu(O.re_sbn(O.sliced_dwconv2d(x[0, :48], wd, 1, 1), bnd, 2, 1e-5)))
+    assert relerr(ydh[0, :48], wantd) < TOL_BF16 and np.all(np.isnan(ydh[0, 48:]))
