@@ -81,16 +81,18 @@ __global__ __launch_bounds__(256) void dwconv_kernel(ActView x, ActView y, const
     *(uint4*)((bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)pix * yld + ch) = pack8(acc);
 }
 
-// Same layer, 4 consecutive output pixels of a row per thread: the 3 x (3 + 3 STRIDE) input window
+constexpr int DW_PX_S2 = 2;   // output pixels per thread at stride 2 (4 at stride 1)
+
+// Same layer, PX consecutive output pixels of a row per thread: the 3 x (3 + 3 STRIDE) input window
 // and the 9 filter chunks are loaded once for 4 outputs, which cuts the load instructions per
-// output from 18 to 6.75 (stride 1) / 9 (stride 2); the kernel is bound by load issue, not HBM.
+// output from 18 to 6.75 (stride 1) / 9 (stride 2).
 // grid (ceil(Ho * ceil(Wo/4) * C/8 / 256), B)
-template <int STRIDE>
+template <int STRIDE, int PX>
 __global__ __launch_bounds__(256) void dwconv4_kernel(ActView x, ActView y, const bf16_t* w, const float* scale,
                                                       const float* shift, int tab_ld, const int32_t* slot_group,
                                                       const GroupTable gt, int C, int H, int W, int Ho, int Wo,
                                                       int act) {
-    constexpr int PX = 4, NCOL = (PX - 1) * STRIDE + 3;
+    constexpr int NCOL = (PX - 1) * STRIDE + 3;
     const int slot = blockIdx.y;
     const int g = slot_group ? slot_group[slot] : 0;
     const int c = gt.k_in[g];
@@ -110,26 +112,60 @@ __global__ __launch_bounds__(256) void dwconv4_kernel(ActView x, ActView y, cons
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[p][i] = 0.f;
     const int ix0 = ox0 * STRIDE - 1;
+    // The whole 3 x NCOL window is fetched with buffer loads before any arithmetic: a tap outside
+    // the image gets an out-of-range offset and comes back as zeros, so there is no branch around a
+    // load and all of them are in flight together (with branches the compiler emits load, wait,
+    // use per tap, and the kernel is bound by that chain of latencies).  The sample is addressed
+    // through a descriptor of its own, so offsets stay small.
+    constexpr uint32_t OOB = 0x80000000u;
+    // (the descriptor must be uniform over the wavefront: sample base only; the channel goes into the offset)
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const bf16_t*)x.p + (int64_t)xs * x.sample_stride), 0, 0x7fffffff, 0x00020000);
+    uint4 xin[3][NCOL];
 #pragma unroll
     for (int u = 0; u < 3; ++u) {
         const int iy = oy * STRIDE + u - 1;
-        if (iy < 0 || iy >= H) continue;
-        float wv[3][8];
-#pragma unroll
-        for (int v = 0; v < 3; ++v) unpack8(*(const uint4*)(w + (u * 3 + v) * C + ch), wv[v]);
-        const bf16_t* xr = xp + (int64_t)iy * W * xld;
+        const bool rok = iy >= 0 && iy < H;
 #pragma unroll
         for (int col = 0; col < NCOL; ++col) {
             const int ix = ix0 + col;
-            if (ix < 0 || ix >= W) continue;
-            float xv[8];
-            unpack8(*(const uint4*)(xr + (int64_t)ix * xld), xv);
+            const uint32_t off = (rok && ix >= 0 && ix < W) ? (uint32_t)(((iy * W + ix) * xld + ch) * 2) : OOB;
+            const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+            xin[u][col] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+    }
+    uint4 win[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) win[t] = *(const uint4*)(w + t * C + ch);
+    // the bf16 pairs stay packed: v_dot2_f32_bf16 against a weight pair with one half zeroed is the
+    // multiply-add of the other half (the bf16 product is exact in fp32, so this equals an fma) and
+    // saves the unpacking of every loaded pixel
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+        bf16x2_t wlo[3][4], whi[3][4];
+#pragma unroll
+        for (int v = 0; v < 3; ++v) {
+            const uint32_t qq[4] = {win[u * 3 + v].x, win[u * 3 + v].y, win[u * 3 + v].z, win[u * 3 + v].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                wlo[v][j] = __builtin_bit_cast(bf16x2_t, qq[j] & 0x0000ffffu);
+                whi[v][j] = __builtin_bit_cast(bf16x2_t, qq[j] & 0xffff0000u);
+            }
+        }
+#pragma unroll
+        for (int col = 0; col < NCOL; ++col) {
+            const uint4 q = xin[u][col];
+            const bf16x2_t xq[4] = {__builtin_bit_cast(bf16x2_t, q.x), __builtin_bit_cast(bf16x2_t, q.y),
+                                    __builtin_bit_cast(bf16x2_t, q.z), __builtin_bit_cast(bf16x2_t, q.w)};
 #pragma unroll
             for (int p = 0; p < PX; ++p) {
                 const int v = col - p * STRIDE;      // filter column this input column meets for output p
                 if (v >= 0 && v < 3) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[p][i] = fmaf(xv[i], wv[v][i], acc[p][i]);
+                    for (int j = 0; j < 4; ++j) {
+                        acc[p][2 * j] = __builtin_amdgcn_fdot2_f32_bf16(xq[j], wlo[v][j], acc[p][2 * j], false);
+                        acc[p][2 * j + 1] = __builtin_amdgcn_fdot2_f32_bf16(xq[j], whi[v][j], acc[p][2 * j + 1], false);
+                    }
                 }
             }
         }
@@ -500,15 +536,16 @@ int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* sca
     const int Ho = (H + 2 - 3) / stride + 1, Wo = (W + 2 - 3) / stride + 1;
     int cmax = 0;
     for (int t = 0; t < gt.T; ++t) cmax = gt.k_in[t] > cmax ? gt.k_in[t] : cmax;
-    const int64_t n = (int64_t)Ho * ((Wo + 3) / 4) * (cmax / 8);
+    const int px = stride == 1 ? 4 : DW_PX_S2;
+    const int64_t n = (int64_t)Ho * ((Wo + px - 1) / px) * (cmax / 8);
     if (n <= 0) return DS_OK;
     dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
     ProfScope prof(DS_K_DWCONV, s);
     if (stride == 1)
-        hipLaunchKernelGGL(dwconv4_kernel<1>, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
+        hipLaunchKernelGGL((dwconv4_kernel<1, 4>), grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
                            Ho, Wo, act);
     else
-        hipLaunchKernelGGL(dwconv4_kernel<2>, grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
+        hipLaunchKernelGGL((dwconv4_kernel<2, DW_PX_S2>), grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
                            Ho, Wo, act);
     DS_CHECK_LAUNCH("depthwise conv");
     return DS_OK;
