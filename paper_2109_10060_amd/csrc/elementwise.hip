@@ -88,7 +88,7 @@ constexpr int DW_PX_S2 = 2;   // output pixels per thread at stride 2 (4 at stri
 // output from 18 to 6.75 (stride 1) / 9 (stride 2).
 // grid (ceil(Ho * ceil(Wo/4) * C/8 / 256), B)
 template <int STRIDE, int PX>
-__global__ __launch_bounds__(256) void dwconv4_kernel(ActView x, ActView y, const bf16_t* w, const float* scale,
+__global__ __launch_bounds__(256, 3) void dwconv4_kernel(ActView x, ActView y, const bf16_t* w, const float* scale,
                                                       const float* shift, int tab_ld, const int32_t* slot_group,
                                                       const GroupTable gt, int C, int H, int W, int Ho, int Wo,
                                                       int act) {
