@@ -46,7 +46,18 @@ __global__ __launch_bounds__(256) void pool_nhwc_kernel(const GateArgs a, int sp
         const int ch = c0 + lane_c * 8;
         float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (ch < c) {
-            for (int r = r0 + lane_r; r < r1; r += 8) {
+            // four rows in flight per lane: the loads are independent, only the adds chain
+            int r = r0 + lane_r;
+            for (; r + 24 < r1; r += 32) {
+                float v[4][8];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) load8<T>(x + (int64_t)(r + 8 * k) * ld + ch, v[k]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) s[i] += v[k][i];
+            }
+            for (; r < r1; r += 8) {
                 float v[8];
                 load8<T>(x + (int64_t)r * ld + ch, v);
 #pragma unroll
