@@ -367,8 +367,14 @@ def forward_vit(arch, p, image, route, store="bf16", taps=None):
     """DS-ViT with the route given (chosen before the patch embedding): sliced patch
     embedding (Eq. 15), class token and position embedding sliced to d_e, pre-LN
     blocks with sliced MHSA (Eq. 16-18) and sliced MLP (Eq. 19), final LayerNorm,
-    classifier on the class token with sliced input width."""
-    d_e, h, hidden = (int(v) for v in arch["routes"][route])
+    classifier on the class token with sliced input width.
+
+    A route may carry a fourth entry, its depth (Section 3.4 lists depth among the dimensions
+    the DS-ViT++ gate controls): the route runs the first `depth` stored blocks and skips the
+    rest, which the residual connections turn into identities (Guideline I of Section 3.1)."""
+    r = [int(v) for v in arch["routes"][route]]
+    d_e, h, hidden = r[:3]
+    n_blocks = r[3] if len(r) > 3 else arch["depth"]
     eps = arch["ln_eps"]
     D = arch["embed"]
     pos = np.asarray(p["pos"], F64)
@@ -376,7 +382,7 @@ def forward_vit(arch, p, image, route, store="bf16", taps=None):
     tok = sliced_linear(patchify(image, arch["patch"]), w_embed, p["embed.b"], d_e) + pos[1:, :d_e]
     cls = (np.asarray(p["cls"], F64)[:d_e] + pos[0, :d_e])[None, :]
     x = _store(np.concatenate([cls, tok], axis=0), store)
-    for l in range(arch["depth"]):
+    for l in range(n_blocks):
         pre = f"l{l}"
         a = _store(layernorm_sliced(x, p[pre + ".ln1.g"], p[pre + ".ln1.b"], eps), store)
         att = sliced_mhsa(a, p[pre + ".wq"], p[pre + ".bq"], p[pre + ".wk"], p[pre + ".bk"],

@@ -212,3 +212,25 @@ def test_seeded_logit_bias_makes_every_route_occur():
         r = np.argmax(lb, axis=1)
         cnt = np.bincount(r, minlength=T)
         assert cnt.min() >= B // T and cnt.max() <= B // T + 1
+
+
+def test_vit_route_depth_equals_truncated_network():
+    # a route of depth L must give what the same network cut down to its first L blocks gives, and a
+    # route whose depth is the stored depth must equal the plain three-entry route (the skipped
+    # blocks are identities because of the residual connections)
+    arch = WL.vit_arch(image=32, patch=8, embed=48, heads=6, head_dim=8, mlp=192, depth=4, routes="depth")
+    p = WL.vit_params(arch, 31)
+    img = WL.images(32, 1, 32)[0]
+    plain = WL.vit_arch(image=32, patch=8, embed=48, heads=6, head_dim=8, mlp=192, depth=4, routes="diag")
+    assert arch["T"] == 12 and arch["routes"].shape == (12, 4)
+    for t in range(arch["T"]):
+        d_e, h, hidden, blocks = (int(v) for v in arch["routes"][t])
+        assert 2 <= blocks <= 4
+        cut = dict(plain, depth=blocks)
+        want = O.forward_vit(cut, p, img, t // 3, store="f64")
+        got = O.forward_vit(arch, p, img, t, store="f64")
+        np.testing.assert_array_equal(got, want)
+    # deeper routes differ from shallower ones (the extra blocks do something)
+    a = O.forward_vit(arch, p, img, 0, store="f64")
+    b = O.forward_vit(arch, p, img, 2, store="f64")
+    assert np.max(np.abs(a - b)) > 1e-6

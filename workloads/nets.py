@@ -205,7 +205,8 @@ def vit_arch(image: int = 224, patch: int = 16, embed: int = 384, heads: int = 6
     """routes[t] = (d_e, h, hidden): embedding slice, head count and MLP hidden slice.
 
     "cross": every combination of 4 embedding slices, 4 head counts and MLP
-    ratios 2,3,4 (hidden = ratio * d_e); "diag": 4 nested routes.
+    ratios 2,3,4 (hidden = ratio * d_e); "diag": 4 nested routes; "depth": the 4 nested
+    routes, each at 3 depths (depth - 2, depth - 1, depth), as (d_e, h, hidden, blocks).
     """
     step = embed // 6
     de_list = [3 * step, 4 * step, 5 * step, 6 * step]
@@ -215,6 +216,10 @@ def vit_arch(image: int = 224, patch: int = 16, embed: int = 384, heads: int = 6
     elif routes == "diag":
         table = [(de_list[0], h_list[0], 2 * de_list[0]), (de_list[1], h_list[1], 3 * de_list[1]),
                  (de_list[2], h_list[2], 3 * de_list[2]), (de_list[3], h_list[3], 4 * de_list[3])]
+    elif routes == "depth":
+        diag = [(de_list[0], h_list[0], 2 * de_list[0]), (de_list[1], h_list[1], 3 * de_list[1]),
+                (de_list[2], h_list[2], 3 * de_list[2]), (de_list[3], h_list[3], 4 * de_list[3])]
+        table = [(*r, depth - k) for r in diag for k in (2, 1, 0)]
     else:
         raise ValueError(routes)
     n_tok = (image // patch) ** 2 + 1
