@@ -199,7 +199,9 @@ int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D_e, const v
 #define DS_ARCH_RESNET 2
 /* DS_ARCH_VIT: pre-LN vision transformer, one route per image chosen before the patch embedding (DS-ViT).
  *   ints:   image, patch, embed, heads, head_dim, mlp, depth, tokens, T, num_classes,
- *           routes[T][3] = (d_e, heads, hidden)
+ *           routes[T][3] = (d_e, heads, hidden), or routes[T][4] = (d_e, heads, hidden, blocks):
+ *           with the fourth entry a route runs only the first `blocks` (0..depth) of the stored
+ *           layers (dynamic depth, Section 3.4); the remaining layers leave its tokens untouched
  *   params: embed.w bf16 [embed][3*patch*patch], embed.b, cls bf16 [embed], pos bf16 [tokens][embed],
  *           per layer: ln1.g, ln1.b, wqkv bf16 [3][heads*head_dim][embed], bqkv fp32 [3][heads*head_dim],
  *             wproj bf16 [embed][heads*head_dim], bproj, ln2.g, ln2.b, fc1.w bf16 [mlp][embed], fc1.b,

@@ -436,6 +436,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
 // =====================================================================================
 struct VitDesc {
     int image, patch, D, H, dh, M, depth, N, T, classes;
+    int rs;                  // entries per route: 3 (d_e, heads, hidden) or 4 (+ number of blocks the route runs)
     const int32_t* routes;
 };
 
@@ -445,7 +446,9 @@ bool parse_vit(const ds_net* net, VitDesc* d) {
     d->image = v[0]; d->patch = v[1]; d->D = v[2]; d->H = v[3]; d->dh = v[4]; d->M = v[5]; d->depth = v[6];
     d->N = v[7]; d->T = v[8]; d->classes = v[9];
     if (d->T < 1 || d->T > DS_MAX_GROUPS) return false;
-    if (net->n_ints != 10 + 3 * d->T) return false;
+    if (net->n_ints == 10 + 3 * d->T) d->rs = 3;
+    else if (net->n_ints == 10 + 4 * d->T) d->rs = 4;
+    else return false;
     d->routes = v + 10;
     return net->n_params == 4 + 12 * d->depth + 4;
 }
@@ -517,7 +520,7 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
     for (int t = 0; t < T; ++t) ge.row[t] = 0;
     gq = ge; gp = ge; g1 = ge; g2 = ge;
     for (int t = 0; t < T; ++t) {
-        const int de = d.routes[3 * t], h = d.routes[3 * t + 1], hid = d.routes[3 * t + 2];
+        const int de = d.routes[d.rs * t], h = d.routes[d.rs * t + 1], hid = d.routes[d.rs * t + 2];
         ge.k_in[t] = kp; ge.k_out[t] = de;
         gq.k_in[t] = de; gq.k_out[t] = h * d.dh;
         gp.k_in[t] = h * d.dh; gp.k_out[t] = de;
@@ -532,8 +535,23 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
     ActView xv = {p.x, nullptr, x_ss, 0}, av = {p.a, nullptr, x_ss, 0};
     RC(ds_launch_cls_rows(xv, (const bf16_t*)P[2], (const bf16_t*)P[3], p.slot_group, gq, B, s));
     const float eps = 1e-6f;
+    const GroupTable fq = gq;      // every route, for the final LayerNorm and the classifier
     for (int l = 0; l < d.depth; ++l) {
         const void* const* L = P + 4 + 12 * l;
+        // dynamic depth: a route that runs fewer than l + 1 blocks gets empty slices from here on, so
+        // no kernel touches its rows and the residual stream carries them through unchanged
+        if (d.rs == 4) {
+            bool any = false;
+            for (int t = 0; t < T; ++t) {
+                if (d.routes[4 * t + 3] <= l) {
+                    gq.k_in[t] = gq.k_out[t] = gp.k_in[t] = gp.k_out[t] = 0;
+                    g1.k_in[t] = g1.k_out[t] = g2.k_in[t] = g2.k_out[t] = 0;
+                } else {
+                    any = true;
+                }
+            }
+            if (!any) break;
+        }
         RC(ds_launch_layernorm(xv, av, (const float*)L[0], (const float*)L[1], eps, p.slot_group, gq, B, d.N, 0, d.N, s));
         RC(linear_gemm(p.a, x_ss, 0, (const bf16_t*)L[2], d.D, (const float*)L[3], nullptr, 0, 0, 0, p.qkv,
                        (int64_t)d.N * Hd, Hd, 0, d.N, 3, (int64_t)Hd * d.D, (int64_t)p.qkv_seg, Hd, p.offs, ml_t, gq,
@@ -549,8 +567,8 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
                        x_ss, 0, 0, d.N, 1, 0, 0, 0, p.offs, ml_t, g2, DS_ACT_NONE, s));
     }
     const void* const* F = P + 4 + 12 * d.depth;
-    RC(ds_launch_layernorm(xv, av, (const float*)F[0], (const float*)F[1], eps, p.slot_group, gq, B, d.N, 0, 1, s));
-    RC(ds_launch_lookup(p.slot_group, gq, 0, p.slot_c, B, s));
+    RC(ds_launch_layernorm(xv, av, (const float*)F[0], (const float*)F[1], eps, p.slot_group, fq, B, d.N, 0, 1, s));
+    RC(ds_launch_lookup(p.slot_group, fq, 0, p.slot_c, B, s));
     return ds_launch_head(av, 0, (const bf16_t*)F[2], d.D, (const float*)F[3], d.classes, p.slot_c, p.perm, logits, nullptr,
                           B, d.D, s);
 }
@@ -623,12 +641,12 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
     if (d.dh != 64 || d.N > 224 || (d.image % d.patch) || d.N != (d.image / d.patch) * (d.image / d.patch) + 1 ||
         (d.patch % 8))
         DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 64, tokens <= 224, patch %% 8 == 0", who);
-    for (int i = 0; i < 3 * d.T; ++i) {
-        if (i % 3 == 1) {
-            if (d.routes[i] < 1 || d.routes[i] > d.H) DS_FAIL(DS_EINVAL, "%s: head count outside 1..%d", who, d.H);
-        } else if (d.routes[i] % 8) {
-            DS_FAIL(DS_EALIGN, "%s: route widths must be multiples of 8", who);
-        }
+    for (int t = 0; t < d.T; ++t) {
+        const int32_t* r = d.routes + d.rs * t;
+        if (r[1] < 1 || r[1] > d.H) DS_FAIL(DS_EINVAL, "%s: head count outside 1..%d", who, d.H);
+        if ((r[0] % 8) || (r[2] % 8) || r[0] < 8 || r[2] < 8 || r[0] > d.D || r[2] > d.M)
+            DS_FAIL(DS_EALIGN, "%s: route widths must be multiples of 8 within the stored widths", who);
+        if (d.rs == 4 && (r[3] < 0 || r[3] > d.depth)) DS_FAIL(DS_EINVAL, "%s: route depth outside 0..%d", who, d.depth);
     }
     plan_vit(d, B, bp, &p);
     return forward_vit(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);

@@ -165,6 +165,22 @@ def test_vit_small_all_samples(gpu_lib, routes):
     _vit_case(gpu_lib, arch, params, imgs, lb, range(B))
 
 
+def test_vit_dynamic_depth_small_all_samples(gpu_lib):
+    # 12 routes = 4 nested widths x 3 depths (2, 3 or 4 of the 4 stored blocks): rows of a route that has
+    # finished must pass through the remaining blocks untouched
+    arch = WL.vit_arch(image=64, patch=16, depth=4, routes="depth")
+    params = WL.vit_params(arch, S + 60)
+    B = 40
+    imgs = WL.images(S + 61, B, 64)
+    lb = WL.seeded_logit_bias(S + 62, B, arch["T"])
+    net, xg, lbg, logits, routes = _vit_case(gpu_lib, arch, params, imgs, lb, range(B))
+    assert len(set(routes.cpu().numpy()[0].tolist())) == arch["T"]
+    # a depth of 0 blocks is legal: embedding, final LayerNorm and classifier only
+    arch0 = dict(arch, routes=arch["routes"].copy())
+    arch0["routes"][:, 3] = 0
+    _vit_case(gpu_lib, arch0, params, imgs[:6], lb[:6], range(6))
+
+
 def test_vit_config5_batch256(gpu_lib):
     arch = WL.vit_arch()
     params = WL.vit_params(arch, S + 5)
