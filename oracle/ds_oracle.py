@@ -320,7 +320,12 @@ def forward_resnet(arch, p, image, logit_bias=None, route_override=None, store="
     """DS-ResNet: 7x7 stem, max-pool, four bottleneck stages.  The first block of a
     stage runs the gate on its input; the stage's mid width, output width and
     projection shortcut follow that route; later blocks inherit it.
-    logit_bias / route_override: [4, T] / [4] per stage.  Returns (logits, routes[4], scores)."""
+    logit_bias / route_override: [4, T] / [4] per stage.  Returns (logits, routes[4], scores).
+
+    arch["nblk"][s][t], when present, is the number of blocks of stage s that route t runs
+    (dynamic depth, Section 3.4 / Guideline I of Section 3.1): the first block always runs, since
+    it changes resolution and width; the skipped later blocks are identities through their
+    residual connections."""
     eps = arch["bn_eps"]
     x = _conv_bn_relu(np.asarray(image, F64), p["stem.w"], p["stem.bn"], 0, eps,
                       arch["stem_out"], 2, 3, store)
@@ -335,7 +340,9 @@ def forward_resnet(arch, p, image, logit_bias=None, route_override=None, store="
         routes.append(t)
         scores.append(z)
         mid, out = int(arch["mid"][s, t]), int(arch["out"][s, t])
-        for b in range(nb):
+        run = nb if arch.get("nblk") is None else int(arch["nblk"][s][t])
+        assert 1 <= run <= nb
+        for b in range(run):
             bp = f"{pre}.b{b}"
             stride = 2 if (b == 0 and s > 0) else 1
             if b == 0:

@@ -234,3 +234,27 @@ def test_vit_route_depth_equals_truncated_network():
     a = O.forward_vit(arch, p, img, 0, store="f64")
     b = O.forward_vit(arch, p, img, 2, store="f64")
     assert np.max(np.abs(a - b)) > 1e-6
+
+
+def test_resnet_route_depth_equals_truncated_network():
+    # a stage whose route runs n blocks must give what a network storing only n blocks in that stage
+    # gives with the same weights and the same per-route BN rows (the skipped blocks are identities
+    # through their residuals)
+    blocks = (2, 3, 2, 2)
+    arch = WL.resnet_arch(image=32, width_div=8, blocks=blocks, routes="depth")
+    plain = {k: v for k, v in arch.items() if k != "nblk"}
+    assert arch["T"] == 8 and arch["nblk"].shape == (4, 8) and arch["nblk"].min() == 1
+    p = WL.resnet_params(arch, 23)
+    img = WL.images(32, 1, 32)[0]
+    rng = np.random.default_rng(5)
+    cases = [[0, 0, 0, 0], [7, 7, 7, 7], [1, 2, 4, 6]] + [list(rng.integers(0, 8, 4)) for _ in range(3)]
+    for rt in cases:
+        got, r_got, _ = O.forward_resnet(arch, p, img, route_override=rt, store="f64")
+        cut = dict(plain, blocks=[int(arch["nblk"][s][rt[s]]) for s in range(4)])
+        want, _, _ = O.forward_resnet(cut, p, img, route_override=rt, store="f64")
+        assert list(r_got) == [int(t) for t in rt]
+        np.testing.assert_array_equal(got, want)
+    # the shallow and the deep route of one ratio differ (the extra block does something)
+    a, _, _ = O.forward_resnet(arch, p, img, route_override=[6, 6, 6, 6], store="f64")
+    b, _, _ = O.forward_resnet(arch, p, img, route_override=[7, 7, 7, 7], store="f64")
+    assert np.max(np.abs(a - b)) > 1e-6

@@ -145,18 +145,27 @@ def mbnet_params(arch: dict, seed: int) -> dict:
 # --------------------------------------------------------------------------
 # DS-ResNet: ResNet-50 with a gate in the first block of each stage
 # --------------------------------------------------------------------------
-def resnet_arch(image: int = 224, width_div: int = 1, blocks=(3, 4, 6, 3)) -> dict:
+def resnet_arch(image: int = 224, width_div: int = 1, blocks=(3, 4, 6, 3), routes: str = "width") -> dict:
     """Bottleneck stages with mid width w*q/4 and output width 4w*q/4, q=1..4.
 
-    mid[s][q-1], out[s][q-1] are the valid channel counts of stage s on ratio
-    index q-1.  The 7x7 stem and the max-pool are never sliced.
+    mid[s][t], out[s][t] are the valid channel counts of stage s on route t.  The 7x7 stem and
+    the max-pool are never sliced.  routes="width": 4 routes, one per ratio; "depth": 8 routes,
+    route t has ratio index t // 2 and runs nblk[s][t] = blocks[s] - 1 + t % 2 (at least 1)
+    blocks of stage s.
     """
     widths = [64 // width_div, 128 // width_div, 256 // width_div, 512 // width_div]
     mid = np.array([[w * q // 4 for q in (1, 2, 3, 4)] for w in widths], np.int32)
+    extra = {}
+    if routes == "depth":
+        mid = np.repeat(mid, 2, axis=1)
+        extra["nblk"] = np.array([[max(1, nb - 1 + t % 2) for t in range(8)] for nb in blocks], np.int32)
+    else:
+        assert routes == "width"
     out = 4 * mid
     return {
+        **extra,
         "name": "resnet", "image": image, "stem_out": 64 // width_div, "widths": widths,
-        "blocks": list(blocks), "T": 4, "mid": mid, "out": out.astype(np.int32),
+        "blocks": list(blocks), "T": mid.shape[1], "mid": mid, "out": out.astype(np.int32),
         "gate_hidden": [max(1, (64 // width_div) // 4)] + [max(1, 4 * w // 4) for w in widths[:-1]],
         "num_classes": 1000, "bn_eps": 1e-5,
     }
