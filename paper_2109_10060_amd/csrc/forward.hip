@@ -231,7 +231,7 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
 
 // =====================================================================================
 // DS-ResNet
-//  ints:   image, stem_out, T, num_classes, widths[4], blocks[4], gate_hidden[4], mid[4][T], out[4][T]
+//  ints:   image, stem_out, T, num_classes, widths[4], blocks[4], gate_hidden[4], mid[4][T], out[4][T] [, nblk[4][T]]
 //  params: stem.w [147][stem_out] bf16, stem.scale, stem.shift,
 //          per stage: gate.w1, gate.b1, gate.w2, gate.b2, then per block:
 //             c1.w [w][C_in] bf16, c1.scale, c1.shift [T][w], c2.w [w][3][3][w] bf16, c2.scale, c2.shift,
@@ -242,6 +242,7 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
 struct RnDesc {
     int image, stem_out, T, classes;
     const int32_t *widths, *blocks, *hidden, *mid, *out;
+    const int32_t* nblk;     // [4][T] blocks of a stage that a route runs, or null: every stored block
 };
 
 bool parse_rn(const ds_net* net, RnDesc* d) {
@@ -249,8 +250,13 @@ bool parse_rn(const ds_net* net, RnDesc* d) {
     const int32_t* v = net->ints;
     d->image = v[0]; d->stem_out = v[1]; d->T = v[2]; d->classes = v[3];
     if (d->T < 1 || d->T * d->T > DS_MAX_GROUPS) return false;
-    if (net->n_ints != 4 + 12 + 8 * d->T) return false;
+    if (net->n_ints != 4 + 12 + 8 * d->T && net->n_ints != 4 + 12 + 12 * d->T) return false;
     d->widths = v + 4; d->blocks = v + 8; d->hidden = v + 12; d->mid = v + 16; d->out = d->mid + 4 * d->T;
+    d->nblk = net->n_ints == 4 + 12 + 12 * d->T ? d->out + 4 * d->T : nullptr;
+    if (d->nblk)
+        for (int st = 0; st < 4; ++st)
+            for (int q = 0; q < d->T; ++q)
+                if (d->nblk[st * d->T + q] < 1 || d->nblk[st * d->T + q] > d->blocks[st]) return false;
     int np = 3 + 2;
     for (int s = 0; s < 4; ++s) np += 4 + 9 * d->blocks[s] + 3;
     return net->n_params == np;
@@ -371,6 +377,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
             g3.k_in[id] = d.mid[st * T + q];
             g3.k_out[id] = d.out[st * T + q];
         }
+        const GroupTable g_out = g3;   // output widths of the stage, kept whole while the depth loop empties g3
         // buffers other than X: Y1, Y2, Pj, Z
         bf16_t* free4[4];
         for (int i = 0, k = 0; i < 5; ++i)
@@ -383,6 +390,16 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
             const int rb = first ? rin : rout;  // resolution of the block input
             const void* const* L = Q;
             Q += first ? 12 : 9;
+            if (d.nblk && !first) {
+                // dynamic depth: a route that has run its blocks gets empty slices from here on, so the
+                // kernels leave its slots of Z as they are (the block is an identity through its residual)
+                bool any = false;
+                for (int id = 0; id < G; ++id) {
+                    if (d.nblk[st * T + id / T] > b) { any = true; continue; }
+                    g1.k_in[id] = g1.k_out[id] = g2.k_in[id] = g2.k_out[id] = g3.k_in[id] = g3.k_out[id] = 0;
+                }
+                if (!any) continue;
+            }
             const bf16_t* in = first ? X : Z;
             const int32_t* in_idx = first ? src : nullptr;
             const int64_t in_ss = first ? x_ss : (int64_t)rout * rout * 4 * w;
@@ -409,7 +426,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
                          (const float*)L[7], (const float*)L[8], 4 * w, shortcut, Z, (int64_t)rout * rout * 4 * w, 0,
                          p.offs[st], ml_out, g3, DS_ACT_RELU, s));
         }
-        RC(ds_launch_lookup(p.slot_group[st], g3, 1, p.slot_c, B, s));
+        RC(ds_launch_lookup(p.slot_group[st], g_out, 1, p.slot_c, B, s));
         X = Z;
         for (int i = 0; i < 5; ++i)
             if (p.buf[i] == Z) xi = i;

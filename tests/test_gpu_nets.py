@@ -121,6 +121,30 @@ def test_resnet_small_all_samples(gpu_lib):
     assert relerr(l3[5].cpu().numpy(), want) < TOL
 
 
+def test_resnet_dynamic_depth_small_all_samples(gpu_lib):
+    # 8 routes per stage: 4 widths x (all blocks | one block fewer); 64 groups per stage.  Samples on a
+    # shallow route must come through the skipped blocks untouched while their neighbours are updated.
+    arch = WL.resnet_arch(image=64, width_div=2, blocks=(2, 3, 3, 1), routes="depth")
+    params = WL.resnet_params(arch, S + 45)
+    B = 41
+    imgs = WL.images(S + 46, B, 64)
+    lb = _rn_bias(S + 47, B, 8)
+    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, range(B))
+    rt = routes.cpu().numpy()
+    assert len(np.unique(rt % 2)) == 2          # both depths occur
+    # a batch that is shallow everywhere, and one where whole stages have nothing left to run
+    for pick in ([0, 2, 4, 6], [6, 6, 6, 6], [7, 7, 7, 7]):
+        ov = torch.tensor(pick, dtype=torch.int32, device=DEV)[:, None].expand(4, B).contiguous()
+        l2, _ = gpu_lib.ds_forward(net, xg, route_override=ov)
+        want, _, _ = O.forward_resnet(arch, params, imgs[3], route_override=pick)
+        assert relerr(l2[3].cpu().numpy(), want) < TOL, pick
+    # an ill-formed depth table is rejected
+    bad = dict(arch, nblk=arch["nblk"].copy())
+    bad["nblk"][1, 2] = 4
+    with pytest.raises(Exception):
+        gpu_lib.ds_forward(gpu_lib.build_resnet(bad, params, DEV), xg, logit_bias=lbg)
+
+
 def test_resnet_config4_batch256(gpu_lib):
     arch = WL.resnet_arch()
     params = WL.resnet_params(arch, S + 4)
