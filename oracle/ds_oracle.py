@@ -370,23 +370,15 @@ def patchify(image, patch):
     return x.transpose(1, 3, 0, 2, 4).reshape(gh * gw, c * patch * patch)
 
 
-def forward_vit(arch, p, image, route, store="bf16", taps=None):
-    """DS-ViT with the route given (chosen before the patch embedding): sliced patch
-    embedding (Eq. 15), class token and position embedding sliced to d_e, pre-LN
-    blocks with sliced MHSA (Eq. 16-18) and sliced MLP (Eq. 19), final LayerNorm,
-    classifier on the class token with sliced input width.
-
-    A route may carry a fourth entry, its depth (Section 3.4 lists depth among the dimensions
-    the DS-ViT++ gate controls): the route runs the first `depth` stored blocks and skips the
-    rest, which the residual connections turn into identities (Guideline I of Section 3.1)."""
+def _vit_body(arch, p, tok, route, store, taps):
+    """Class token, position embedding, the route's blocks, final LayerNorm and classifier for
+    one sample whose patch tokens tok [N-1, d_e] (before the position embedding) are given."""
     r = [int(v) for v in arch["routes"][route]]
     d_e, h, hidden = r[:3]
     n_blocks = r[3] if len(r) > 3 else arch["depth"]
     eps = arch["ln_eps"]
-    D = arch["embed"]
     pos = np.asarray(p["pos"], F64)
-    w_embed = np.asarray(p["embed.w"], F64).reshape(D, -1)
-    tok = sliced_linear(patchify(image, arch["patch"]), w_embed, p["embed.b"], d_e) + pos[1:, :d_e]
+    tok = tok + pos[1:, :d_e]
     cls = (np.asarray(p["cls"], F64)[:d_e] + pos[0, :d_e])[None, :]
     x = _store(np.concatenate([cls, tok], axis=0), store)
     for l in range(n_blocks):
@@ -403,6 +395,45 @@ def forward_vit(arch, p, image, route, store="bf16", taps=None):
             taps[pre] = x
     f = _store(layernorm_sliced(x[:1], p["ln.g"], p["ln.b"], eps), store)
     return sliced_linear(f[0], p["head.w"], p["head.b"], arch["num_classes"])
+
+
+def forward_vit(arch, p, image, route, store="bf16", taps=None):
+    """DS-ViT with the route given (chosen before the patch embedding): sliced patch
+    embedding (Eq. 15), class token and position embedding sliced to d_e, pre-LN
+    blocks with sliced MHSA (Eq. 16-18) and sliced MLP (Eq. 19), final LayerNorm,
+    classifier on the class token with sliced input width.
+
+    A route may carry a fourth entry, its depth (Section 3.4 lists depth among the dimensions
+    the DS-ViT++ gate controls): the route runs the first `depth` stored blocks and skips the
+    rest, which the residual connections turn into identities (Guideline I of Section 3.1)."""
+    d_e = int(arch["routes"][route][0])
+    w_embed = np.asarray(p["embed.w"], F64).reshape(arch["embed"], -1)
+    tok = sliced_linear(patchify(image, arch["patch"]), w_embed, p["embed.b"], d_e)
+    return _vit_body(arch, p, tok, route, store, taps)
+
+
+def forward_vit_stem(arch, p, image, logit_bias=None, route_override=None, store="bf16", taps=None):
+    """DS-ViT++ with the efficient stem of Section 3.4: a strided convolution and two
+    depthwise-separable blocks (each layer followed by batch-norm and ReLU, never sliced, width
+    arch["stem_dim"]) run before the gate; the gate (Eq. 21-22) reads the stem's feature map and
+    picks the route; the patch embedding is the stem's last convolution (kernel = stride =
+    arch["patch"], no padding), its filters sliced to the route's d_e (Eq. 15 with the stem's
+    channels as input).  Returns (logits, route, gate scores)."""
+    eps = arch["bn_eps"]
+    C = arch["stem_dim"]
+    x = _conv_bn_relu(np.asarray(image, F64), p["stem.c0.w"], p["stem.c0.bn"], 0, eps, C, 2, 3, store)
+    for i in (1, 2):
+        y = re_sbn(sliced_dwconv2d(x, p[f"stem.ds{i}.dw.w"], 1, 1), p[f"stem.ds{i}.dw.bn"], 0, eps)
+        x = _store(relu(y), store)
+        x = _conv_bn_relu(x, p[f"stem.ds{i}.pw.w"], p[f"stem.ds{i}.pw.bn"], 0, eps, C, 1, 0, store)
+    if taps is not None:
+        taps["stem"] = x
+    z = gate_logits(gate_encoder(x), p["gate.w1"], p["gate.b1"], p["gate.w2"], p["gate.b2"], logit_bias)
+    t = gate_route(z) if route_override is None else int(route_override)
+    d_e = int(arch["routes"][t][0])
+    y = sliced_conv2d(x, p["embed.w"], d_e, arch["patch"], 0)           # [d_e, gh, gw]
+    tok = y.reshape(d_e, -1).T + np.asarray(p["embed.b"], F64)[:d_e]
+    return _vit_body(arch, p, tok, t, store, taps), t, z
 
 
 # --------------------------------------------------------------------------
@@ -440,6 +471,22 @@ def madds_resnet(arch, mids, outs):
             r = ro
         cprev = o
     return total + cprev * arch["num_classes"]
+
+
+def madds_patch_stem(image, d_e, dim, blocks, kernels, strides):
+    """Multiply-adds of a convolutional patch-embedding stem (the table of Section 3.4):
+    blocks[i] is "c" (dense convolution) or "ds" (depthwise + pointwise), all at width `dim`
+    except the last layer, which projects to d_e; padding keeps n/stride output pixels."""
+    r, cin, total = image, 3, 0
+    for i, (kind, k, s) in enumerate(zip(blocks, kernels, strides)):
+        cout = d_e if i == len(blocks) - 1 else dim
+        r = r // s
+        if kind == "c":
+            total += r * r * k * k * cin * cout
+        else:
+            total += r * r * k * k * cin + r * r * cin * cout
+        cin = cout
+    return total
 
 
 def madds_vit(arch, d_e, h, hidden):

@@ -210,12 +210,17 @@ def resnet_params(arch: dict, seed: int) -> dict:
 # DS-ViT: DeiT-S-shaped transformer, one route per image chosen before the patch embed
 # --------------------------------------------------------------------------
 def vit_arch(image: int = 224, patch: int = 16, embed: int = 384, heads: int = 6,
-             head_dim: int = 64, mlp: int = 1536, depth: int = 12, routes: str = "cross") -> dict:
+             head_dim: int = 64, mlp: int = 1536, depth: int = 12, routes: str = "cross",
+             stem_dim: int = 0) -> dict:
     """routes[t] = (d_e, h, hidden): embedding slice, head count and MLP hidden slice.
 
     "cross": every combination of 4 embedding slices, 4 head counts and MLP
     ratios 2,3,4 (hidden = ratio * d_e); "diag": 4 nested routes; "depth": the 4 nested
     routes, each at 3 depths (depth - 2, depth - 1, depth), as (d_e, h, hidden, blocks).
+
+    stem_dim > 0: the convolutional stem of Section 3.4 (7x7 stride-2 convolution and two
+    depthwise-separable blocks at stem_dim channels, then the gate) precedes the patch embedding,
+    which then is a patch x patch stride-patch convolution over the stem's half-resolution map.
     """
     step = embed // 6
     de_list = [3 * step, 4 * step, 5 * step, 6 * step]
@@ -232,7 +237,12 @@ def vit_arch(image: int = 224, patch: int = 16, embed: int = 384, heads: int = 6
     else:
         raise ValueError(routes)
     n_tok = (image // patch) ** 2 + 1
+    extra = {}
+    if stem_dim:
+        n_tok = (image // 2 // patch) ** 2 + 1
+        extra = {"stem_dim": stem_dim, "gate_hidden": 16, "bn_eps": 1e-5}
     return {
+        **extra,
         "name": "vit", "image": image, "patch": patch, "embed": embed, "heads": heads,
         "head_dim": head_dim, "mlp": mlp, "depth": depth, "tokens": n_tok,
         "routes": np.array(table, np.int32), "T": len(table), "num_classes": 1000, "ln_eps": 1e-6,
@@ -246,7 +256,8 @@ def vit_params(arch: dict, seed: int) -> dict:
     std = 0.02
     bf = as_bf16_values
     p = {}
-    p["embed.w"] = bf(d.normal((D, 3, P, P), std=std))
+    C = arch.get("stem_dim", 0)
+    p["embed.w"] = bf(d.normal((D, C if C else 3, P, P), std=std))
     p["embed.b"] = d.normal((D,), std=std)
     p["cls"] = bf(d.normal((D,), std=std))
     p["pos"] = bf(d.normal((arch["tokens"], D), std=std))
@@ -269,4 +280,17 @@ def vit_params(arch: dict, seed: int) -> dict:
     p["ln.b"] = d.normal((D,), std=std)
     p["head.w"] = bf(d.normal((arch["num_classes"], D), std=std))
     p["head.b"] = d.normal((arch["num_classes"],), std=std)
+    if C:
+        T, hid = arch["T"], arch["gate_hidden"]
+        p["stem.c0.w"] = bf(_kaiming(d, (C, 3, 7, 7)))
+        p["stem.c0.bn"] = bn_tables(d, 1, C)
+        for i in (1, 2):
+            p[f"stem.ds{i}.dw.w"] = bf(_kaiming(d, (C, 1, 3, 3)))
+            p[f"stem.ds{i}.dw.bn"] = bn_tables(d, 1, C)
+            p[f"stem.ds{i}.pw.w"] = bf(_kaiming(d, (C, C, 1, 1)))
+            p[f"stem.ds{i}.pw.bn"] = bn_tables(d, 1, C)
+        p["gate.w1"] = d.normal((hid, C), std=C ** -0.5)
+        p["gate.b1"] = d.normal((hid,), std=0.1)
+        p["gate.w2"] = d.normal((T, hid), std=hid ** -0.5)
+        p["gate.b2"] = d.normal((T,), std=0.1)
     return p
