@@ -211,6 +211,19 @@ int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D_e, const v
  *           ln.g, ln.b, head.w bf16 [num_classes][embed], head.b.
  *   Routes come from logit_bias (argmax) or route_override; one of them is required. */
 #define DS_ARCH_VIT    3
+/* DS_ARCH_VIT_STEM: DS_ARCH_VIT behind the convolutional stem of Section 3.4 (blocks [c, ds, ds, c]): a 7x7
+ * stride-2 padding-3 convolution and two depthwise-separable blocks (3x3 depthwise, 1x1 pointwise), each
+ * layer with folded batch-norm and ReLU, all at stem_dim channels and never sliced; the gate (Eq. 21-22)
+ * pools the stem's feature map and picks the route (logit_bias and route_override optional, as for the
+ * CNNs); the patch embedding is the stem's last convolution, patch x patch with stride patch and no
+ * padding over that map, its filters sliced to the route's d_e.  tokens = ((image / 2) / patch)^2 + 1.
+ *   ints:   image, patch, embed, heads, head_dim, mlp, depth, tokens, T, num_classes,
+ *           rs (3 or 4 entries per route), stem_dim (multiple of 8, <= 64), gate_hidden, routes[T][rs]
+ *   params: stem.c0.w bf16 [7*7*3][stem_dim], stem.c0.scale, stem.c0.shift fp32 [stem_dim],
+ *           2 x (dw.w bf16 [3][3][C], dw.scale, dw.shift fp32 [C], pw.w bf16 [C][C], pw.scale, pw.shift),
+ *           gate.w1 [gate_hidden][C], gate.b1, gate.w2 [T][gate_hidden], gate.b2 (fp32),
+ *           embed.w bf16 [embed][patch][patch][C], then as DS_ARCH_VIT from embed.b on. */
+#define DS_ARCH_VIT_STEM 4
 typedef struct ds_net {
     int32_t arch;
     int32_t n_ints;

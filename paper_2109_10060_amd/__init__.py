@@ -26,7 +26,7 @@ DS_F32, DS_BF16 = 0, 1
 DS_NCHW, DS_NHWC = 0, 1
 DS_ACT_NONE, DS_ACT_RELU, DS_ACT_GELU = 0, 1, 2
 DS_MAX_GROUPS = 64
-DS_ARCH_MBNET, DS_ARCH_RESNET, DS_ARCH_VIT = 1, 2, 3
+DS_ARCH_MBNET, DS_ARCH_RESNET, DS_ARCH_VIT, DS_ARCH_VIT_STEM = 1, 2, 3, 4
 
 EXPORTS = [
     "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_gate_double_workspace",

@@ -92,10 +92,23 @@ def vit_cost(arch, routes) -> Cost:
     de, h, hid = tab[:, 0], tab[:, 1], tab[:, 2]
     hd = h * arch["head_dim"]
     N, B = arch["tokens"], routes.shape[0]
-    kp = 3 * arch["patch"] ** 2
     c = Cost()
-    c.add("index", 0.0, 2.0 * 2 * B * (N - 1) * kp)                                 # patch extraction
-    _gemm(c, "gemm", N - 1, N - 1, 1, np.full(B, kp), de)
+    C = arch.get("stem_dim", 0)
+    if C:
+        r = _osz(arch["image"], 7, 2, 3)
+        full = np.full(B, C, np.float64)
+        c.add("stem", 2.0 * B * r * r * 147 * C, B * (3 * arch["image"] ** 2 * 2 + r * r * C * 2))
+        for _ in range(2):
+            c.add("dwconv", 2.0 * B * r * r * 9 * C, 2.0 * 2 * B * r * r * C)
+            _gemm(c, "gemm", r * r, r * r, 1, full, full)
+        c.add("gate", 2.0 * B * r * r * C, 2.0 * B * r * r * C)
+        # the patch projection reads every pixel of the stem's map once
+        _gemm(c, "gemm_taps", (N - 1) * arch["patch"] ** 2, N - 1, 1, full, de)
+        c["gemm_taps"]["flops"] += 2.0 * (N - 1) * (arch["patch"] ** 2 - 1) * C * de.sum()
+    else:
+        kp = 3 * arch["patch"] ** 2
+        c.add("index", 0.0, 2.0 * 2 * B * (N - 1) * kp)                             # patch extraction
+        _gemm(c, "gemm", N - 1, N - 1, 1, np.full(B, kp), de)
     for _ in range(arch["depth"]):
         c.add("layernorm", 8.0 * N * de.sum(), 4.0 * N * de.sum())
         k_in, k_out = de, 3 * hd

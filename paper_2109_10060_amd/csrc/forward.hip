@@ -451,11 +451,22 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
 //                     ln2.g, ln2.b, fc1.w [mlp][D] bf16, fc1.b, fc2.w [D][mlp] bf16, fc2.b,
 //          ln.g, ln.b, head.w [classes][D] bf16, head.b
 // =====================================================================================
+//
+// DS-ViT++ with the convolutional stem (DS_ARCH_VIT_STEM): 7x7 stride-2 convolution and two depthwise-separable
+// blocks at stem_dim channels, the gate on that map, and the patch embedding as a patch x patch stride-patch
+// convolution over it.
+//  ints:   image, patch, embed, heads, head_dim, mlp, depth, tokens, T, num_classes, rs, stem_dim, gate_hidden,
+//          routes[T][rs]
+//  params: stem.c0.w [7*7*3][stem_dim] bf16, scale, shift, 2 x (dw.w [3][3][C] bf16, dw.scale, dw.shift,
+//          pw.w [C][C] bf16, pw.scale, pw.shift), gate.w1, gate.b1, gate.w2, gate.b2,
+//          embed.w [D][patch][patch][C] bf16, then as above from embed.b on
 struct VitDesc {
     int image, patch, D, H, dh, M, depth, N, T, classes;
     int rs;                  // entries per route: 3 (d_e, heads, hidden) or 4 (+ number of blocks the route runs)
+    int stem_dim, gate_hidden, pbase;   // stem width (0: none), gate MLP width, index of embed.w in params
     const int32_t* routes;
 };
+constexpr int VIT_STEM_PARAMS = 3 + 12 + 4;
 
 bool parse_vit(const ds_net* net, VitDesc* d) {
     if (net->n_ints < 10) return false;
@@ -463,24 +474,48 @@ bool parse_vit(const ds_net* net, VitDesc* d) {
     d->image = v[0]; d->patch = v[1]; d->D = v[2]; d->H = v[3]; d->dh = v[4]; d->M = v[5]; d->depth = v[6];
     d->N = v[7]; d->T = v[8]; d->classes = v[9];
     if (d->T < 1 || d->T > DS_MAX_GROUPS) return false;
-    if (net->n_ints == 10 + 3 * d->T) d->rs = 3;
-    else if (net->n_ints == 10 + 4 * d->T) d->rs = 4;
-    else return false;
-    d->routes = v + 10;
-    return net->n_params == 4 + 12 * d->depth + 4;
+    d->stem_dim = d->gate_hidden = d->pbase = 0;
+    if (net->arch == DS_ARCH_VIT_STEM) {
+        if (net->n_ints < 13) return false;
+        d->rs = v[10]; d->stem_dim = v[11]; d->gate_hidden = v[12];
+        if ((d->rs != 3 && d->rs != 4) || net->n_ints != 13 + d->rs * d->T) return false;
+        if (d->stem_dim < 8 || d->gate_hidden < 1) return false;
+        d->routes = v + 13;
+        d->pbase = VIT_STEM_PARAMS;
+    } else {
+        if (net->n_ints == 10 + 3 * d->T) d->rs = 3;
+        else if (net->n_ints == 10 + 4 * d->T) d->rs = 4;
+        else return false;
+        d->routes = v + 10;
+    }
+    return net->n_params == d->pbase + 4 + 12 * d->depth + 4;
 }
 
 struct VitPlan {
     bf16_t *patches, *x, *a, *qkv, *o, *h;
+    bf16_t *sa, *sb;          // the stem's two feature maps
     size_t qkv_seg;
-    float* gate_logits;
-    int32_t *offs, *perm, *inv, *slot_group, *route, *slot_c;
-    void *list_p, *list_t;
+    float *gate_logits, *gate_partial;
+    int32_t *off1, *offs, *perm, *inv, *slot_group, *route, *slot_c;
+    void *list_p, *list_t, *list_s;
 };
+
+inline int vit_stem_res(const VitDesc& d) { return (d.image + 6 - 7) / 2 + 1; }
 
 void plan_vit(const VitDesc& d, int B, Bump& bp, VitPlan* p) {
     const int np = d.N - 1, kp = 3 * d.patch * d.patch, Hd = d.H * d.dh;
-    p->patches = bp.take<bf16_t>((size_t)B * np * kp);
+    p->patches = p->sa = p->sb = nullptr;
+    p->gate_partial = nullptr; p->off1 = nullptr; p->list_s = nullptr;
+    if (d.stem_dim) {
+        const int r = vit_stem_res(d);
+        p->sa = bp.take<bf16_t>((size_t)B * r * r * d.stem_dim);
+        p->sb = bp.take<bf16_t>((size_t)B * r * r * d.stem_dim);
+        p->gate_partial = bp.take<float>(ds_gate_partial_bytes(B, d.stem_dim) / sizeof(float));
+        p->off1 = bp.take<int32_t>(2);
+        p->list_s = bp.take<char>(16 + ds_mtile_capacity(B, r * r, 1) * 16);
+    } else {
+        p->patches = bp.take<bf16_t>((size_t)B * np * kp);
+    }
     p->x = bp.take<bf16_t>((size_t)B * d.N * d.D);
     p->a = bp.take<bf16_t>((size_t)B * d.N * d.D);
     p->qkv_seg = ds_align_up((size_t)B * d.N * Hd, 128);
@@ -517,14 +552,42 @@ int32_t linear_gemm(const bf16_t* A, int64_t a_ss, int a_ld, const bf16_t* Wt, i
 
 int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, int B, const int32_t* route_override,
                     const float* logit_bias, float* logits, int32_t* routes_out, const VitPlan& p, hipStream_t s) {
-    const void* const* P = net->params;
-    const int np = d.N - 1, kp = 3 * d.patch * d.patch, Hd = d.H * d.dh, T = d.T;
-    if (!logit_bias && !route_override) DS_FAIL(DS_EINVAL, "ds_forward(vit): routes need logit_bias or route_override");
+    const void* const* P = net->params + d.pbase;
+    const int np = d.N - 1, Hd = d.H * d.dh, T = d.T;
+    const int kp = d.stem_dim ? d.stem_dim : 3 * d.patch * d.patch;   // reduction length of one embedding tap
+    if (!d.stem_dim && !logit_bias && !route_override)
+        DS_FAIL(DS_EINVAL, "ds_forward(vit): routes need logit_bias or route_override");
     int32_t* route = routes_out ? routes_out : p.route;
     GateArgs g;
     memset(&g, 0, sizeof(g));
     g.B = B; g.T = T; g.logit_bias = logit_bias; g.route_override = route_override;
     g.logits = p.gate_logits; g.route = route;
+    const int sr = vit_stem_res(d);
+    if (d.stem_dim) {
+        // stem: every sample at full width, original order; the gate pools its last feature map
+        const void* const* S = net->params;
+        const int C = d.stem_dim;
+        const int64_t map = (int64_t)sr * sr * C;
+        RC(ds_launch_set_offsets(p.off1, B, s));
+        RC(ds_launch_stem(images, nullptr, p.sa, (const bf16_t*)S[0], (const float*)S[1], (const float*)S[2], B, d.image,
+                          d.image, 7, 2, 3, C, s));
+        MList ml_s = {p.list_s, (int)ds_mtile_capacity(B, sr * sr, 1), sr * sr};
+        RC(ds_build_mtiles(p.off1, 1, sr * sr, ml_s.list, s));
+        const GroupTable g1c = table1(C, C);
+        for (int i = 0; i < 2; ++i) {
+            const void* const* Q = S + 3 + 6 * i;
+            ActView xv = {p.sa, nullptr, map, C}, yv = {p.sb, nullptr, map, C};
+            RC(ds_launch_dwconv(xv, yv, (const bf16_t*)Q[0], (const float*)Q[1], (const float*)Q[2], C, nullptr, g1c, B, C,
+                                sr, sr, 1, DS_ACT_RELU, s));
+            RC(conv_gemm(p.sb, nullptr, map, C, (const bf16_t*)Q[3], C, 1, 1, 0, sr, sr, (const float*)Q[4],
+                         (const float*)Q[5], C, nullptr, p.sa, map, C, p.off1, ml_s, g1c, DS_ACT_RELU, s));
+        }
+        const void* const* G = S + 15;
+        g.x = p.sa; g.dtype = DS_BF16; g.layout = DS_NHWC; g.C = C; g.HW = sr * sr;
+        g.x_sample_stride = map; g.x_ld = C;
+        g.w1 = (const float*)G[0]; g.b1 = (const float*)G[1]; g.w2 = (const float*)G[2]; g.b2 = (const float*)G[3];
+        g.C_mlp = d.gate_hidden; g.partial = p.gate_partial;
+    }
     RC(ds_launch_gate(g, s));
     RC(ds_launch_bucket(route, B, T, p.perm, p.inv, p.offs, p.slot_group, s));
     MList ml_p = {p.list_p, (int)ds_mtile_capacity(B, np, T), np};
@@ -545,10 +608,28 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
         g2.k_in[t] = hid; g2.k_out[t] = de;
     }
     const int64_t x_ss = (int64_t)d.N * d.D;
-    RC(ds_launch_patchify(images, p.perm, p.patches, B, d.image, d.image, d.patch, s));
-    // tokens 1..N-1: patch embedding + bias + position embedding (broadcast over samples)
-    RC(linear_gemm(p.patches, (int64_t)np * kp, kp, (const bf16_t*)P[0], kp, (const float*)P[1], (const bf16_t*)P[3], 0,
-                   d.D, 0, p.x, x_ss, 0, 1, np, 1, 0, 0, 0, p.offs, ml_p, ge, DS_ACT_NONE, s));
+    if (d.stem_dim) {
+        // tokens 1..N-1: the stem's last convolution (kernel = stride = patch) over each sample's map, read through
+        // the bucket permutation, + bias + position embedding (broadcast over samples)
+        GemmArgs a;
+        memset(&a, 0, sizeof(a));
+        const int C = d.stem_dim, gw = sr / d.patch;
+        a.A = p.sa; a.Wt = (const bf16_t*)P[0]; a.C = p.x; a.R = (const bf16_t*)P[3];
+        a.scale = nullptr; a.shift = (const float*)P[1]; a.tab_ld = 0;
+        a.a_index = p.perm; a.c_index = nullptr;
+        a.a_sample_stride = (int64_t)sr * sr * C; a.c_sample_stride = x_ss; a.r_sample_stride = 0;
+        a.a_ld = C; a.c_ld = 0; a.r_ld = d.D; a.c_row0 = 1; a.r_use_index = 0;
+        a.w_ld = (int64_t)d.patch * d.patch * C; a.w_tap_stride = C; a.n_seg = 1;
+        a.H = sr; a.W = sr; a.Ho = gw; a.Wo = gw; a.K = d.patch; a.stride = d.patch; a.pad = 0; a.rows = np;
+        a.offsets = p.offs; a.mtiles = ds_mtile_entries(ml_p.list); a.n_mtiles = ds_mtile_count(ml_p.list);
+        a.act = DS_ACT_NONE; a.out_f32 = 0; a.gt = ge;
+        RC(ds_launch_gemm(a, ml_p.cap, max_out(ge), s));
+    } else {
+        RC(ds_launch_patchify(images, p.perm, p.patches, B, d.image, d.image, d.patch, s));
+        // tokens 1..N-1: patch embedding + bias + position embedding (broadcast over samples)
+        RC(linear_gemm(p.patches, (int64_t)np * kp, kp, (const bf16_t*)P[0], kp, (const float*)P[1], (const bf16_t*)P[3], 0,
+                       d.D, 0, p.x, x_ss, 0, 1, np, 1, 0, 0, 0, p.offs, ml_p, ge, DS_ACT_NONE, s));
+    }
     ActView xv = {p.x, nullptr, x_ss, 0}, av = {p.a, nullptr, x_ss, 0};
     RC(ds_launch_cls_rows(xv, (const bf16_t*)P[2], (const bf16_t*)P[3], p.slot_group, gq, B, s));
     const float eps = 1e-6f;
@@ -605,7 +686,7 @@ extern "C" size_t ds_forward_workspace(const ds_net* net, int32_t B) {
         RnPlan p;
         if (!parse_rn(net, &d)) return 0;
         plan_rn(d, B, bp, &p);
-    } else if (net->arch == DS_ARCH_VIT) {
+    } else if (net->arch == DS_ARCH_VIT || net->arch == DS_ARCH_VIT_STEM) {
         VitDesc d;
         VitPlan p;
         if (!parse_vit(net, &d)) return 0;
@@ -655,9 +736,16 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
     VitDesc d;
     VitPlan p;
     parse_vit(net, &d);
-    if (d.dh != 64 || d.N > 224 || (d.image % d.patch) || d.N != (d.image / d.patch) * (d.image / d.patch) + 1 ||
-        (d.patch % 8))
+    if (d.stem_dim) {
+        const int sr = vit_stem_res(d);
+        if (d.dh != 64 || d.N > 224 || d.patch < 1 || (sr % d.patch) || d.N != (sr / d.patch) * (sr / d.patch) + 1)
+            DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 64, tokens <= 224, patch dividing the stem's map", who);
+        if ((d.stem_dim % 8) || d.stem_dim > 64)
+            DS_FAIL(DS_EALIGN, "%s: stem width must be a multiple of 8, at most 64", who);
+    } else if (d.dh != 64 || d.N > 224 || (d.image % d.patch) || d.N != (d.image / d.patch) * (d.image / d.patch) + 1 ||
+               (d.patch % 8)) {
         DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 64, tokens <= 224, patch %% 8 == 0", who);
+    }
     for (int t = 0; t < d.T; ++t) {
         const int32_t* r = d.routes + d.rs * t;
         if (r[1] < 1 || r[1] > d.H) DS_FAIL(DS_EINVAL, "%s: head count outside 1..%d", who, d.H);

@@ -31,33 +31,37 @@ __device__ __forceinline__ void load8<float>(const float* p, float* v) {
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
+// NHWC: grid (items, splits), block 256.  The block is shaped to the channel count: CL = 2^lcl lanes
+// (8 channels each) across the channels, 256 / CL rows of the map in flight per step, so narrow maps
+// (24 or 64 channels) keep every lane loading.
 template <typename T>
-__global__ __launch_bounds__(256) void pool_nhwc_kernel(const GateArgs a, int splits) {
-    __shared__ float red[8][256 + 8];
+__global__ __launch_bounds__(256) void pool_nhwc_kernel(const GateArgs a, int splits, int lcl) {
+    __shared__ float red[256 * 16];   // (256 >> lcl) rows of (8 << lcl) + 8 floats
     const int item = blockIdx.x, sp = blockIdx.y;
     const int c = a.c_in ? a.c_in[item] : a.C;
     const int sample = a.x_index ? a.x_index[item] : item;
     const int ld = a.x_ld > 0 ? a.x_ld : c;
     const T* x = (const T*)a.x + (int64_t)sample * a.x_sample_stride;
-    const int lane_c = threadIdx.x & 31, lane_r = threadIdx.x >> 5;
+    const int CL = 1 << lcl, R = 256 >> lcl, red_ld = CL * 8 + 8;
+    const int lane_c = threadIdx.x & (CL - 1), lane_r = threadIdx.x >> lcl;
     const int per = (a.HW + splits - 1) / splits;
     const int r0 = sp * per, r1 = min(a.HW, r0 + per);
-    for (int c0 = 0; c0 < c; c0 += 256) {
+    for (int c0 = 0; c0 < c; c0 += CL * 8) {
         const int ch = c0 + lane_c * 8;
         float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (ch < c) {
             // four rows in flight per lane: the loads are independent, only the adds chain
             int r = r0 + lane_r;
-            for (; r + 24 < r1; r += 32) {
+            for (; r + 3 * R < r1; r += 4 * R) {
                 float v[4][8];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) load8<T>(x + (int64_t)(r + 8 * k) * ld + ch, v[k]);
+                for (int k = 0; k < 4; ++k) load8<T>(x + (int64_t)(r + R * k) * ld + ch, v[k]);
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
 #pragma unroll
                     for (int i = 0; i < 8; ++i) s[i] += v[k][i];
             }
-            for (; r < r1; r += 8) {
+            for (; r < r1; r += R) {
                 float v[8];
                 load8<T>(x + (int64_t)r * ld + ch, v);
 #pragma unroll
@@ -65,13 +69,12 @@ __global__ __launch_bounds__(256) void pool_nhwc_kernel(const GateArgs a, int sp
             }
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) red[lane_r][lane_c * 8 + i] = s[i];
+        for (int i = 0; i < 8; ++i) red[lane_r * red_ld + lane_c * 8 + i] = s[i];
         __syncthreads();
         const int cc = c0 + threadIdx.x;
-        if (cc < c) {
+        if (threadIdx.x < CL * 8 && cc < c) {
             float t = 0.f;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) t += red[r][threadIdx.x];
+            for (int r = 0; r < R; ++r) t += red[r * red_ld + threadIdx.x];
             a.partial[((int64_t)item * splits + sp) * a.C + cc] = t;
         }
         __syncthreads();
@@ -206,8 +209,10 @@ int32_t ds_launch_pool(const GateArgs& a, int32_t kind, int32_t* splits_out, hip
     if (a.layout == DS_NHWC) {
         splits = a.HW >= 2048 ? 8 : (a.HW >= 512 ? 4 : (a.HW >= 128 ? 2 : 1));
         dim3 grid(a.B, splits);
-        if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nhwc_kernel<bf16_t>, grid, dim3(256), 0, s, a, splits);
-        else hipLaunchKernelGGL(pool_nhwc_kernel<float>, grid, dim3(256), 0, s, a, splits);
+        int lcl = 0;
+        while ((8 << lcl) < a.C && lcl < 5) ++lcl;   // lanes across the channels: 2^lcl * 8 >= C, at most 32
+        if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nhwc_kernel<bf16_t>, grid, dim3(256), 0, s, a, splits, lcl);
+        else hipLaunchKernelGGL(pool_nhwc_kernel<float>, grid, dim3(256), 0, s, a, splits, lcl);
     } else {
         dim3 grid(a.B, (a.C + 3) / 4);
         if (a.dtype == DS_BF16) hipLaunchKernelGGL(pool_nchw_kernel<bf16_t>, grid, dim3(256), 0, s, a);

@@ -17,7 +17,9 @@ template <int KS, int PAD, int VP, int NTILES>
 __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict__ img, const int32_t* index,
                                                         bf16_t* __restrict__ y, const bf16_t* __restrict__ w,
                                                         const float* scale, const float* shift, int H, int W, int Ho,
-                                                        int Wo, int tiles_x, int tiles_y, int total_tiles) {
+                                                        int Wo, int tiles_x, int tiles_y, int total_tiles, int cout) {
+    // cout <= COUT filters are stored ([taps][cout]) and written (cout channels per pixel); the matrix
+    // columns beyond them carry zero weights and are dropped
     constexpr int COUT = NTILES * 32, PAIRS = 3 * KS, KP = ((PAIRS * VP + 15) / 16) * 16, KSTEPS = KP / 16;
     constexpr int W_LD = KP + 8, TH = 8, TW = 16, PR = 2 * TH + KS - 2, PC = 40, CBASE = 4 - PAD - 1;
     __shared__ __attribute__((aligned(16))) bf16_t Wl[COUT * W_LD];
@@ -29,7 +31,7 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
         const int pair = k / VP, e = k - pair * VP;
         const int c = pair / KS, u = pair - c * KS, v = e - 1;
         bf16_t val = 0;
-        if (pair < PAIRS && v >= 0 && v < KS) val = w[((u * KS + v) * 3 + c) * COUT + n];
+        if (pair < PAIRS && v >= 0 && v < KS && n < cout) val = w[((u * KS + v) * 3 + c) * cout + n];
         Wl[n * W_LD + k] = val;
     }
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
@@ -37,8 +39,8 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
     float sc[NTILES], sh[NTILES];
 #pragma unroll
     for (int t = 0; t < NTILES; ++t) {
-        sc[t] = scale[t * 32 + l32];
-        sh[t] = shift[t * 32 + l32];
+        sc[t] = t * 32 + l32 < cout ? scale[t * 32 + l32] : 0.f;
+        sh[t] = t * 32 + l32 < cout ? shift[t * 32 + l32] : 0.f;
     }
     for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
         const int slot = tile / (tiles_x * tiles_y);
@@ -86,9 +88,10 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
             const int i = 8 * (e >> 2) + 4 * lhi + (e & 3);
             const int oy = oy0 + wave * 2 + (i >> 4), ox = ox0 + (i & 15);
             if (oy < Ho && ox < Wo) {
-                bf16_t* op = y + (((int64_t)slot * Ho + oy) * Wo + ox) * COUT + l32;
+                bf16_t* op = y + (((int64_t)slot * Ho + oy) * Wo + ox) * cout + l32;
 #pragma unroll
-                for (int t = 0; t < NTILES; ++t) op[t * 32] = f2bf(fmaxf(acc[t][e] * sc[t] + sh[t], 0.f));
+                for (int t = 0; t < NTILES; ++t)
+                    if (t * 32 + l32 < cout) op[t * 32] = f2bf(fmaxf(acc[t][e] * sc[t] + sh[t], 0.f));
             }
         }
     }
@@ -224,13 +227,13 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
 
 template <int KS, int PAD, int VP, int NTILES>
 int32_t launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
-                    const float* shift, int B, int H, int W, int Ho, int Wo, hipStream_t s) {
+                    const float* shift, int B, int H, int W, int Ho, int Wo, int cout, hipStream_t s) {
     const int tiles_x = (Wo + 15) / 16, tiles_y = (Ho + 7) / 8;
     const long long total = (long long)B * tiles_x * tiles_y;
     const int grid = (int)(total < 256 * 5 ? total : 256 * 5);
     ProfScope prof(DS_K_STEM, s);
     hipLaunchKernelGGL((stem_mfma_kernel<KS, PAD, VP, NTILES>), dim3(grid), dim3(256), 0, s, img, index, y, w, scale, shift,
-                       H, W, Ho, Wo, tiles_x, tiles_y, (int)total);
+                       H, W, Ho, Wo, tiles_x, tiles_y, (int)total, cout);
     DS_CHECK_LAUNCH("stem conv (mfma)");
     return DS_OK;
 }
@@ -262,9 +265,10 @@ int32_t ds_launch_stem_mfma(const bf16_t* img, const int32_t* index, bf16_t* y, 
                             int32_t pad, int32_t Cout, hipStream_t s) {
     if (stride != 2 || (W % 4) != 0) return DS_EUNSUPPORTED;
     const int Ho = (H + 2 * pad - K) / 2 + 1, Wo = (W + 2 * pad - K) / 2 + 1;
-    if (K == 7 && pad == 3 && Cout == 64) return launch_stem<7, 3, 8, 2>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, s);
-    if (K == 7 && pad == 3 && Cout == 32) return launch_stem<7, 3, 8, 1>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, s);
-    if (K == 3 && pad == 1 && Cout == 32) return launch_stem<3, 1, 4, 1>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, s);
-    if (K == 3 && pad == 1 && Cout == 64) return launch_stem<3, 1, 4, 2>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, s);
+    if (Cout < 1 || Cout > 64) return DS_EUNSUPPORTED;
+    if (K == 7 && pad == 3 && Cout > 32) return launch_stem<7, 3, 8, 2>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, Cout, s);
+    if (K == 7 && pad == 3) return launch_stem<7, 3, 8, 1>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, Cout, s);
+    if (K == 3 && pad == 1 && Cout > 32) return launch_stem<3, 1, 4, 2>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, Cout, s);
+    if (K == 3 && pad == 1) return launch_stem<3, 1, 4, 1>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, Cout, s);
     return DS_EUNSUPPORTED;
 }

@@ -101,13 +101,28 @@ def build_resnet(arch: dict, p: dict, device="cuda:0") -> Net:
 
 
 def build_vit(arch: dict, p: dict, device="cuda:0") -> Net:
-    from . import DS_ARCH_VIT
+    from . import DS_ARCH_VIT, DS_ARCH_VIT_STEM
     bf, f32 = torch.bfloat16, torch.float32
     D = arch["embed"]
+    C = arch.get("stem_dim", 0)
     ints = [arch["image"], arch["patch"], D, arch["heads"], arch["head_dim"], arch["mlp"], arch["depth"],
-            arch["tokens"], arch["T"], arch["num_classes"], *arch["routes"].reshape(-1).tolist()]
-    t = [_dev(p["embed.w"].reshape(D, -1), bf, device), _dev(p["embed.b"], f32, device), _dev(p["cls"], bf, device),
-         _dev(p["pos"], bf, device)]
+            arch["tokens"], arch["T"], arch["num_classes"]]
+    t = []
+    if C:
+        eps = arch["bn_eps"]
+        ints += [arch["routes"].shape[1], C, arch["gate_hidden"]]
+        t += [_stem(p["stem.c0.w"], device), *_fold(p["stem.c0.bn"], eps, device)]
+        for i in (1, 2):
+            t.append(_dev(np.transpose(p[f"stem.ds{i}.dw.w"][:, 0], (1, 2, 0)), bf, device))
+            t += list(_fold(p[f"stem.ds{i}.dw.bn"], eps, device))
+            t.append(_dev(p[f"stem.ds{i}.pw.w"][:, :, 0, 0], bf, device))
+            t += list(_fold(p[f"stem.ds{i}.pw.bn"], eps, device))
+        t += [_dev(p[k], f32, device) for k in ("gate.w1", "gate.b1", "gate.w2", "gate.b2")]
+        t.append(_ohwi(p["embed.w"], device))
+    else:
+        t.append(_dev(p["embed.w"].reshape(D, -1), bf, device))
+    ints += arch["routes"].reshape(-1).tolist()
+    t += [_dev(p["embed.b"], f32, device), _dev(p["cls"], bf, device), _dev(p["pos"], bf, device)]
     for l in range(arch["depth"]):
         q = f"l{l}"
         t += [_dev(p[q + ".ln1.g"], f32, device), _dev(p[q + ".ln1.b"], f32, device),
@@ -119,4 +134,4 @@ def build_vit(arch: dict, p: dict, device="cuda:0") -> Net:
               _dev(p[q + ".fc2.w"], bf, device), _dev(p[q + ".fc2.b"], f32, device)]
     t += [_dev(p["ln.g"], f32, device), _dev(p["ln.b"], f32, device), _dev(p["head.w"], bf, device),
           _dev(p["head.b"], f32, device)]
-    return Net(DS_ARCH_VIT, ints, t, arch["num_classes"], 1, arch["T"])
+    return Net(DS_ARCH_VIT_STEM if C else DS_ARCH_VIT, ints, t, arch["num_classes"], 1, arch["T"])

@@ -205,6 +205,62 @@ def test_vit_dynamic_depth_small_all_samples(gpu_lib):
     _vit_case(gpu_lib, arch0, params, imgs[:6], lb[:6], range(6))
 
 
+def _vit_stem_case(gpu_lib, arch, params, imgs, lb, check):
+    net = gpu_lib.build_vit(arch, params, DEV)
+    xg, lbg = dev(imgs, torch.bfloat16), dev(lb[None], torch.float32)
+    logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
+    torch.cuda.synchronize()
+    lg, rt = logits.cpu().numpy(), routes.cpu().numpy()[0]
+    worst = 0.0
+    for b in check:
+        want, ro, z = O.forward_vit_stem(arch, params, imgs[b], logit_bias=lb[b])
+        if int(rt[b]) != ro:
+            # the gate reads bf16 stem features: it may only disagree inside that noise
+            assert O.gate_margin(z) < 2e-2 * np.max(np.abs(z)), (b, rt[b], ro, z)
+            want, _, _ = O.forward_vit_stem(arch, params, imgs[b], logit_bias=lb[b], route_override=int(rt[b]))
+        worst = max(worst, relerr(lg[b], want))
+    assert worst < TOL, worst
+    return net, xg, lbg, logits, routes
+
+
+@pytest.mark.parametrize("stem_dim,routes", [(24, "diag"), (8, "depth")])
+def test_vit_stem_small_all_samples(gpu_lib, stem_dim, routes):
+    # 64x64 images -> 32x32 stem map -> 4x4 patches of 8x8 (+ class token): 17 tokens, DeiT-S widths
+    arch = WL.vit_arch(image=64, patch=8, depth=2, routes=routes, stem_dim=stem_dim)
+    assert arch["tokens"] == 17
+    params = WL.vit_params(arch, S + 70)
+    B = 29
+    imgs = WL.images(S + 71, B, 64)
+    lb = WL.seeded_logit_bias(S + 72, B, arch["T"], amp=16.0)
+    net, xg, lbg, logits, rt = _vit_stem_case(gpu_lib, arch, params, imgs, lb, range(B))
+    assert len(set(rt.cpu().numpy()[0].tolist())) == arch["T"]
+    # forced routes reproduce the free-running logits; the gate also runs without any bias
+    l2, _ = gpu_lib.ds_forward(net, xg, route_override=rt.clone())
+    assert torch.equal(l2, logits)
+    l3, r3 = gpu_lib.ds_forward(net, xg)
+    want, ro, z = O.forward_vit_stem(arch, params, imgs[2])
+    if int(r3[0, 2]) == ro:
+        assert relerr(l3[2].cpu().numpy(), want) < TOL
+    else:
+        assert O.gate_margin(z) < 2e-2 * np.max(np.abs(z))
+
+
+def test_vit_stem_batch256(gpu_lib):
+    # the paper's stem at its real shape: 224x224 -> 112x112x24 -> 14x14 patches of 8x8, 197 tokens
+    arch = WL.vit_arch(stem_dim=24, patch=8, depth=2)
+    assert arch["tokens"] == 197 and arch["T"] == 48
+    params = WL.vit_params(arch, S + 75)
+    B = 256
+    imgs = WL.images(S + 175, B)
+    lb = WL.seeded_logit_bias(S + 275, B, arch["T"], amp=16.0)
+    target = np.argmax(lb, axis=1)
+    check = [int(np.where(target == t)[0][0]) for t in (0, 47)] + [200]
+    net, xg, lbg, logits, routes = _vit_stem_case(gpu_lib, arch, params, imgs, lb, check)
+    pi = torch.randperm(B, generator=torch.Generator().manual_seed(4)).to(DEV)
+    l3, r3 = gpu_lib.ds_forward(net, xg[pi].contiguous(), logit_bias=lbg[:, pi].contiguous())
+    assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
+
+
 def test_vit_config5_batch256(gpu_lib):
     arch = WL.vit_arch()
     params = WL.vit_params(arch, S + 5)
