@@ -13,6 +13,50 @@
 
 namespace {
 
+typedef short i16x2_t __attribute__((ext_vector_type(2)));
+
+// Input patch of one tile: 3 x PR rows of PC pixels, fetched as 8-byte pieces.  Which piece a thread
+// owns does not depend on the tile, so the decomposition is done once; per tile the pieces are requested
+// with branch-free buffer loads (a piece outside the image gets an out-of-range offset and reads as
+// zeros) and are held in registers while the previous tile is still being worked on.
+template <int PR, int PC, int NTH, int XOFF>
+struct PatchLoader {
+    static constexpr int NCH = 3 * PR * (PC / 4), NL = (NCH + NTH - 1) / NTH;
+    static constexpr uint32_t OOB = 0x80000000u;
+    int r[NL], x[NL], plane[NL], lds[NL];
+    uint2 v[NL];
+    __device__ void init(int tid, int H, int W) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int c = tid + i * NTH;
+            const int row = c / (PC / 4), ch = c - row * (PC / 4);
+            const int cc = row / PR;
+            r[i] = row - cc * PR;
+            x[i] = ch * 4 - XOFF;
+            plane[i] = cc * H * W;
+            lds[i] = c < NCH ? row * PC + ch * 4 : -1;
+        }
+    }
+    // iy0, ix0: image row / column of patch row 0 / the patch's column XOFF
+    __device__ void issue(const bf16_t* img, int sample, int iy0, int ix0, int H, int W) {
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(img + (int64_t)sample * 3 * H * W), 0, 0x7fffffff, 0x00020000);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int iy = iy0 + r[i], col0 = ix0 + x[i];
+            const bool ok = lds[i] >= 0 && iy >= 0 && iy < H && col0 >= 0 && col0 + 3 < W;
+            const uint32_t off = ok ? (uint32_t)((plane[i] + iy * W + col0) * 2) : OOB;
+            const auto t = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)off, 0, 0);
+            v[i] = make_uint2(t[0], t[1]);
+        }
+    }
+    __device__ void store(bf16_t* patch) const {
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            if (lds[i] >= 0) *(uint2*)(patch + lds[i]) = v[i];
+    }
+};
+
 template <int KS, int PAD, int VP, int NTILES>
 __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict__ img, const int32_t* index,
                                                         bf16_t* __restrict__ y, const bf16_t* __restrict__ w,
@@ -42,22 +86,23 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
         sc[t] = t * 32 + l32 < cout ? scale[t * 32 + l32] : 0.f;
         sh[t] = t * 32 + l32 < cout ? shift[t * 32 + l32] : 0.f;
     }
+    PatchLoader<PR, PC, 256, 4> pl;
+    pl.init(tid, H, W);
+    auto fetch = [&](int tile) {
+        const int slot = tile / (tiles_x * tiles_y);
+        const int t2 = tile - slot * tiles_x * tiles_y;
+        const int ty = t2 / tiles_x, tx = t2 - ty * tiles_x;
+        const int sample = __builtin_amdgcn_readfirstlane(index ? index[slot] : slot);
+        pl.issue(img, sample, ty * TH * 2 - PAD, tx * TW * 2, H, W);
+    };
     for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
         const int slot = tile / (tiles_x * tiles_y);
         const int t2 = tile - slot * tiles_x * tiles_y;
         const int ty = t2 / tiles_x, tx = t2 - ty * tiles_x;
         const int oy0 = ty * TH, ox0 = tx * TW;
-        const int sample = index ? index[slot] : slot;
+        fetch(tile);      // all pieces in flight together
         __syncthreads();  // filter bank ready / previous patch no longer read
-        for (int c = tid; c < 3 * PR * (PC / 4); c += 256) {
-            const int row = c / (PC / 4), ch = c - row * (PC / 4);
-            const int cc = row / PR, r = row - cc * PR;
-            const int iy = oy0 * 2 - PAD + r, col0 = ox0 * 2 - 4 + ch * 4;
-            uint2 v = make_uint2(0, 0);
-            if (iy >= 0 && iy < H && col0 >= 0 && col0 + 3 < W)
-                v = *(const uint2*)(img + (((int64_t)sample * 3 + cc) * H + iy) * W + col0);
-            *(uint2*)(patch + row * PC + ch * 4) = v;
-        }
+        pl.store(patch);
         __syncthreads();
         f32x16_t acc[NTILES];
 #pragma unroll
@@ -112,12 +157,17 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
                                                         int total_tiles) {
     constexpr int KS = 7, PAD = 3, VP = 8, NTH = 320;
     constexpr int COUT = NTILES * 32, PAIRS = 3 * KS, KP = ((PAIRS * VP + 15) / 16) * 16, KSTEPS = KP / 16;
-    constexpr int W_LD = KP + 8, CH = 9, CW = 17, NPIX = CH * CW, PR = 2 * CH + KS - 2, PC = 44, CBASE = 2;
+    constexpr int W_LD = KP + 8, CH = 9, CW = 17, NPIX = CH * CW, PR = 2 * CH + KS - 2, PC = 48, CBASE = 2;
     constexpr int C_LD = COUT + 8;                     // conv tile row stride in LDS (bf16)
     __shared__ __attribute__((aligned(16))) bf16_t Wl[COUT * W_LD];
     __shared__ __attribute__((aligned(16))) bf16_t patch[3 * PR * PC];
     __shared__ __attribute__((aligned(16))) bf16_t ctile[NPIX * C_LD];
+    __shared__ __attribute__((aligned(16))) float scl[COUT], shl[COUT];
     const int tid = threadIdx.x;
+    if (tid < COUT) {
+        scl[tid] = scale[tid];
+        shl[tid] = shift[tid];
+    }
     for (int i = tid; i < COUT * KP; i += NTH) {
         const int n = i / KP, k = i - n * KP;
         const int pair = k / VP, e = k - pair * VP;
@@ -129,12 +179,6 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int pi = wave * 32 + l32;                    // this lane's convolution pixel as the A-operand row
     const int pcy = pi < NPIX ? pi / CW : 0, pcx = pi < NPIX ? pi - (pi / CW) * CW : 0;
-    float sc[NTILES], sh[NTILES];
-#pragma unroll
-    for (int t = 0; t < NTILES; ++t) {
-        sc[t] = scale[t * 32 + l32];
-        sh[t] = shift[t * 32 + l32];
-    }
     // patch offset of this lane's 8 reduction values at every k-step (-1: padding beyond the last pair)
     int koff[KSTEPS];
 #pragma unroll
@@ -143,25 +187,27 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
         const int c = pair / KS, u = pair - c * KS;
         koff[ks] = pair < PAIRS ? (c * PR + 2 * pcy + u) * PC + 2 * pcx + CBASE : -1;
     }
+    // input rows 2 oy0 - 3 .., columns 2 ox0 - 6 .. (a multiple of 4, so the 8-byte loads are aligned)
+    PatchLoader<PR, PC, NTH, 6> pl;
+    pl.init(tid, H, W);
+    auto fetch = [&](int tile) {
+        const int slot = tile / (tiles_x * tiles_y);
+        const int t2 = tile - slot * tiles_x * tiles_y;
+        const int ty = t2 / tiles_x, tx = t2 - ty * tiles_x;
+        const int sample = __builtin_amdgcn_readfirstlane(index ? index[slot] : slot);
+        pl.issue(img, sample, (8 * ty - 1) * 2 - PAD, (16 * tx - 1) * 2, H, W);
+    };
+    if ((int)blockIdx.x < total_tiles) fetch(blockIdx.x);
     for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
         const int slot = tile / (tiles_x * tiles_y);
         const int t2 = tile - slot * tiles_x * tiles_y;
         const int ty = t2 / tiles_x, tx = t2 - ty * tiles_x;
         const int p0 = ty * 4, q0 = tx * 8;            // pooled tile origin
         const int oy0 = 2 * p0 - 1, ox0 = 2 * q0 - 1;  // first convolution pixel
-        const int sample = index ? index[slot] : slot;
         __syncthreads();  // filter bank ready / previous patch and conv tile no longer read
-        // input rows 2 oy0 - 3 .., columns 2 ox0 - 6 .. (a multiple of 4, so the 8-byte loads are aligned)
-        for (int c = tid; c < 3 * PR * (PC / 4); c += NTH) {
-            const int row = c / (PC / 4), ch = c - row * (PC / 4);
-            const int cc = row / PR, r = row - cc * PR;
-            const int iy = oy0 * 2 - PAD + r, col0 = ox0 * 2 - 6 + ch * 4;
-            uint2 v = make_uint2(0, 0);
-            if (iy >= 0 && iy < H && col0 >= 0 && col0 + 3 < W)
-                v = *(const uint2*)(img + (((int64_t)sample * 3 + cc) * H + iy) * W + col0);
-            *(uint2*)(patch + row * PC + ch * 4) = v;
-        }
+        pl.store(patch);
         __syncthreads();
+        if (tile + (int)gridDim.x < total_tiles) fetch(tile + gridDim.x);   // in flight during this tile's arithmetic
         f32x16_t acc[NTILES];
 #pragma unroll
         for (int t = 0; t < NTILES; ++t)
@@ -177,21 +223,27 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
 #pragma unroll
             for (int t = 0; t < NTILES; ++t) {
                 const bf16x8_t bfr = *(const bf16x8_t*)(Wl + (t * 32 + l32) * W_LD + kbase);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bfr, acc[t], 0, 0, 0);
+                // filters as the row operand: the accumulator then holds this lane's own pixel (column l32)
+                // and channels 32 t + 8 g + 4 lhi + 0..3 in elements 4 g .. 4 g + 3, i.e. runs of four
+                // consecutive channels that go to LDS as one 8-byte write
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af.v, acc[t], 0, 0, 0);
             }
         }
-        // batch-norm, ReLU, bf16 rounding; the accumulator holds pixel i of the wavefront, channel l32 (+32 t)
+        // batch-norm, ReLU, bf16 rounding
+        if (pi < NPIX) {
+            const int oy = oy0 + pcy, ox = ox0 + pcx;
+            const bool in = oy >= 0 && oy < Ho && ox >= 0 && ox < Wo;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int i = wave * 32 + 8 * (e >> 2) + 4 * lhi + (e & 3);
-            if (i < NPIX) {
-                const int cy = i / CW, cx = i - cy * CW;
-                const int oy = oy0 + cy, ox = ox0 + cx;
-                const bool in = oy >= 0 && oy < Ho && ox >= 0 && ox < Wo;
+            for (int t = 0; t < NTILES; ++t)
 #pragma unroll
-                for (int t = 0; t < NTILES; ++t)
-                    ctile[i * C_LD + t * 32 + l32] = in ? f2bf(fmaxf(acc[t][e] * sc[t] + sh[t], 0.f)) : (bf16_t)0;
-            }
+                for (int g = 0; g < 4; ++g) {
+                    const int ch = t * 32 + g * 8 + lhi * 4;
+                    const float4 s4 = *(const float4*)(scl + ch), h4 = *(const float4*)(shl + ch);
+                    uint2 o;
+                    o.x = f2bf2(fmaxf(acc[t][4 * g] * s4.x + h4.x, 0.f), fmaxf(acc[t][4 * g + 1] * s4.y + h4.y, 0.f));
+                    o.y = f2bf2(fmaxf(acc[t][4 * g + 2] * s4.z + h4.z, 0.f), fmaxf(acc[t][4 * g + 3] * s4.w + h4.w, 0.f));
+                    *(uint2*)(ctile + pi * C_LD + ch) = in ? o : make_uint2(0u, 0u);
+                }
         }
         __syncthreads();
         // pooled pixel (pr, pc) of the tile, 8 channels per thread
@@ -200,9 +252,11 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
             const int ch = (it % CHUNKS) * 8, pp = it / CHUNKS;
             const int pr = pp >> 3, pc = pp & 7;
             if (p0 + pr >= Hp || q0 + pc >= Wp) continue;
-            float m[8];
+            // every value is >= 0 after the ReLU, and non-negative bf16 values order like their bit patterns:
+            // the maximum is a packed signed 16-bit integer maximum (a -0 loses to everything), no unpacking
+            i16x2_t m[4];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) m[k] = 0.f;
+            for (int k = 0; k < 4; ++k) m[k] = i16x2_t{0, 0};
 #pragma unroll
             for (int u = 0; u < 3; ++u)
 #pragma unroll
@@ -210,16 +264,13 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
                     const uint4 q = *(const uint4*)(ctile + ((2 * pr + u) * CW + 2 * pc + v) * C_LD + ch);
                     const uint32_t qq[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        m[2 * k] = fmaxf(m[2 * k], __uint_as_float(qq[k] << 16));
-                        m[2 * k + 1] = fmaxf(m[2 * k + 1], __uint_as_float(qq[k] & 0xffff0000u));
-                    }
+                    for (int k = 0; k < 4; ++k) m[k] = __builtin_elementwise_max(m[k], __builtin_bit_cast(i16x2_t, qq[k]));
                 }
             uint4 o;
-            o.x = f2bf2(m[0], m[1]);
-            o.y = f2bf2(m[2], m[3]);
-            o.z = f2bf2(m[4], m[5]);
-            o.w = f2bf2(m[6], m[7]);
+            o.x = __builtin_bit_cast(uint32_t, m[0]);
+            o.y = __builtin_bit_cast(uint32_t, m[1]);
+            o.z = __builtin_bit_cast(uint32_t, m[2]);
+            o.w = __builtin_bit_cast(uint32_t, m[3]);
             *(uint4*)(y + (((int64_t)slot * Hp + p0 + pr) * Wp + q0 + pc) * COUT + ch) = o;
         }
     }
