@@ -96,6 +96,7 @@ static inline const int4* ds_mtile_entries(const void* list) { return (const int
 static inline const int32_t* ds_mtile_count(const void* list) { return (const int32_t*)list; }
 
 // ---- routing agent ------------------------------------------------------------
+constexpr int POOL_SPLIT_MAX = 8;   // most partial sums per (item, channel) the spatial pool leaves for its consumer
 struct GateArgs {
     const void* x;            // feature maps; nullptr = route on logit_bias alone
     int32_t dtype, layout;

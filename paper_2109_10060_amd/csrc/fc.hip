@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void fc_tile_kernel(const FcArgs a) {
 // Needs C and w_ld to be multiples of 8.
 constexpr int PF = 4;
 
-template <typename WT, typename ACC, int TOV>
+template <typename WT, typename ACC, int TOV, bool MULTI>
 __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
     constexpr int IPT = TI * TOV / 256;                 // items per thread
     static_assert(IPT >= 1 && TI * TOV % 256 == 0, "tile shape");
@@ -136,10 +136,26 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
                 vreg[0] = __uint_as_float(q.x << 16); vreg[1] = __uint_as_float(q.x & 0xffff0000u);
                 vreg[2] = __uint_as_float(q.y << 16); vreg[3] = __uint_as_float(q.y & 0xffff0000u);
             } else {
+                // every partial sum is requested before the first is added: a loop of load-then-add is a
+                // chain of memory round trips (the slots past a.splits re-read the last one and are dropped)
                 double sd[4] = {0, 0, 0, 0};
-                for (int sp = 0; sp < a.splits; ++sp) {
-                    const float4 t = *(const float4*)(a.v_partial + ((int64_t)vitem * a.splits + sp) * a.C + c);
-                    sd[0] += t.x; sd[1] += t.y; sd[2] += t.z; sd[3] += t.w;
+                if (!MULTI) {   // a.splits == 1
+                    for (int sp = 0; sp < a.splits; ++sp) {
+                        const float4 t = *(const float4*)(a.v_partial + ((int64_t)vitem * a.splits + sp) * a.C + c);
+                        sd[0] += t.x; sd[1] += t.y; sd[2] += t.z; sd[3] += t.w;
+                    }
+                } else {
+                    float4 t[POOL_SPLIT_MAX];
+#pragma unroll
+                    for (int sp = 0; sp < POOL_SPLIT_MAX; ++sp) {
+                        const int q = sp < a.splits ? sp : a.splits - 1;
+                        t[sp] = *(const float4*)(a.v_partial + ((int64_t)vitem * a.splits + q) * a.C + c);
+                    }
+#pragma unroll
+                    for (int sp = 0; sp < POOL_SPLIT_MAX; ++sp)
+                        if (sp < a.splits) {
+                            sd[0] += t[sp].x; sd[1] += t[sp].y; sd[2] += t[sp].z; sd[3] += t[sp].w;
+                        }
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) vreg[j] = (float)(sd[j] * (double)a.v_scale);
@@ -214,17 +230,22 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
 
 int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t kind, hipStream_t s) {
     if (a.items <= 0 || a.n_out <= 0) return DS_OK;
+    if (!a.v_rows && (a.splits < 1 || a.splits > POOL_SPLIT_MAX))
+        DS_FAIL(DS_EINVAL, "fc: %d partial sums per channel (1..%d)", a.splits, POOL_SPLIT_MAX);
     const unsigned gy = (unsigned)((a.items + TI - 1) / TI);
     ProfScope prof(kind, s);
     const bool vec = (a.C % 8) == 0 && (a.w_ld % 8) == 0 && (a.v_rows == nullptr || (a.v_row_stride % 4) == 0);
     if (vec) {
         // narrow output tiles when 64-wide ones would leave most compute units without a workgroup
         const bool narrow = (long long)((a.n_out + 63) / 64) * gy < 256;
+        const bool multi = !a.v_rows && a.splits > 1;   // several partial sums per channel to combine
         const dim3 grid((unsigned)((a.n_out + (narrow ? 15 : 63)) / (narrow ? 16 : 64)), gy);
 #define DS_FC_LAUNCH(WT, ACC)                                                                               \
     do {                                                                                                    \
-        if (narrow) hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 16>), grid, dim3(256), 0, s, a);         \
-        else hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 64>), grid, dim3(256), 0, s, a);                \
+        if (narrow && multi) hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 16, true>), grid, dim3(256), 0, s, a);   \
+        else if (narrow) hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 16, false>), grid, dim3(256), 0, s, a);      \
+        else if (multi) hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 64, true>), grid, dim3(256), 0, s, a);        \
+        else hipLaunchKernelGGL((fc_tile_vec_kernel<WT, ACC, 64, false>), grid, dim3(256), 0, s, a);                  \
     } while (0)
         if (w_bf16) DS_FC_LAUNCH(bf16_t, float);
         else if (acc_f64) DS_FC_LAUNCH(float, double);

@@ -9,7 +9,6 @@
 
 namespace {
 
-constexpr int POOL_SPLIT_MAX = 8;
 
 // ---- encoder: partial spatial sums -------------------------------------------
 // NHWC: grid (items, splits); block 256 = 32 channel chunks of 8 x 8 row lanes.
