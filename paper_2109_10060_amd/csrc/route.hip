@@ -101,40 +101,48 @@ __global__ __launch_bounds__(256) void pool_nchw_kernel(const GateArgs a) {
 }
 
 // ---- routing head, output layer + argmax: one wavefront per item ---------------------------
-// hidden [items][C_mlp] comes from the tiled first layer (fp64 accumulation, ReLU applied)
-__global__ __launch_bounds__(64) void gate_out_kernel(const GateArgs a, const float* hidden) {
+// hidden [items][C_mlp] comes from the tiled first layer (fp64 accumulation, ReLU applied).
+// The wavefront is split into groups of G = 64 >> lg lanes, one group per output, so that all T
+// outputs (up to 64 per pass) are computed side by side: a group strides over the hidden units and
+// adds its partial sums with a butterfly.  The argmax (NaN never wins, ties go to the lowest index)
+// is a butterfly over (value, index) pairs.
+__global__ __launch_bounds__(64) void gate_out_kernel(const GateArgs a, const float* hidden, int lg) {
     const int item = blockIdx.x;
     const int out = a.out_index ? a.out_index[item] : item;
     const int lane = threadIdx.x;
     const bool have_x = a.x != nullptr;
-    for (int t = 0; t < a.T; ++t) {
+    const int G = 64 >> lg, per_pass = 1 << lg;
+    const int sub = lane & (G - 1), tl = lane >> (6 - lg);
+    float best = 0.f;
+    int arg = 0;
+    bool have = false;
+    for (int t0 = 0; t0 < a.T; t0 += per_pass) {
+        const int t = t0 + tl;
         double s = 0.0;
         if (have_x) {
-            const float* wr = a.w2 + (int64_t)t * a.C_mlp;
-            const float* h = hidden + (int64_t)item * a.C_mlp;
-            for (int j = lane; j < a.C_mlp; j += 64) s += (double)wr[j] * (double)h[j];
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-            s += a.b2 ? (double)a.b2[t] : 0.0;
+            if (t < a.T) {
+                const float* wr = a.w2 + (int64_t)t * a.C_mlp;
+                const float* h = hidden + (int64_t)item * a.C_mlp;
+                for (int j = sub; j < a.C_mlp; j += G) s += (double)wr[j] * (double)h[j];
+            }
+            for (int o = G >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+            if (t < a.T && a.b2) s += (double)a.b2[t];
         }
-        if (lane == 0) {
+        if (t < a.T && sub == 0) {
             if (a.logit_bias) s += (double)a.logit_bias[(int64_t)out * a.T + t];
-            a.logits[(int64_t)out * a.T + t] = (float)s;
+            const float v = (float)s;
+            a.logits[(int64_t)out * a.T + t] = v;
+            if (v == v && (!have || v > best)) { best = v; arg = t; have = true; }   // t ascends within a lane
         }
     }
-    __syncthreads();
-    if (lane == 0) {
-        int arg = 0;
-        bool have = false;
-        float best = 0.f;
-        for (int t = 0; t < a.T; ++t) {
-            const float v = a.logits[(int64_t)out * a.T + t];
-            if (v != v) continue;
-            if (!have || v > best) { best = v; arg = t; have = true; }
-        }
-        if (a.route_override) arg = a.route_override[out];
-        a.route[out] = arg;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(best, o, 64);
+        const int oa = __shfl_xor(arg, o, 64);
+        const bool oh = __shfl_xor((int)have, o, 64) != 0;
+        if (oh && (!have || ob > best || (ob == best && oa < arg))) { best = ob; arg = oa; have = true; }
     }
+    if (lane == 0) a.route[out] = a.route_override ? a.route_override[out] : arg;
 }
 
 // ---- bucketing ----------------------------------------------------------------
@@ -239,7 +247,9 @@ int32_t ds_launch_gate(const GateArgs& a, hipStream_t s) {
         if (rc) return rc;
     }
     ProfScope prof(DS_K_GATE, s);
-    hipLaunchKernelGGL(gate_out_kernel, dim3(a.B), dim3(64), 0, s, a, hidden);
+    int lg = 0;
+    while ((1 << lg) < a.T && lg < 6) ++lg;   // 2^lg outputs side by side, 64 >> lg lanes each
+    hipLaunchKernelGGL(gate_out_kernel, dim3(a.B), dim3(64), 0, s, a, hidden, lg);
     DS_CHECK_LAUNCH("gate head");
     return DS_OK;
 }
@@ -342,7 +352,9 @@ extern "C" int32_t ds_gate_double(const void* x, int32_t x_dtype, int32_t x_layo
     if (rc) return rc;
     if (routing) {
         ProfScope prof(DS_K_GATE, s);
-        hipLaunchKernelGGL(gate_out_kernel, dim3(B), dim3(64), 0, s, a, (const float*)hidden);
+        int lg = 0;
+        while ((1 << lg) < T && lg < 6) ++lg;
+        hipLaunchKernelGGL(gate_out_kernel, dim3(B), dim3(64), 0, s, a, (const float*)hidden, lg);
         DS_CHECK_LAUNCH("gate head");
     }
     // attention head: factor[b][c] = 1 + tanh(W3[c, :] . hidden[b] + b3[c]); rows beyond the
