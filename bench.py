@@ -48,9 +48,15 @@ def build_workload(name: str, B: int):
         params = WL.vit_params(arch, S + 6)
         lb = WL.seeded_logit_bias(S + 206, B, arch["T"], amp=16.0)[None]
         label = "DS-ViT++ stem (conv + 2 depthwise-separable blocks at 24 channels, gate on its map) + config5's network, bf16"
+    elif name == "vit_pp":
+        arch = WL.vit_arch(embed=416, heads=8, head_dim=48, mlp=1664, depth=14, routes="pp", stem_dim=24, patch=8)
+        params = WL.vit_params(arch, S + 7)
+        lb = WL.seeded_logit_bias(S + 207, B, arch["T"], amp=16.0)[None]
+        label = ("DS-ViT++ supernet (stem, embed 192..416, 4..8 heads of 48, MLP ratio 3..4, depth 12..14; "
+                 "8 nested routes), bf16")
     else:
         raise SystemExit(f"unknown workload {name}")
-    imgs = WL.images(S + 100 + {"mbnet": 3, "resnet": 4, "vit": 5, "vit_stem": 6}[name], B)
+    imgs = WL.images(S + 100 + {"mbnet": 3, "resnet": 4, "vit": 5, "vit_stem": 6, "vit_pp": 7}[name], B)
     return arch, params, imgs, lb.astype("float32"), label
 
 
@@ -69,7 +75,7 @@ def cpu_baseline(name, arch, params, imgs, lb, budget_s=15.0):
             O.forward_mbnet(arch, params, imgs[n], logit_bias=lb[0, n])
         elif name == "resnet":
             O.forward_resnet(arch, params, imgs[n], logit_bias=lb[:, n])
-        elif name == "vit_stem":
+        elif name in ("vit_stem", "vit_pp"):
             O.forward_vit_stem(arch, params, imgs[n], logit_bias=lb[0, n])
         else:
             O.forward_vit(arch, params, imgs[n], O.gate_route(lb[0, n]))
@@ -84,7 +90,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem"])
+    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp"])
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -117,7 +123,7 @@ def main():
     B = args.batch
     arch, params, imgs, lb, label = build_workload(args.workload, B)
     net = {"mbnet": ds.build_mbnet, "resnet": ds.build_resnet, "vit": ds.build_vit,
-           "vit_stem": ds.build_vit}[args.workload](arch, params, dev)
+           "vit_stem": ds.build_vit, "vit_pp": ds.build_vit}[args.workload](arch, params, dev)
     x = torch.from_numpy(imgs).to(dev).to(torch.bfloat16).contiguous()
     lbg = torch.from_numpy(lb).to(dev).contiguous()
     logits = torch.empty((B, net.num_classes), dtype=torch.float32, device=dev)
@@ -156,7 +162,8 @@ def main():
     prof = ds.ds_profile_read() if sampled else {}
 
     rt = routes.cpu().numpy()
-    cost = {"mbnet": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost}[args.workload](arch, rt)
+    cost = {"mbnet": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost,
+            "vit_pp": C.vit_cost}[args.workload](arch, rt)
     roofline = None
     kernels = {}
     if prof:

@@ -164,8 +164,9 @@ int32_t ds_sliced_layernorm(const void* x, int64_t x_ld, const float* gamma, con
  * (+ residual).  Group t uses d_e = k_in[t] and h*Dh = k_out[t].  x, residual, y:
  * device bf16 [B, N, D_e]; wqkv: device bf16 [3, H*Dh, D_e] (Wq, Wk, Wv stacked, each
  * sliced to its own leading block); bqkv: device fp32 [3, H*Dh] or NULL; wproj:
- * device bf16 [D_e, H*Dh]; bproj: device fp32 [D_e] or NULL.  head_dim must be 64,
- * N <= 224. */
+ * device bf16 [D_e, H*Dh]; bproj: device fp32 [D_e] or NULL.  head_dim must be 32, 48
+ * or 64 (DS-ViT++'s Q-K-V widths 192..384 in steps of 48 with 4..8 heads are 8 stored heads
+ * of 48), N <= 224. */
 size_t ds_sliced_mhsa_workspace(int32_t B, int32_t N, int32_t H, int32_t head_dim, int32_t T);
 int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D_e, const void* wqkv,
                        const float* bqkv, const void* wproj, const float* bproj, int32_t H,

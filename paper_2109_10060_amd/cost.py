@@ -109,7 +109,14 @@ def vit_cost(arch, routes) -> Cost:
         kp = 3 * arch["patch"] ** 2
         c.add("index", 0.0, 2.0 * 2 * B * (N - 1) * kp)                             # patch extraction
         _gemm(c, "gemm", N - 1, N - 1, 1, np.full(B, kp), de)
-    for _ in range(arch["depth"]):
+    full = tab[:, :3].copy()
+    for l in range(arch["depth"]):
+        # dynamic depth: a route that runs fewer than l + 1 blocks contributes nothing to this layer
+        on = (tab[:, 3] > l).astype(np.float64) if tab.shape[1] > 3 else np.ones(B)
+        if not on.any():
+            break
+        de, h, hid = full[:, 0] * on, full[:, 1] * on, full[:, 2] * on
+        hd = h * arch["head_dim"]
         c.add("layernorm", 8.0 * N * de.sum(), 4.0 * N * de.sum())
         k_in, k_out = de, 3 * hd
         _gemm(c, "gemm", N, N, 1, k_in, k_out)
@@ -118,6 +125,7 @@ def vit_cost(arch, routes) -> Cost:
         c.add("layernorm", 8.0 * N * de.sum(), 4.0 * N * de.sum())
         _gemm(c, "gemm", N, N, 1, de, hid)
         _gemm(c, "gemm", N, N, 1, hid, de, residual=True)
+    de = full[:, 0]
     c.add("layernorm", 8.0 * de.sum(), 4.0 * de.sum())
     c.add("head", 2.0 * arch["num_classes"] * de.sum(), 2.0 * de.sum() + 2.0 * arch["num_classes"] * de.max())
     return c

@@ -216,7 +216,7 @@ extern "C" int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D
                                   size_t ws_bytes, void* stream) {
     const char* who = "ds_sliced_mhsa";
     if (B < 0 || N < 1 || D_e < 1 || H < 1) DS_FAIL(DS_EINVAL, "%s: bad size", who);
-    if (head_dim != 64) DS_FAIL(DS_EUNSUPPORTED, "%s: head_dim must be 64", who);
+    if (head_dim != 32 && head_dim != 48 && head_dim != 64) DS_FAIL(DS_EUNSUPPORTED, "%s: head_dim must be 32, 48 or 64", who);
     if (N > 224) DS_FAIL(DS_EUNSUPPORTED, "%s: N above 224", who);
     const int Hd = H * head_dim;
     GroupTable gt;
@@ -263,7 +263,7 @@ extern "C" int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D
 
     const int64_t seg = (int64_t)(bufsz / sizeof(bf16_t));
     rc = ds_launch_attention(qkv, qkv + seg, qkv + 2 * seg, obuf, (int64_t)N * Hd, Hd, Hd, (int64_t)N * Hd, slot_group,
-                             gt, B, N, H, s);
+                             gt, B, N, H, head_dim, s);
     if (rc) return rc;
 
     GemmArgs b;

@@ -1,5 +1,6 @@
 // Head-sliced self-attention (Section 3.4, Eq. 17): one workgroup per (slot, head),
-// heads at or beyond the slot's head count exit at once.  Head dimension 64,
+// heads at or beyond the slot's head count exit at once.  Head dimension 32, 48 or 64
+// (DS-ViT++ stores 8 heads of 48: its Q-K-V widths 192..384 in steps of 48 go with 4..8 heads),
 // sequence length up to 224 (7 key tiles of 32).
 //
 // K and V^T of the head live in LDS.  One wavefront per 32-query tile (up to 7 per workgroup):
@@ -14,15 +15,20 @@
 
 namespace {
 
-constexpr int DH = 64, NKT = 7, KEYS = NKT * 32, K_LD = DH + 8, V_LD = KEYS + 8;
+constexpr int NKT = 7, KEYS = NKT * 32, V_LD = KEYS + 8;
 
+// DH: head dimension, a multiple of 16.  The output tiles are 32 channels tall, so V^T is padded with
+// zero rows to DT * 32 channels and the channels past DH are computed and dropped.
+template <int DH>
 __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                         int64_t sample_stride, int ld, int o_ld,
                                                         int64_t o_sample_stride, const int32_t* slot_group,
                                                         const GroupTable gt, int N, float scale) {
+    constexpr int K_LD = DH + 8, KK = DH / 16, DT = (DH + 31) / 32, CPR = DH / 8;
+    static_assert(DH % 16 == 0 && DH <= 64, "head dimension");
     __shared__ __attribute__((aligned(16))) bf16_t Ks[KEYS * K_LD];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[DH * V_LD];
+    __shared__ __attribute__((aligned(16))) bf16_t Vt[DT * 32 * V_LD];
     const int slot = blockIdx.x, head = blockIdx.y;
     const int g = slot_group ? slot_group[slot] : 0;
     if (head * DH >= gt.k_out[g]) return;
@@ -32,17 +38,19 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
     // this lane's query row, fetched first so that its latency overlaps the staging of K and V
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int qrow = wave * 32 + l32;
-    bf16x8_t qf[4];
+    bf16x8_t qf[KK];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < KK; ++kk) {
         uint4 t = make_uint4(0, 0, 0, 0);
         if (qrow < N) t = *(const uint4*)(q + base + (int64_t)qrow * ld + kk * 16 + lhi * 8);
         qf[kk] = *(bf16x8_t*)&t;
     }
 
     const int nthreads = blockDim.x;          // one wavefront per 32-query tile
-    for (int c = tid; c < KEYS * 8; c += nthreads) {
-        const int row = c >> 3, ch = (c & 7) * 8;
+    if constexpr (DH % 32 != 0)
+        for (int c = tid; c < (DT * 32 - DH) * V_LD / 2; c += nthreads) ((uint32_t*)(Vt + DH * V_LD))[c] = 0u;
+    for (int c = tid; c < KEYS * CPR; c += nthreads) {
+        const int row = c / CPR, ch = (c - row * CPR) * 8;
         uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
         if (row < N) {
             kv = *(const uint4*)(k + base + (int64_t)row * ld + ch);
@@ -65,7 +73,7 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
 #pragma unroll
             for (int e = 0; e < 16; ++e) sacc[kt][e] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
+            for (int kk = 0; kk < KK; ++kk) {
                 const bf16x8_t kf = *(const bf16x8_t*)(Ks + (kt * 32 + l32) * K_LD + kk * 16 + lhi * 8);
                 sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[kt], 0, 0, 0);
             }
@@ -99,9 +107,9 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
         sum += __shfl_xor(sum, 32, 64);
         const float inv = 1.0f / sum;
 
-        f32x16_t oacc[2];
+        f32x16_t oacc[DT];
 #pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) oacc[dt][e] = 0.f;
 #pragma unroll
@@ -113,7 +121,7 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
                 for (int e = 0; e < 4; ++e)
                     pf.u[e] = f2bf2(sacc[kt][8 * half + 2 * e] * inv, sacc[kt][8 * half + 2 * e + 1] * inv);
 #pragma unroll
-                for (int dt = 0; dt < 2; ++dt) {
+                for (int dt = 0; dt < DT; ++dt) {
                     const bf16_t* vp = Vt + (dt * 32 + l32) * V_LD + kt * 32 + 16 * half + 4 * lhi;
                     union { uint2 h[2]; bf16x8_t v; } vf;
                     vf.h[0] = *(const uint2*)vp;
@@ -126,9 +134,10 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
         if (qrow < N) {
             bf16_t* op = o + (int64_t)slot * o_sample_stride + (int64_t)qrow * o_ld + head * DH + 4 * lhi;
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
+                    if (dt * 32 + 8 * g4 >= DH) continue;   // padding channels of the last tile
                     uint2 w;
                     w.x = f2bf2(oacc[dt][4 * g4], oacc[dt][4 * g4 + 1]);
                     w.y = f2bf2(oacc[dt][4 * g4 + 2], oacc[dt][4 * g4 + 3]);
@@ -142,12 +151,21 @@ __global__ __launch_bounds__(448) void attention_kernel(const bf16_t* __restrict
 
 int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* o, int64_t sample_stride,
                             int32_t ld, int32_t o_ld, int64_t o_sample_stride, const int32_t* slot_group,
-                            const GroupTable& gt, int32_t B, int32_t N, int32_t H, hipStream_t s) {
+                            const GroupTable& gt, int32_t B, int32_t N, int32_t H, int32_t head_dim, hipStream_t s) {
     if (B <= 0 || H <= 0) return DS_OK;
     if (N < 1 || N > KEYS) DS_FAIL(DS_EUNSUPPORTED, "attention: sequence length %d outside 1..%d", N, KEYS);
+    if (head_dim != 32 && head_dim != 48 && head_dim != 64)
+        DS_FAIL(DS_EUNSUPPORTED, "attention: head dimension %d (32, 48 or 64)", head_dim);
     ProfScope prof(DS_K_ATTENTION, s);
-    hipLaunchKernelGGL(attention_kernel, dim3((unsigned)B, (unsigned)H), dim3(64 * ((N + 31) / 32)), 0, s, q, k, v, o, sample_stride,
-                       ld, o_ld, o_sample_stride, slot_group, gt, N, 0.125f);
+    const dim3 grid((unsigned)B, (unsigned)H), block(64 * ((N + 31) / 32));
+    const float scale = 1.0f / sqrtf((float)head_dim);
+#define DS_ATT(D)                                                                                                  \
+    hipLaunchKernelGGL(attention_kernel<D>, grid, block, 0, s, q, k, v, o, sample_stride, ld, o_ld, o_sample_stride, \
+                       slot_group, gt, N, scale)
+    if (head_dim == 64) DS_ATT(64);
+    else if (head_dim == 48) DS_ATT(48);
+    else DS_ATT(32);
+#undef DS_ATT
     DS_CHECK_LAUNCH("attention");
     return DS_OK;
 }

@@ -177,10 +177,11 @@ int32_t ds_launch_compose_index(const int32_t* inner, const int32_t* outer, int3
 int32_t ds_launch_lookup(const int32_t* idx, const GroupTable& gt, int32_t which, int32_t* out, int32_t B, hipStream_t s);
 
 // ---- attention ----------------------------------------------------------------
-// q, k, v, o: bf16 [slot][N][ld]; head j uses columns j*64..j*64+63; group g runs heads < k_out[g]/64
+// q, k, v, o: bf16 [slot][N][ld]; head j uses columns j*Dh..j*Dh+Dh-1; group g runs heads < k_out[g]/Dh;
+// head_dim Dh: 32, 48 or 64
 int32_t ds_launch_attention(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* o, int64_t sample_stride,
                             int32_t ld, int32_t o_ld, int64_t o_sample_stride, const int32_t* slot_group,
-                            const GroupTable& gt, int32_t B, int32_t N, int32_t H, hipStream_t s);
+                            const GroupTable& gt, int32_t B, int32_t N, int32_t H, int32_t head_dim, hipStream_t s);
 
 // ---- small index helpers ---------------------------------------------------------
 int32_t ds_launch_set_offsets(int32_t* offsets, int32_t B, hipStream_t s);  // offsets[0..1] = {0, B}

@@ -655,7 +655,7 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
                        (int64_t)d.N * Hd, Hd, 0, d.N, 3, (int64_t)Hd * d.D, (int64_t)p.qkv_seg, Hd, p.offs, ml_t, gq,
                        DS_ACT_NONE, s));
         RC(ds_launch_attention(p.qkv, p.qkv + p.qkv_seg, p.qkv + 2 * p.qkv_seg, p.o, (int64_t)d.N * Hd, Hd, Hd,
-                               (int64_t)d.N * Hd, p.slot_group, gq, B, d.N, d.H, s));
+                               (int64_t)d.N * Hd, p.slot_group, gq, B, d.N, d.H, d.dh, s));
         RC(linear_gemm(p.o, (int64_t)d.N * Hd, Hd, (const bf16_t*)L[4], Hd, (const float*)L[5], p.x, x_ss, 0, 1, p.x, x_ss,
                        0, 0, d.N, 1, 0, 0, 0, p.offs, ml_t, gp, DS_ACT_NONE, s));
         RC(ds_launch_layernorm(xv, av, (const float*)L[6], (const float*)L[7], eps, p.slot_group, gq, B, d.N, 0, d.N, s));
@@ -736,15 +736,16 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
     VitDesc d;
     VitPlan p;
     parse_vit(net, &d);
+    const bool dh_ok = d.dh == 32 || d.dh == 48 || d.dh == 64;
     if (d.stem_dim) {
         const int sr = vit_stem_res(d);
-        if (d.dh != 64 || d.N > 224 || d.patch < 1 || (sr % d.patch) || d.N != (sr / d.patch) * (sr / d.patch) + 1)
-            DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 64, tokens <= 224, patch dividing the stem's map", who);
+        if (!dh_ok || d.N > 224 || d.patch < 1 || (sr % d.patch) || d.N != (sr / d.patch) * (sr / d.patch) + 1)
+            DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 32, 48 or 64, tokens <= 224, patch dividing the stem's map", who);
         if ((d.stem_dim % 8) || d.stem_dim > 64)
             DS_FAIL(DS_EALIGN, "%s: stem width must be a multiple of 8, at most 64", who);
-    } else if (d.dh != 64 || d.N > 224 || (d.image % d.patch) || d.N != (d.image / d.patch) * (d.image / d.patch) + 1 ||
+    } else if (!dh_ok || d.N > 224 || (d.image % d.patch) || d.N != (d.image / d.patch) * (d.image / d.patch) + 1 ||
                (d.patch % 8)) {
-        DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 64, tokens <= 224, patch %% 8 == 0", who);
+        DS_FAIL(DS_EUNSUPPORTED, "%s: vit needs head_dim 32, 48 or 64, tokens <= 224, patch %% 8 == 0", who);
     }
     for (int t = 0; t < d.T; ++t) {
         const int32_t* r = d.routes + d.rs * t;

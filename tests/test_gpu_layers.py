@@ -371,6 +371,46 @@ def test_sliced_mhsa(gpu_lib, N, B):
         assert np.all(np.isnan(yh[b, :, de:]))
 
 
+# DS-ViT++ stores 8 heads of 48 channels (Q-K-V widths 192..384 in steps of 48 with 4..8 heads); 32 is the
+# other head dimension the kernel takes
+@pytest.mark.parametrize("dh,H,N,B", [(48, 8, 197, 9), (48, 8, 33, 4), (32, 12, 50, 5), (32, 4, 224, 2)])
+def test_sliced_mhsa_head_dims(gpu_lib, dh, H, N, B):
+    D = 416
+    d = WL.nets.Draw(4100 + dh + N)
+    bf = WL.nets.as_bf16_values
+    x = bf(d.normal((B, N, D)))
+    wq, wk, wv = (bf(d.normal((H * dh, D), std=0.06)) for _ in range(3))
+    bq, bk, bv = (d.normal((H * dh,), std=0.1) for _ in range(3))
+    wp, bp = bf(d.normal((D, H * dh), std=0.05)), d.normal((D,), std=0.1)
+    routes = [(192, H // 2), (256, H // 2 + 1), (416, H), (320, H - 1), (192, H), (416, 1)]
+    route = d.randint(B, len(routes))
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), len(routes))
+    g = gpu_lib.make_groups(off, perm, [r[0] for r in routes], [r[1] * dh for r in routes])
+    y = torch.full((B, N, D), float("nan"), dtype=torch.bfloat16, device=DEV)
+    xg = dev(x, torch.bfloat16)
+    gpu_lib.ds_sliced_mhsa(xg, dev(np.stack([wq, wk, wv]), torch.bfloat16), dev(np.stack([bq, bk, bv])),
+                           dev(wp, torch.bfloat16), dev(bp), H, dh, g, residual=xg, y=y)
+    yh = host(y)
+    for b in range(B):
+        de, h = routes[route[b]]
+        att = O.sliced_mhsa(x[b, :, :de], wq, bq, wk, bk, wv, bv, wp, bp, h, dh, store="bf16")
+        want = O.bf16_round(x[b, :, :de] + att)
+        assert relerr(yh[b, :, :de], want) < TOL_BF16, (b, de, h)
+        assert np.all(np.isnan(yh[b, :, de:]))
+
+
+def test_sliced_mhsa_rejects_other_head_dims(gpu_lib):
+    D, H, dh, B, N = 128, 2, 40, 2, 16
+    x = torch.zeros((B, N, D), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((3, H * dh, D), dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros((3, H * dh), dtype=torch.float32, device=DEV)
+    wp, bp = torch.zeros((D, H * dh), dtype=torch.bfloat16, device=DEV), torch.zeros((D,), dtype=torch.float32, device=DEV)
+    off = torch.tensor([0, B], dtype=torch.int32, device=DEV)
+    g = gpu_lib.make_groups(off, None, [D], [H * dh])
+    with pytest.raises(gpu_lib.DsError):
+        gpu_lib.ds_sliced_mhsa(x, w, b, wp, bp, H, dh, g, residual=x, y=torch.empty_like(x))
+
+
 def test_sliced_mhsa_rejects_sequences_beyond_224(gpu_lib):
     D, H, dh, B, N = 128, 2, 64, 2, 225
     x = torch.zeros((B, N, D), dtype=torch.bfloat16, device=DEV)

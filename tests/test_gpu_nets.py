@@ -261,6 +261,34 @@ def test_vit_stem_batch256(gpu_lib):
     assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
 
 
+def test_vit_pp_small_all_samples(gpu_lib):
+    # the DS-ViT++ supernet shape in small: stem, 8 stored heads of 48, embedding up to 416, MLP ratios 3 / 3.5 / 4,
+    # 8 nested routes that also differ in depth (2..4 of 4 stored blocks)
+    arch = WL.vit_arch(image=64, patch=8, embed=416, heads=8, head_dim=48, mlp=1664, depth=4, routes="pp", stem_dim=24)
+    assert arch["tokens"] == 17 and arch["T"] == 8
+    params = WL.vit_params(arch, S + 80)
+    B = 27
+    imgs = WL.images(S + 81, B, 64)
+    lb = WL.seeded_logit_bias(S + 82, B, arch["T"], amp=16.0)
+    net, xg, lbg, logits, rt = _vit_stem_case(gpu_lib, arch, params, imgs, lb, range(B))
+    assert len(set(rt.cpu().numpy()[0].tolist())) == arch["T"]
+
+
+def test_vit_pp_batch256(gpu_lib):
+    # DS-ViT++ at the sizes of its routing-space table: 224x224 images, stem at 24 channels, 197 tokens, embedding
+    # 192..416, 4..8 heads of 48, depth 12..14
+    arch = WL.vit_arch(embed=416, heads=8, head_dim=48, mlp=1664, depth=14, routes="pp", stem_dim=24, patch=8)
+    assert arch["tokens"] == 197
+    params = WL.vit_params(arch, S + 85)
+    B = 256
+    imgs = WL.images(S + 185, B)
+    lb = WL.seeded_logit_bias(S + 285, B, arch["T"], amp=16.0)
+    target = np.argmax(lb, axis=1)
+    check = [int(np.where(target == t)[0][0]) for t in (0, 3, 7)]
+    net, xg, lbg, logits, routes = _vit_stem_case(gpu_lib, arch, params, imgs, lb, check)
+    assert np.bincount(routes.cpu().numpy()[0], minlength=8).min() >= 28
+
+
 def test_vit_config5_batch256(gpu_lib):
     arch = WL.vit_arch()
     params = WL.vit_params(arch, S + 5)

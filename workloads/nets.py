@@ -215,7 +215,8 @@ def vit_arch(image: int = 224, patch: int = 16, embed: int = 384, heads: int = 6
     """routes[t] = (d_e, h, hidden): embedding slice, head count and MLP hidden slice.
 
     "cross": every combination of 4 embedding slices, 4 head counts and MLP
-    ratios 2,3,4 (hidden = ratio * d_e); "diag": 4 nested routes; "depth": the 4 nested
+    ratios 2,3,4 (hidden = ratio * d_e); "diag": 4 nested routes; "pp": 8 nested routes of the
+    DS-ViT++ space (use embed=416, heads=8, head_dim=48, mlp=1664, depth=14); "depth": the 4 nested
     routes, each at 3 depths (depth - 2, depth - 1, depth), as (d_e, h, hidden, blocks).
 
     stem_dim > 0: the convolutional stem of Section 3.4 (7x7 stride-2 convolution and two
@@ -230,6 +231,17 @@ def vit_arch(image: int = 224, patch: int = 16, embed: int = 384, heads: int = 6
     elif routes == "diag":
         table = [(de_list[0], h_list[0], 2 * de_list[0]), (de_list[1], h_list[1], 3 * de_list[1]),
                  (de_list[2], h_list[2], 3 * de_list[2]), (de_list[3], h_list[3], 4 * de_list[3])]
+    elif routes == "pp":
+        # the DS-ViT++ routing space (its table in Section 5.2): embedding 192..416 in steps of 32, Q-K-V width
+        # 48 h with h = 4..8 heads, MLP ratio 3 / 3.5 / 4, depth - 2 .. depth blocks; 8 nested routes along
+        # the diagonal of that space, scaled to the stored sizes given
+        s13 = embed // 13
+        table = []
+        for i in range(8):
+            de = 6 * s13 + i * s13
+            h = heads - 4 + (i * 4 + 3) // 7
+            ratio2 = 6 + (i * 2 + 3) // 7                      # twice the MLP ratio: 6, 7 or 8
+            table.append((de, h, ratio2 * de // 2, depth - 2 + (i * 2 + 3) // 7))
     elif routes == "depth":
         diag = [(de_list[0], h_list[0], 2 * de_list[0]), (de_list[1], h_list[1], 3 * de_list[1]),
                 (de_list[2], h_list[2], 3 * de_list[2]), (de_list[3], h_list[3], 4 * de_list[3])]
