@@ -208,6 +208,36 @@ def sliced_dwconv2d(x, w, stride=1, pad=1):
     return y
 
 
+def spatial_dwconv2d(x, w, k, dilation=1, stride=1, pad=0):
+    """Depthwise convolution with a spatially sliced filter (Section 3.2).
+
+    Kernel size (Eq. 11): the centred k x k block W[:, :, k0:k0+k, k0:k0+k], k0 = (K - k) / 2, of the
+    stored K x K filter.  Dilation (Eq. 12): every `dilation`-th tap of that block, W[..., ::l, ::l];
+    the taps keep their spacing, i.e. the n = ceil(k / l) selected taps per axis act as an n x n
+    convolution of dilation l.  Padding (Eq. 13): `pad` zeros per side (the input padded to the
+    maximum and cropped back is the same thing), which sets the output resolution
+    (H + 2 pad - span) / stride + 1 with span = (n - 1) l + 1.
+    x: [c, H, W] valid channels; w: [C, 1, K, K]."""
+    x = np.asarray(x, F64)
+    w = np.asarray(w, F64)
+    c, H, W = x.shape
+    K = w.shape[2]
+    assert (K - k) % 2 == 0 and 1 <= k <= K and dilation >= 1
+    k0 = (K - k) // 2
+    taps = list(range(k0, k0 + k, dilation))
+    span = (len(taps) - 1) * dilation + 1
+    Ho = (H + 2 * pad - span) // stride + 1
+    Wo = (W + 2 * pad - span) // stride + 1
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad)))
+    y = np.zeros((c, Ho, Wo), F64)
+    for i, u in enumerate(taps):
+        for j, v in enumerate(taps):
+            a, b = i * dilation, j * dilation
+            view = xp[:, a:a + stride * (Ho - 1) + 1:stride, b:b + stride * (Wo - 1) + 1:stride]
+            y += w[:c, 0, u, v][:, None, None] * view
+    return y
+
+
 def re_sbn(x, bn, t, eps):
     """Eq. 14: gamma[:c] * (x - mu_t) / sigma_t + beta[:c] with route t's statistics;
     sigma_t = sqrt(var_t + eps).  x: [c, H, W]."""

@@ -127,6 +127,44 @@ def test_conv_masked_full_nesting_additivity():
 
 
 # ------------------------------------------------------------------ depthwise conv
+@pytest.mark.parametrize("k,l,stride,pad", [(3, 1, 1, 1), (5, 1, 1, 2), (7, 1, 2, 3), (7, 2, 1, 3), (7, 3, 1, 3),
+                                            (5, 2, 2, 0), (3, 1, 1, 0), (7, 1, 1, 0), (5, 1, 2, 3), (1, 1, 1, 0)])
+def test_spatial_dwconv_matches_library_brute_force_and_masked_full(k, l, stride, pad):
+    # kernel size = centred crop (Eq. 11), dilation = every l-th tap kept at its spacing (Eq. 12), padding
+    # (Eq. 13): against torch's dilated grouped convolution on explicitly copied taps, against plain loops,
+    # and - at the padding that keeps the taps where the stored filter has them - against the full 7x7
+    # filter with the unselected taps zeroed (the masking view of Eq. 7)
+    C, c, H, W, K = 7, 5, 11, 9, 7
+    x = RNG.standard_normal((c, H, W))
+    w = RNG.standard_normal((C, 1, K, K))
+    k0 = (K - k) // 2
+    got = O.spatial_dwconv2d(x, w, k, l, stride, pad)
+    wsel = w[:c, :, k0:k0 + k:l, k0:k0 + k:l].copy()
+    want = F.conv2d(t64(x)[None], t64(wsel), stride=stride, padding=pad, dilation=l, groups=c)[0].numpy()
+    assert got.shape == want.shape
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    # plain loops for a few outputs
+    n = wsel.shape[-1]
+    for ch, yy, xx in [(0, 0, 0), (4, got.shape[1] - 1, got.shape[2] - 1), (2, 1, 0)]:
+        acc = 0.0
+        for i in range(n):
+            for j in range(n):
+                a, b = yy * stride - pad + i * l, xx * stride - pad + j * l
+                if 0 <= a < H and 0 <= b < W:
+                    acc += w[ch, 0, k0 + i * l, k0 + j * l] * x[ch, a, b]
+        assert abs(got[ch, yy, xx] - acc) < 1e-12
+    # masked full filter: zero every tap that is not selected, pad by (K-1)/2; equal when pad = (K-1)/2 - k0
+    if pad == (K - 1) // 2 - k0:
+        mask = np.zeros((K, K))
+        sel = list(range(k0, k0 + k, l))
+        mask[np.ix_(sel, sel)] = 1.0
+        full = O.sliced_dwconv2d(x, w * mask, stride, (K - 1) // 2)
+        np.testing.assert_allclose(got, full, rtol=1e-12, atol=1e-12)
+    # the plain 3x3 layer is the k = K = 3 case
+    w3 = RNG.standard_normal((C, 1, 3, 3))
+    np.testing.assert_array_equal(O.spatial_dwconv2d(x, w3, 3, 1, stride, 1), O.sliced_dwconv2d(x, w3, stride, 1))
+
+
 @pytest.mark.parametrize("stride", [1, 2])
 def test_dwconv_matches_library_and_brute(stride):
     C, c, H, W = 9, 6, 8, 7
