@@ -153,6 +153,29 @@ int32_t ds_sliced_dwconv(const void* x, int32_t B, int32_t C, int32_t H, int32_t
                          int32_t stride, int32_t act, void* y, void* ws, size_t ws_bytes,
                          void* stream);
 
+/* Depthwise convolution with a spatially sliced filter (Section 3.2: kernel size Eq. 11,
+ * dilation Eq. 12, padding Eq. 13).  The filter is stored once as K x K taps (K odd, at most 7;
+ * w: device bf16 [K, K, C]).  Group t uses the centred ksize[t] x ksize[t] block of it
+ * (K - ksize[t] even), of that block every dilation[t]-th tap, applied at dilation[t] (the taps
+ * keep the spacing they have in the stored filter), with pad[t] zeros on each side; its output is
+ * Ho_t x Wo_t = (H + 2 pad - span) / stride + 1 with span = (ceil(ksize / dilation) - 1) dilation + 1.
+ * With pad[t] = (K - 1) / 2 - (K - ksize[t]) / 2 this equals the full K x K filter with the
+ * unselected taps zeroed and padding (K - 1) / 2.  Split batch-norm and activation as in
+ * ds_sliced_dwconv.  x: device bf16 [B, H, W, C]; y: device bf16, sample b at
+ * y + b * y_sample_stride, holding [Ho_t, Wo_t, C] packed (row stride Wo_t * C, channel stride C,
+ * channels beyond k_in[t] not written); y_sample_stride >= Ho_t * Wo_t * C for every group.
+ * Host struct. */
+typedef struct ds_spatial {
+    int32_t ksize[DS_MAX_GROUPS];
+    int32_t dilation[DS_MAX_GROUPS];
+    int32_t pad[DS_MAX_GROUPS];
+} ds_spatial;
+int32_t ds_sliced_dwconv_spatial(const void* x, int32_t B, int32_t C, int32_t H, int32_t W,
+                                 const void* w, int32_t K, const float* scale, const float* shift,
+                                 const ds_groups* g, const ds_spatial* sp, int32_t stride,
+                                 int32_t act, void* y, int64_t y_sample_stride, void* ws,
+                                 size_t ws_bytes, void* stream);
+
 /* LayerNorm over the k_in[t] valid features of each row with gamma[:k], beta[:k]
  * (the statistics use the valid features only).  x, y: device bf16 [B, rows, ld]. */
 int32_t ds_sliced_layernorm(const void* x, int64_t x_ld, const float* gamma, const float* beta,

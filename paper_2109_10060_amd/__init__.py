@@ -32,7 +32,7 @@ EXPORTS = [
     "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_gate_double_workspace",
     "ds_gate_double", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
-    "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
+    "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_dwconv_spatial", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
     "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
 ]
 
@@ -47,6 +47,11 @@ class ds_groups(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("offsets", ctypes.c_void_p), ("perm", ctypes.c_void_p),
                 ("k_in", ctypes.c_int32 * DS_MAX_GROUPS), ("k_out", ctypes.c_int32 * DS_MAX_GROUPS),
                 ("table_row", ctypes.c_int32 * DS_MAX_GROUPS)]
+
+
+class ds_spatial(ctypes.Structure):
+    _fields_ = [("ksize", ctypes.c_int32 * DS_MAX_GROUPS), ("dilation", ctypes.c_int32 * DS_MAX_GROUPS),
+                ("pad", ctypes.c_int32 * DS_MAX_GROUPS)]
 
 
 class ds_net(ctypes.Structure):
@@ -234,6 +239,32 @@ def ds_sliced_dwconv(x, w, scale, shift, groups: ds_groups, stride: int, act=DS_
                               ctypes.byref(groups), stride, act, _ptr(y), _ptr(ws), ctypes.c_size_t(ws.numel()),
                               _stream()))
     return y
+
+
+def ds_sliced_dwconv_spatial(x, w, scale, shift, groups: ds_groups, ksize: Sequence[int], dilation: Sequence[int],
+                             pad: Sequence[int], stride: int, act=DS_ACT_RELU, y=None):
+    """x: [B,H,W,C] bf16; w: [K,K,C] bf16.  y: [B, rows_max, C] with each sample's Ho_t x Wo_t pixels packed at
+    the start of its block (rows_max = the largest Ho_t * Wo_t); returns (y, [(Ho_t, Wo_t) per group])."""
+    lib = load()
+    B, H, W, C = x.shape
+    K = w.shape[0]
+    sp = ds_spatial()
+    res = []
+    for t in range(groups.T):
+        sp.ksize[t], sp.dilation[t], sp.pad[t] = int(ksize[t]), int(dilation[t]), int(pad[t])
+        dl = max(int(dilation[t]), 1)          # an invalid table is reported by the library, not here
+        n = (int(ksize[t]) + dl - 1) // dl
+        span = (n - 1) * dl + 1
+        res.append(((H + 2 * int(pad[t]) - span) // stride + 1, (W + 2 * int(pad[t]) - span) // stride + 1))
+    rows_max = max(max(a * b for a, b in res), 1)
+    if y is None:
+        y = torch.zeros((B, rows_max, C), dtype=x.dtype, device=x.device)
+    ws = _ws(lib.ds_slot_workspace(B), x)
+    _chk(lib.ds_sliced_dwconv_spatial(_ptr(x, torch.bfloat16), B, C, H, W, _ptr(w, torch.bfloat16), K, _ptr(scale), _ptr(shift),
+                                      ctypes.byref(groups), ctypes.byref(sp), stride, act, _ptr(y),
+                                      ctypes.c_int64(y.shape[1] * y.shape[2]), _ptr(ws), ctypes.c_size_t(ws.numel()),
+                                      _stream()))
+    return y, res
 
 
 def ds_sliced_layernorm(x, gamma, beta, eps: float, groups: ds_groups, y=None):

@@ -179,6 +179,50 @@ extern "C" int32_t ds_sliced_dwconv(const void* x, int32_t B, int32_t C, int32_t
     return ds_launch_dwconv(xv, yv, (const bf16_t*)w, scale, shift, C, slot_group, gt, B, C, H, W, stride, act, s);
 }
 
+extern "C" int32_t ds_sliced_dwconv_spatial(const void* x, int32_t B, int32_t C, int32_t H, int32_t W, const void* w,
+                                            int32_t K, const float* scale, const float* shift, const ds_groups* g,
+                                            const ds_spatial* sp, int32_t stride, int32_t act, void* y,
+                                            int64_t y_sample_stride, void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "ds_sliced_dwconv_spatial";
+    if (B < 0 || C < 1 || H < 1 || W < 1 || stride < 1 || stride > 4) DS_FAIL(DS_EINVAL, "%s: bad size", who);
+    if (K < 1 || K > 7 || (K % 2) == 0) DS_FAIL(DS_EUNSUPPORTED, "%s: stored filter size %d (odd, at most 7)", who, K);
+    if (act != DS_ACT_NONE && act != DS_ACT_RELU) DS_FAIL(DS_EUNSUPPORTED, "%s: activation", who);
+    if (!sp) DS_FAIL(DS_EINVAL, "%s: null spatial table", who);
+    GroupTable gt;
+    int mi, mo;
+    int32_t rc = check_groups(who, g, C, C, true, &gt, &mi, &mo);
+    if (rc) return rc;
+    SpatialTable st;
+    memset(&st, 0, sizeof(st));
+    for (int t = 0; t < g->T; ++t) {
+        const int k = sp->ksize[t], l = sp->dilation[t], pad = sp->pad[t];
+        if (k < 1 || k > K || ((K - k) % 2)) DS_FAIL(DS_EINVAL, "%s: group %d kernel size %d is no centred block of %d", who, t, k, K);
+        if (l < 1 || pad < 0 || pad > 16) DS_FAIL(DS_EINVAL, "%s: group %d dilation %d / padding %d", who, t, l, pad);
+        st.k0[t] = (K - k) / 2;
+        st.n[t] = (k + l - 1) / l;
+        st.l[t] = l;
+        st.pad[t] = pad;
+        const int span = (st.n[t] - 1) * l + 1;
+        const int Ho = (H + 2 * pad - span) / stride + 1, Wo = (W + 2 * pad - span) / stride + 1;
+        if (H + 2 * pad < span || W + 2 * pad < span) DS_FAIL(DS_ESHAPE, "%s: group %d has no output pixel", who, t);
+        if ((int64_t)Ho * Wo * C > y_sample_stride) DS_FAIL(DS_ESHAPE, "%s: group %d output exceeds y_sample_stride", who, t);
+    }
+    if (B == 0) return DS_OK;
+    if (!x || !w || !y || !scale || !shift) DS_FAIL(DS_EINVAL, "%s: null tensor", who);
+    if ((C % 8) || (y_sample_stride % 8) || !ds_aligned16(x) || !ds_aligned16(w) || !ds_aligned16(y) || !ds_aligned16(scale) ||
+        !ds_aligned16(shift))
+        DS_FAIL(DS_EALIGN, "%s: needs 16-byte aligned pointers, C %% 8 == 0 and y_sample_stride %% 8 == 0", who);
+    if ((int64_t)H * W * C * 2 >= 0x7fffffffLL) DS_FAIL(DS_EUNSUPPORTED, "%s: a sample spans 2 GiB or more", who);
+    if (!ws || ws_bytes < ds_slot_workspace(B)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes", who, ds_slot_workspace(B));
+    hipStream_t s = (hipStream_t)stream;
+    int32_t* slot_group = (int32_t*)ws;
+    rc = ds_launch_expand_groups(g->offsets, g->T, slot_group, s);
+    if (rc) return rc;
+    ActView xv = {(void*)x, g->perm, (int64_t)H * W * C, C};
+    ActView yv = {y, g->perm, y_sample_stride, C};
+    return ds_launch_dwconv_spatial(xv, yv, (const bf16_t*)w, K, scale, shift, C, slot_group, gt, st, B, C, H, W, stride, act, s);
+}
+
 extern "C" int32_t ds_sliced_layernorm(const void* x, int64_t x_ld, const float* gamma, const float* beta, float eps,
                                        const ds_groups* g, int32_t B, int32_t rows, void* y, int64_t y_ld, void* ws,
                                        size_t ws_bytes, void* stream) {

@@ -53,6 +53,15 @@ struct GroupTable {
     int32_t row[DS_MAX_GROUPS];
 };
 
+// per-group spatial slice of a stored KS x KS filter (Section 3.2, Eq. 11-13): the taps k0 + i*l, i < n, per axis
+// (centred k x k block, every l-th tap), applied at dilation l with `pad` zeros per side
+struct SpatialTable {
+    int32_t k0[DS_MAX_GROUPS];
+    int32_t n[DS_MAX_GROUPS];
+    int32_t l[DS_MAX_GROUPS];
+    int32_t pad[DS_MAX_GROUPS];
+};
+
 // ---- grouped GEMM / implicit-GEMM convolution -------------------------------
 #define DS_GEMM_BM 128
 
@@ -145,6 +154,10 @@ int32_t ds_launch_expand_groups(const int32_t* offsets, int32_t T, int32_t* slot
 int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* scale, const float* shift,
                          int32_t tab_ld, const int32_t* slot_group, const GroupTable& gt, int32_t B, int32_t C,
                          int32_t H, int32_t W, int32_t stride, int32_t act, hipStream_t s);
+// spatially sliced filter; y is packed [Ho_t][Wo_t][ld] per slot, the resolution following the group's padding
+int32_t ds_launch_dwconv_spatial(ActView x, ActView y, const bf16_t* w, int32_t KS, const float* scale, const float* shift,
+                                 int32_t tab_ld, const int32_t* slot_group, const GroupTable& gt, const SpatialTable& st,
+                                 int32_t B, int32_t C, int32_t H, int32_t W, int32_t stride, int32_t act, hipStream_t s);
 int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const float* beta, float eps,
                             const int32_t* slot_group, const GroupTable& gt, int32_t B, int32_t rows,
                             int32_t row0, int32_t n_rows, hipStream_t s);

@@ -187,6 +187,88 @@ __global__ __launch_bounds__(256, 3) void dwconv4_kernel(ActView x, ActView y, c
     }
 }
 
+// ---- depthwise convolution with a spatially sliced filter (Section 3.2, Eq. 11-13) --------------
+// The filter is stored once as KS x KS taps ([KS][KS][C]); a route uses the centred k x k block of it
+// (Eq. 11), every l-th tap of that block at dilation l (Eq. 12) and its own padding (Eq. 13), which also
+// sets its output resolution.  One slot per blockIdx.y, so the route's tap count N is uniform over the
+// workgroup and picks a fully unrolled row routine: the N input pixels and N filter taps of a row are
+// all requested (branch-free buffer loads, zeros outside the image) before the first multiply.
+// A lane owns 8 channels of one output pixel; the output is packed [Ho_t][Wo_t][width] per slot.
+template <int N>
+__device__ __forceinline__ void dws_rows(float (&acc)[8], const __amdgpu_buffer_rsrc_t rsrc, const bf16_t* w, int KS, int C,
+                                         int k0, int l, int iy0, int ix0, int H, int W, int xld, int ch) {
+    constexpr uint32_t OOB = 0x80000000u;
+#pragma unroll 1
+    for (int i = 0; i < N; ++i) {
+        const int iy = iy0 + i * l;
+        const bool rok = iy >= 0 && iy < H;
+        uint4 xin[N], win[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const int ix = ix0 + j * l;
+            const uint32_t off = (rok && ix >= 0 && ix < W) ? (uint32_t)(((iy * W + ix) * xld + ch) * 2) : OOB;
+            const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+            xin[j] = make_uint4(t[0], t[1], t[2], t[3]);
+            win[j] = *(const uint4*)(w + ((k0 + i * l) * KS + k0 + j * l) * C + ch);
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const uint32_t xq[4] = {xin[j].x, xin[j].y, xin[j].z, xin[j].w};
+            const uint32_t wq[4] = {win[j].x, win[j].y, win[j].z, win[j].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bf16x2_t xv = __builtin_bit_cast(bf16x2_t, xq[q]);
+                acc[2 * q] = __builtin_amdgcn_fdot2_f32_bf16(xv, __builtin_bit_cast(bf16x2_t, wq[q] & 0x0000ffffu), acc[2 * q], false);
+                acc[2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(xv, __builtin_bit_cast(bf16x2_t, wq[q] & 0xffff0000u), acc[2 * q + 1], false);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void dwconv_spatial_kernel(ActView x, ActView y, const bf16_t* w, int KS,
+                                                             const float* scale, const float* shift, int tab_ld,
+                                                             const int32_t* slot_group, const GroupTable gt,
+                                                             const SpatialTable st, int C, int H, int W, int stride,
+                                                             int act) {
+    const int slot = blockIdx.y;
+    const int g = slot_group ? slot_group[slot] : 0;
+    const int c = gt.k_in[g];
+    const int chunks = c >> 3;
+    const int n = st.n[g], l = st.l[g], pad = st.pad[g], k0 = st.k0[g];
+    const int span = (n - 1) * l + 1;
+    const int Ho = (H + 2 * pad - span) / stride + 1, Wo = (W + 2 * pad - span) / stride + 1;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (Ho <= 0 || Wo <= 0 || idx >= Ho * Wo * chunks) return;
+    const int pix = idx / chunks, ch = (idx - pix * chunks) * 8;
+    const int oy = pix / Wo, ox = pix - oy * Wo;
+    const int xs = x.index ? x.index[slot] : slot;
+    const int ys = y.index ? y.index[slot] : slot;
+    const int xld = x.ld > 0 ? x.ld : c, yld = y.ld > 0 ? y.ld : c;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const bf16_t*)x.p + (int64_t)xs * x.sample_stride), 0, 0x7fffffff, 0x00020000);
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int iy0 = oy * stride - pad, ix0 = ox * stride - pad;
+    switch (n) {   // uniform over the workgroup
+        case 1: dws_rows<1>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+        case 2: dws_rows<2>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+        case 3: dws_rows<3>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+        case 4: dws_rows<4>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+        case 5: dws_rows<5>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+        case 6: dws_rows<6>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+        default: dws_rows<7>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+    }
+    const int64_t ti = (int64_t)gt.row[g] * tab_ld + ch;
+    float sc[8], sh[8];
+    loadf8(scale + ti, sc);
+    loadf8(shift + ti, sh);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        acc[i] = acc[i] * sc[i] + sh[i];
+        if (act == DS_ACT_RELU) acc[i] = fmaxf(acc[i], 0.f);
+    }
+    *(uint4*)((bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)pix * yld + ch) = pack8(acc);
+}
+
 // ---- channel re-weighting by the attention head of the gate (Section 3.5, Eq. 23) ---------
 // NHWC bf16: 8 channels per thread; channels at or beyond the sample's width are not touched
 __global__ __launch_bounds__(256) void channel_scale_nhwc_bf16_kernel(const bf16_t* x, bf16_t* y, const float* scale,
@@ -548,6 +630,28 @@ int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* sca
         hipLaunchKernelGGL((dwconv4_kernel<2, DW_PX_S2>), grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
                            Ho, Wo, act);
     DS_CHECK_LAUNCH("depthwise conv");
+    return DS_OK;
+}
+
+int32_t ds_launch_dwconv_spatial(ActView x, ActView y, const bf16_t* w, int32_t KS, const float* scale, const float* shift,
+                                 int32_t tab_ld, const int32_t* slot_group, const GroupTable& gt, const SpatialTable& st,
+                                 int32_t B, int32_t C, int32_t H, int32_t W, int32_t stride, int32_t act, hipStream_t s) {
+    if (B <= 0) return DS_OK;
+    int64_t nmax = 0;
+    for (int t = 0; t < gt.T; ++t) {
+        if (st.n[t] < 1 || st.n[t] > 7) DS_FAIL(DS_EUNSUPPORTED, "spatial depthwise conv: %d taps per axis (1..7)", st.n[t]);
+        const int span = (st.n[t] - 1) * st.l[t] + 1;
+        const int Ho = (H + 2 * st.pad[t] - span) / stride + 1, Wo = (W + 2 * st.pad[t] - span) / stride + 1;
+        if (Ho <= 0 || Wo <= 0) continue;
+        const int64_t n = (int64_t)Ho * Wo * (gt.k_in[t] / 8);
+        nmax = n > nmax ? n : nmax;
+    }
+    if (nmax <= 0) return DS_OK;
+    dim3 grid((unsigned)((nmax + 255) / 256), (unsigned)B);
+    ProfScope prof(DS_K_DWCONV, s);
+    hipLaunchKernelGGL(dwconv_spatial_kernel, grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld, slot_group, gt, st, C, H,
+                       W, stride, act);
+    DS_CHECK_LAUNCH("spatial depthwise conv");
     return DS_OK;
 }
 

@@ -323,6 +323,78 @@ def test_sliced_dwconv(gpu_lib, stride, H, C):
         assert np.all(np.isnan(yh[b, c:]))
 
 
+# spatially sliced depthwise filter (Section 3.2, Eq. 11-13): per route a centred block of the stored 7x7 filter,
+# optionally every other / every third tap at that dilation, and its own padding, hence its own output resolution
+@pytest.mark.parametrize("stride,H,C,K", [(1, 14, 512, 7), (2, 14, 512, 7), (1, 28, 72, 5), (2, 9, 64, 3)])
+def test_sliced_dwconv_spatial(gpu_lib, stride, H, C, K):
+    B = 11
+    d = WL.nets.Draw(2100 + stride + C + K)
+    x = WL.nets.as_bf16_values(d.normal((B, C, H, H)))
+    w = WL.nets.as_bf16_values(d.normal((C, 1, K, K), std=0.3))
+    # (kernel size, dilation, padding): same-size crops, a dilated full filter, valid (unpadded) and over-padded routes
+    spec = [(3, 1, 1), (5, 1, 2), (7, 1, 3), (7, 2, 3), (7, 3, 3), (3, 1, 0), (5, 2, 1), (1, 1, 0), (7, 1, 1), (3, 1, 3)]
+    spec = [(k, l, p) for k, l, p in spec if k <= K and (K - k) % 2 == 0]
+    T = len(spec)
+    bn = WL.bn_tables(d, T, C)
+    route = np.arange(B, dtype=np.int32) % T
+    route = route[d.permutation(B)]
+    cs = [max(8, C * (1 + t % 4) // 4 // 8 * 8) for t in range(T)]
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    scale, shift = gpu_lib.ds_bn_fold(dev(bn["gamma"]), dev(bn["beta"]), dev(bn["mean"]), dev(bn["var"]), 1e-5)
+    g = gpu_lib.make_groups(off, perm, cs)
+    res = []
+    for k, l, p in spec:
+        n = (k + l - 1) // l
+        res.append((H + 2 * p - ((n - 1) * l + 1)) // stride + 1)
+    rows_max = max(r * r for r in res)
+    y = torch.full((B, rows_max, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+    _, got_res = gpu_lib.ds_sliced_dwconv_spatial(
+        dev(x.transpose(0, 2, 3, 1), torch.bfloat16), dev(w[:, 0].transpose(1, 2, 0), torch.bfloat16), scale, shift, g,
+        [s_[0] for s_ in spec], [s_[1] for s_ in spec], [s_[2] for s_ in spec], stride, y=y)
+    assert [r[0] for r in got_res] == res
+    yh = host(y)
+    for b in range(B):
+        t = int(route[b])
+        k, l, p = spec[t]
+        c, r = cs[t], res[t]
+        want = O.bf16_round(O.relu(O.re_sbn(O.spatial_dwconv2d(x[b, :c], w, k, l, stride, p), bn, t, 1e-5)))
+        assert want.shape == (c, r, r)
+        got = yh[b, :r * r, :c].reshape(r, r, c).transpose(2, 0, 1)
+        assert relerr(got, want) < TOL_BF16, (b, spec[t])
+        assert np.all(np.isnan(yh[b, :r * r, c:])) and np.all(np.isnan(yh[b, r * r:]))
+    # the plain 3x3 entry point is the K = 3, k = 3, padding 1 case of this one
+    if K == 3:
+        g3 = gpu_lib.make_groups(off, perm, cs)
+        Ho = (H - 1) // stride + 1
+        y3 = torch.full((B, Ho, Ho, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+        gpu_lib.ds_sliced_dwconv(dev(x.transpose(0, 2, 3, 1), torch.bfloat16), dev(w[:, 0].transpose(1, 2, 0), torch.bfloat16),
+                                 scale, shift, g3, stride, y=y3)
+        ys = torch.full((B, Ho * Ho, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+        gpu_lib.ds_sliced_dwconv_spatial(dev(x.transpose(0, 2, 3, 1), torch.bfloat16),
+                                         dev(w[:, 0].transpose(1, 2, 0), torch.bfloat16), scale, shift, g3,
+                                         [3] * T, [1] * T, [1] * T, stride, y=ys)
+        a, b_ = host(y3).reshape(B, Ho * Ho, C), host(ys)
+        assert np.array_equal(np.isnan(a), np.isnan(b_)) and relerr(np.nan_to_num(b_), np.nan_to_num(a)) < 1e-2
+
+
+def test_sliced_dwconv_spatial_rejects_bad_tables(gpu_lib):
+    B, C, H, K = 2, 16, 8, 7
+    x = torch.zeros((B, H, H, C), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((K, K, C), dtype=torch.bfloat16, device=DEV)
+    sc = torch.ones((1, C), dtype=torch.float32, device=DEV)
+    off = torch.tensor([0, B], dtype=torch.int32, device=DEV)
+    g = gpu_lib.make_groups(off, None, [C])
+    for k, l, p in [(4, 1, 1), (9, 1, 1), (3, 0, 1), (3, 1, -1), (7, 1, 0)]:      # even crop, too large, dilation 0, negative pad, ok
+        if (k, l, p) == (7, 1, 0):
+            gpu_lib.ds_sliced_dwconv_spatial(x, w, sc, sc, g, [k], [l], [p], 1)
+        else:
+            with pytest.raises(gpu_lib.DsError):
+                gpu_lib.ds_sliced_dwconv_spatial(x, w, sc, sc, g, [k], [l], [p], 1)
+    xs = torch.zeros((B, 4, 4, C), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(gpu_lib.DsError):                                          # no output pixel: 7 taps on a 4x4 map
+        gpu_lib.ds_sliced_dwconv_spatial(xs, w, sc, sc, g, [7], [1], [0], 1, y=torch.zeros((B, 1, C), dtype=torch.bfloat16, device=DEV))
+
+
 # ------------------------------------------------------------------ LayerNorm
 def test_sliced_layernorm(gpu_lib):
     B, N, D, T = 13, 29, 384, 4
