@@ -322,7 +322,9 @@ def _conv_bn_relu(x, w, bn, t, eps, c_out, stride, pad, store, act=True, residua
 
 def forward_mbnet(arch, p, image, logit_bias=None, route_override=None, store="bf16", taps=None):
     """DS-MBNet: stem, 5 fixed depthwise-separable blocks, gate, 8 sliced blocks,
-    pool, classifier with sliced input width.  Returns (logits[1000], route, gate scores)."""
+    pool, classifier with sliced input width.  Returns (logits[1000], route, gate scores).
+    With arch["ksize"] (DS-MBNet++) the depthwise filters are stored larger and a route also
+    picks their kernel size."""
     eps = arch["bn_eps"]
     x = _conv_bn_relu(np.asarray(image, F64), p["stem.w"], p["stem.bn"], 0, eps,
                       arch["stem_out"], 2, 1, store)
@@ -336,7 +338,14 @@ def forward_mbnet(arch, p, image, logit_bias=None, route_override=None, store="b
         c_in = int(arch["cin"][t, i])
         c_out = int(arch["cout"][t, i])
         assert x.shape[0] == c_in
-        y = re_sbn(sliced_dwconv2d(x, p[f"ds{i}.dw.w"], s, 1), p[f"ds{i}.dw.bn"], tb, eps)
+        if "ksize" in arch:
+            # DS-MBNet++: the route's centred block of the stored filter (Eq. 11) at the padding that keeps
+            # the resolution
+            k = int(arch["ksize"][t, i])
+            y = spatial_dwconv2d(x, p[f"ds{i}.dw.w"], k, 1, s, (k - 1) // 2)
+        else:
+            y = sliced_dwconv2d(x, p[f"ds{i}.dw.w"], s, 1)
+        y = re_sbn(y, p[f"ds{i}.dw.bn"], tb, eps)
         x = _store(relu(y), store)
         x = _conv_bn_relu(x, p[f"ds{i}.pw.w"], p[f"ds{i}.pw.bn"], tb, eps, c_out, 1, 0, store)
         if taps is not None:

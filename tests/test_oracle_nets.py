@@ -89,7 +89,11 @@ def _ref_mbnet(arch, p, img, t):
     for i, (_a, _b, s) in enumerate(arch["blocks"]):
         tb = t if i >= arch["gate_after"] else 0
         ci, co = int(arch["cin"][t, i]), int(arch["cout"][t, i])
-        x = F.relu(_bn(F.conv2d(x, t64(p[f"ds{i}.dw.w"][:ci]), stride=s, padding=1, groups=ci),
+        wd = p[f"ds{i}.dw.w"][:ci]
+        k = int(arch["ksize"][t, i]) if "ksize" in arch else 3
+        k0 = (wd.shape[-1] - k) // 2
+        wd = wd[:, :, k0:k0 + k, k0:k0 + k].copy()              # the route's centred block of the stored filter
+        x = F.relu(_bn(F.conv2d(x, t64(wd), stride=s, padding=(k - 1) // 2, groups=ci),
                        p[f"ds{i}.dw.bn"], tb, ci, eps))
         x = F.relu(_bn(F.conv2d(x, t64(p[f"ds{i}.pw.w"][:co, :ci])), p[f"ds{i}.pw.bn"], tb, co, eps))
     c = x.shape[1]
@@ -150,6 +154,25 @@ def test_mbnet_assembly_matches_library_layers(t):
     got, rt, _ = O.forward_mbnet(arch, p, img, route_override=t, store="f64")
     assert rt == t
     np.testing.assert_allclose(got, _ref_mbnet(arch, p, img, t), rtol=1e-9, atol=1e-9)
+
+
+@pytest.mark.parametrize("t", [0, 5, 11])
+def test_mbnet_pp_assembly_matches_library_layers(t):
+    arch = WL.mbnet_pp_arch(image=32, width_div=2)
+    assert arch["T"] == 12 and sorted(set(arch["ksize"][:, 7].tolist())) == [3, 5, 7] and set(arch["ksize"][:, 2].tolist()) == {5}
+    p = WL.mbnet_params(arch, 13)
+    assert p["ds1.dw.w"].shape[-1] == 5 and p["ds7.dw.w"].shape[-1] == 7
+    img = WL.images(14, 1, 32)[0]
+    got, rt, _ = O.forward_mbnet(arch, p, img, route_override=t, store="f64")
+    assert rt == t
+    np.testing.assert_allclose(got, _ref_mbnet(arch, p, img, t), rtol=1e-9, atol=1e-9)
+
+
+def test_mbnet_pp_channel_lists_are_the_papers():
+    # lower half of the DS-MBNet routing-space table: [288:640:32] and [800:1152:32], 12 paths (Section 5.2)
+    a = WL.mbnet_pp_arch()
+    assert a["cout"][:, 5].tolist() == list(range(288, 641, 32)) and a["cout"][:, 12].tolist() == list(range(800, 1153, 32))
+    assert a["T"] == 12 and [b[1] for b in a["blocks"][:5]] == [32, 48, 48, 96, 96] and a["stem_out"] == 16
 
 
 def test_mbnet_gate_picks_the_biased_route_and_bf16_storage_stays_close():

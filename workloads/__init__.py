@@ -8,6 +8,7 @@ distributions, layer lists and route tables.  None of the method's arithmetic
 from .nets import (  # noqa: F401
     BASE_SEED,
     mbnet_arch,
+    mbnet_pp_arch,
     mbnet_params,
     resnet_arch,
     resnet_params,

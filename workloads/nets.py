@@ -117,6 +117,34 @@ def mbnet_arch(image: int = 224, width_div: int = 1) -> dict:
     }
 
 
+def mbnet_pp_arch(image: int = 224, width_div: int = 1) -> dict:
+    """DS-MBNet++ (lower half of the DS-MBNet routing-space table): stem 16, depthwise-separable blocks
+    32 / 48, 48 / 96, 96 with 5x5 depthwise filters (fixed), then six blocks at [288:640:32] and two at
+    [800:1152:32] channels whose depthwise filters are stored 7x7 and used at kernel size 3, 5 or 7.
+    12 routes: route t has the t-th entry of both channel lists and kernel size 3 (t < 4), 5 (t < 8) or 7;
+    padding is (k - 1) / 2 throughout, so every route keeps the resolution.  ksize is [T, 13], kfull [13]."""
+    d = width_div
+    c1max, c2max = 640 // d, 1152 // d
+    blocks = [(16 // d, 32 // d, 1), (32 // d, 48 // d, 2), (48 // d, 48 // d, 1), (48 // d, 96 // d, 2),
+              (96 // d, 96 // d, 1), (96 // d, c1max, 2)] + [(c1max, c1max, 1)] * 5 + [(c1max, c2max, 2), (c2max, c2max, 1)]
+    T = 12
+    cin = np.zeros((T, 13), np.int32)
+    cout = np.zeros((T, 13), np.int32)
+    ksize = np.zeros((T, 13), np.int32)
+    kfull = [5] * 5 + [7] * 8
+    for t in range(T):
+        c1, c2 = (288 + 32 * t) // d, (800 + 32 * t) // d
+        for i, (ci, co, _s) in enumerate(blocks):
+            cin[t, i] = ci if i < 6 else (c1 if i < 12 else c2)
+            cout[t, i] = co if i < 5 else (c1 if i < 11 else c2)
+            ksize[t, i] = 5 if i < 5 else (3, 5, 7)[t // 4]
+    return {
+        "name": "mbnet", "image": image, "stem_out": 16 // d, "blocks": blocks,
+        "gate_after": 5, "gate_hidden": blocks[4][1] // 4, "T": T,
+        "cin": cin, "cout": cout, "kfull": kfull, "ksize": ksize, "num_classes": 1000, "bn_eps": 1e-5,
+    }
+
+
 def mbnet_params(arch: dict, seed: int) -> dict:
     d = Draw(seed)
     T = arch["T"]
@@ -126,7 +154,8 @@ def mbnet_params(arch: dict, seed: int) -> dict:
     p["stem.bn"] = bn_tables(d, 1, so)
     for i, (ci, co, _s) in enumerate(arch["blocks"]):
         Tb = 1 if i < arch["gate_after"] else T
-        p[f"ds{i}.dw.w"] = as_bf16_values(_kaiming(d, (ci, 1, 3, 3)))
+        kf = arch["kfull"][i] if "kfull" in arch else 3
+        p[f"ds{i}.dw.w"] = as_bf16_values(_kaiming(d, (ci, 1, kf, kf)))
         p[f"ds{i}.dw.bn"] = bn_tables(d, Tb, ci)
         p[f"ds{i}.pw.w"] = as_bf16_values(_kaiming(d, (co, ci, 1, 1)))
         p[f"ds{i}.pw.bn"] = bn_tables(d, Tb, co)
