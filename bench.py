@@ -33,6 +33,11 @@ def build_workload(name: str, B: int):
         params = WL.mbnet_params(arch, S + 3)
         lb = WL.seeded_logit_bias(S + 203, B, arch["T"])[None]
         label = "config3: DS-MBNet (MobileNetV1-shaped, 14 width routes), bf16"
+    elif name == "mbnet_pp":
+        arch = WL.mbnet_pp_arch()
+        params = WL.mbnet_params(arch, S + 8)
+        lb = WL.seeded_logit_bias(S + 208, B, arch["T"])[None]
+        label = "DS-MBNet++ (12 routes over channels [288:640:32] / [800:1152:32] and depthwise kernel size 3/5/7), bf16"
     elif name == "resnet":
         arch = WL.resnet_arch()
         params = WL.resnet_params(arch, S + 4)
@@ -56,7 +61,7 @@ def build_workload(name: str, B: int):
                  "8 nested routes), bf16")
     else:
         raise SystemExit(f"unknown workload {name}")
-    imgs = WL.images(S + 100 + {"mbnet": 3, "resnet": 4, "vit": 5, "vit_stem": 6, "vit_pp": 7}[name], B)
+    imgs = WL.images(S + 100 + {"mbnet": 3, "resnet": 4, "vit": 5, "vit_stem": 6, "vit_pp": 7, "mbnet_pp": 8}[name], B)
     return arch, params, imgs, lb.astype("float32"), label
 
 
@@ -71,7 +76,7 @@ def cpu_baseline(name, arch, params, imgs, lb, budget_s=15.0):
     t0 = time.perf_counter()
     n = 0
     while n < imgs.shape[0] and (time.perf_counter() - t0 < budget_s or n < 2):
-        if name == "mbnet":
+        if name in ("mbnet", "mbnet_pp"):
             O.forward_mbnet(arch, params, imgs[n], logit_bias=lb[0, n])
         elif name == "resnet":
             O.forward_resnet(arch, params, imgs[n], logit_bias=lb[:, n])
@@ -90,7 +95,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp"])
+    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp"])
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -122,7 +127,7 @@ def main():
         return
     B = args.batch
     arch, params, imgs, lb, label = build_workload(args.workload, B)
-    net = {"mbnet": ds.build_mbnet, "resnet": ds.build_resnet, "vit": ds.build_vit,
+    net = {"mbnet": ds.build_mbnet, "mbnet_pp": ds.build_mbnet, "resnet": ds.build_resnet, "vit": ds.build_vit,
            "vit_stem": ds.build_vit, "vit_pp": ds.build_vit}[args.workload](arch, params, dev)
     x = torch.from_numpy(imgs).to(dev).to(torch.bfloat16).contiguous()
     lbg = torch.from_numpy(lb).to(dev).contiguous()
@@ -162,7 +167,7 @@ def main():
     prof = ds.ds_profile_read() if sampled else {}
 
     rt = routes.cpu().numpy()
-    cost = {"mbnet": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost,
+    cost = {"mbnet": C.mbnet_cost, "mbnet_pp": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost,
             "vit_pp": C.vit_cost}[args.workload](arch, rt)
     roofline = None
     kernels = {}

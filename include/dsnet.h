@@ -205,9 +205,13 @@ int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D_e, const v
  * [n_gates, B]. */
 /* DS_ARCH_MBNET: MobileNetV1-shaped net, one gate after block `gate_after` (Section 5.2, DS-MBNet).
  *   ints:   image, stem_out, n_blocks, gate_after, gate_hidden, T, num_classes,
- *           n_blocks x (C_in, C_out, stride), cin[T][n_blocks], cout[T][n_blocks] (valid widths per route)
+ *           n_blocks x (C_in, C_out, stride), cin[T][n_blocks], cout[T][n_blocks] (valid widths per route),
+ *           optionally kfull[n_blocks], ksize[T][n_blocks] (DS-MBNet++, Eq. 11): block i stores a
+ *           kfull[i] x kfull[i] depthwise filter (odd, at most 7) and route t uses its centred
+ *           ksize[t][i] x ksize[t][i] block at padding (ksize - 1) / 2, so the resolution does not
+ *           depend on the route; blocks before the gate use row 0
  *   params: stem.w bf16 [3*3*3][stem_out] (tap-major, input channel, then filters), stem.scale, stem.shift,
- *           per block: dw.w bf16 [3][3][C_in], dw.scale, dw.shift fp32 [Tb][C_in], pw.w bf16 [C_out][C_in],
+ *           per block: dw.w bf16 [k][k][C_in] (k = 3, or kfull[i]), dw.scale, dw.shift fp32 [Tb][C_in], pw.w bf16 [C_out][C_in],
  *           pw.scale, pw.shift fp32 [Tb][C_out] (Tb = 1 before the gate, T after),
  *           gate.w1 [gate_hidden][C], gate.b1, gate.w2 [T][gate_hidden], gate.b2 (fp32),
  *           fc.w bf16 [num_classes][C_last], fc.b fp32. */

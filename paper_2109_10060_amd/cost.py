@@ -47,7 +47,8 @@ def mbnet_cost(arch, routes) -> Cost:
         rin = r
         r = _osz(r, 3, s, 1)
         ci, co = arch["cin"][routes, i].astype(np.float64), arch["cout"][routes, i].astype(np.float64)
-        c.add("dwconv", 2.0 * r * r * 9 * ci.sum(), 2.0 * (rin * rin + r * r) * ci.sum())
+        kk = arch["ksize"][routes, i].astype(np.float64) ** 2 if "ksize" in arch else 9.0
+        c.add("dwconv", 2.0 * r * r * (kk * ci).sum(), 2.0 * (rin * rin + r * r) * ci.sum())
         _gemm(c, "gemm", r * r, r * r, 1, ci, co)
         if i == arch["gate_after"] - 1:
             c.add("gate", 2.0 * B * (r * r * co[0]), 2.0 * B * r * r * co[0])

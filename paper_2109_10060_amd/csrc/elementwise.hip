@@ -194,6 +194,8 @@ __global__ __launch_bounds__(256, 3) void dwconv4_kernel(ActView x, ActView y, c
 // workgroup and picks a fully unrolled row routine: the N input pixels and N filter taps of a row are
 // all requested (branch-free buffer loads, zeros outside the image) before the first multiply.
 // A lane owns 8 channels of one output pixel; the output is packed [Ho_t][Wo_t][width] per slot.
+constexpr int DWS_PX = 4;   // output pixels per lane on undilated routes
+
 template <int N>
 __device__ __forceinline__ void dws_rows(float (&acc)[8], const __amdgpu_buffer_rsrc_t rsrc, const bf16_t* w, int KS, int C,
                                          int k0, int l, int iy0, int ix0, int H, int W, int xld, int ch) {
@@ -225,6 +227,52 @@ __device__ __forceinline__ void dws_rows(float (&acc)[8], const __amdgpu_buffer_
     }
 }
 
+// Undilated routes: PX neighbouring output pixels of a row per lane, so that the (PX - 1) STRIDE + N input
+// columns of a filter row are loaded once and every tap's weight pair masks are made once for all PX outputs.
+template <int N, int STRIDE, int PX>
+__device__ __forceinline__ void dws_rows_px(float (&acc)[PX][8], const __amdgpu_buffer_rsrc_t rsrc, const bf16_t* w, int KS,
+                                            int C, int k0, int iy0, int ix0, int H, int W, int xld, int ch) {
+    constexpr uint32_t OOB = 0x80000000u;
+    constexpr int NCOL = (PX - 1) * STRIDE + N;
+#pragma unroll 1
+    for (int i = 0; i < N; ++i) {
+        const int iy = iy0 + i;
+        const bool rok = iy >= 0 && iy < H;
+        uint4 xin[NCOL], win[N];
+#pragma unroll
+        for (int col = 0; col < NCOL; ++col) {
+            const int ix = ix0 + col;
+            const uint32_t off = (rok && ix >= 0 && ix < W) ? (uint32_t)(((iy * W + ix) * xld + ch) * 2) : OOB;
+            const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+            xin[col] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) win[j] = *(const uint4*)(w + ((k0 + i) * KS + k0 + j) * C + ch);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const uint32_t wq[4] = {win[j].x, win[j].y, win[j].z, win[j].w};
+            bf16x2_t wlo[4], whi[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                wlo[q] = __builtin_bit_cast(bf16x2_t, wq[q] & 0x0000ffffu);
+                whi[q] = __builtin_bit_cast(bf16x2_t, wq[q] & 0xffff0000u);
+            }
+#pragma unroll
+            for (int p = 0; p < PX; ++p) {
+                const uint4 xv = xin[p * STRIDE + j];
+                const uint32_t xq[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bf16x2_t xx = __builtin_bit_cast(bf16x2_t, xq[q]);
+                    acc[p][2 * q] = __builtin_amdgcn_fdot2_f32_bf16(xx, wlo[q], acc[p][2 * q], false);
+                    acc[p][2 * q + 1] = __builtin_amdgcn_fdot2_f32_bf16(xx, whi[q], acc[p][2 * q + 1], false);
+                }
+            }
+        }
+    }
+}
+
+template <int STRIDE, int PX>
 __global__ __launch_bounds__(256) void dwconv_spatial_kernel(ActView x, ActView y, const bf16_t* w, int KS,
                                                              const float* scale, const float* shift, int tab_ld,
                                                              const int32_t* slot_group, const GroupTable gt,
@@ -237,36 +285,60 @@ __global__ __launch_bounds__(256) void dwconv_spatial_kernel(ActView x, ActView 
     const int n = st.n[g], l = st.l[g], pad = st.pad[g], k0 = st.k0[g];
     const int span = (n - 1) * l + 1;
     const int Ho = (H + 2 * pad - span) / stride + 1, Wo = (W + 2 * pad - span) / stride + 1;
+    // STRIDE == 0: any stride, one pixel per lane.  Otherwise undilated routes take PX pixels per lane.
+    const bool wide = STRIDE > 0 && l == 1;                     // uniform over the workgroup
+    const int px = wide ? PX : 1;
+    const int xgroups = (Wo + px - 1) / px;
     const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (Ho <= 0 || Wo <= 0 || idx >= Ho * Wo * chunks) return;
-    const int pix = idx / chunks, ch = (idx - pix * chunks) * 8;
-    const int oy = pix / Wo, ox = pix - oy * Wo;
+    if (Ho <= 0 || Wo <= 0 || idx >= Ho * xgroups * chunks) return;
+    const int pg = idx / chunks, ch = (idx - pg * chunks) * 8;
+    const int oy = pg / xgroups, ox0 = (pg - oy * xgroups) * px;
     const int xs = x.index ? x.index[slot] : slot;
     const int ys = y.index ? y.index[slot] : slot;
     const int xld = x.ld > 0 ? x.ld : c, yld = y.ld > 0 ? y.ld : c;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)((const bf16_t*)x.p + (int64_t)xs * x.sample_stride), 0, 0x7fffffff, 0x00020000);
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int iy0 = oy * stride - pad, ix0 = ox * stride - pad;
-    switch (n) {   // uniform over the workgroup
-        case 1: dws_rows<1>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
-        case 2: dws_rows<2>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
-        case 3: dws_rows<3>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
-        case 4: dws_rows<4>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
-        case 5: dws_rows<5>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
-        case 6: dws_rows<6>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
-        default: dws_rows<7>(acc, rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+    float acc[PX][8];
+#pragma unroll
+    for (int p = 0; p < PX; ++p)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[p][i] = 0.f;
+    const int iy0 = oy * stride - pad, ix0 = ox0 * stride - pad;
+    if (wide) {
+        if constexpr (STRIDE > 0) {
+            switch (n) {
+                case 1: dws_rows_px<1, STRIDE, PX>(acc, rsrc, w, KS, C, k0, iy0, ix0, H, W, xld, ch); break;
+                case 3: dws_rows_px<3, STRIDE, PX>(acc, rsrc, w, KS, C, k0, iy0, ix0, H, W, xld, ch); break;
+                case 5: dws_rows_px<5, STRIDE, PX>(acc, rsrc, w, KS, C, k0, iy0, ix0, H, W, xld, ch); break;
+                default: dws_rows_px<7, STRIDE, PX>(acc, rsrc, w, KS, C, k0, iy0, ix0, H, W, xld, ch); break;
+            }
+        }
+    } else {
+        switch (n) {
+            case 1: dws_rows<1>(acc[0], rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+            case 2: dws_rows<2>(acc[0], rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+            case 3: dws_rows<3>(acc[0], rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+            case 4: dws_rows<4>(acc[0], rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+            case 5: dws_rows<5>(acc[0], rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+            case 6: dws_rows<6>(acc[0], rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+            default: dws_rows<7>(acc[0], rsrc, w, KS, C, k0, l, iy0, ix0, H, W, xld, ch); break;
+        }
     }
     const int64_t ti = (int64_t)gt.row[g] * tab_ld + ch;
     float sc[8], sh[8];
     loadf8(scale + ti, sc);
     loadf8(shift + ti, sh);
+    bf16_t* yp = (bf16_t*)y.p + (int64_t)ys * y.sample_stride + ((int64_t)oy * Wo + ox0) * yld + ch;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        acc[i] = acc[i] * sc[i] + sh[i];
-        if (act == DS_ACT_RELU) acc[i] = fmaxf(acc[i], 0.f);
+    for (int p = 0; p < PX; ++p) {
+        if (p >= px || ox0 + p >= Wo) break;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            acc[p][i] = acc[p][i] * sc[i] + sh[i];
+            if (act == DS_ACT_RELU) acc[p][i] = fmaxf(acc[p][i], 0.f);
+        }
+        *(uint4*)(yp + (int64_t)p * yld) = pack8(acc[p]);
     }
-    *(uint4*)((bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)pix * yld + ch) = pack8(acc);
 }
 
 // ---- channel re-weighting by the attention head of the gate (Section 3.5, Eq. 23) ---------
@@ -643,14 +715,22 @@ int32_t ds_launch_dwconv_spatial(ActView x, ActView y, const bf16_t* w, int32_t 
         const int span = (st.n[t] - 1) * st.l[t] + 1;
         const int Ho = (H + 2 * st.pad[t] - span) / stride + 1, Wo = (W + 2 * st.pad[t] - span) / stride + 1;
         if (Ho <= 0 || Wo <= 0) continue;
-        const int64_t n = (int64_t)Ho * Wo * (gt.k_in[t] / 8);
+        const int px = (stride <= 2 && st.l[t] == 1) ? DWS_PX : 1;   // pixels per lane, as the kernel chooses them
+        const int64_t n = (int64_t)Ho * ((Wo + px - 1) / px) * (gt.k_in[t] / 8);
         nmax = n > nmax ? n : nmax;
     }
     if (nmax <= 0) return DS_OK;
     dim3 grid((unsigned)((nmax + 255) / 256), (unsigned)B);
     ProfScope prof(DS_K_DWCONV, s);
-    hipLaunchKernelGGL(dwconv_spatial_kernel, grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld, slot_group, gt, st, C, H,
-                       W, stride, act);
+    if (stride == 1)
+        hipLaunchKernelGGL((dwconv_spatial_kernel<1, DWS_PX>), grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld,
+                           slot_group, gt, st, C, H, W, stride, act);
+    else if (stride == 2)
+        hipLaunchKernelGGL((dwconv_spatial_kernel<2, DWS_PX>), grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld,
+                           slot_group, gt, st, C, H, W, stride, act);
+    else
+        hipLaunchKernelGGL((dwconv_spatial_kernel<0, 1>), grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld,
+                           slot_group, gt, st, C, H, W, stride, act);
     DS_CHECK_LAUNCH("spatial depthwise conv");
     return DS_OK;
 }

@@ -83,14 +83,16 @@ int32_t conv_gemm(const bf16_t* A, const int32_t* a_index, int64_t a_sstride, in
 // DS-MBNet
 //  ints:   image, stem_out, n_blocks, gate_after, gate_hidden, T, num_classes,
 //          n_blocks x (C_in, C_out, stride), cin[T][n_blocks], cout[T][n_blocks]
+//          [, kfull[n_blocks], ksize[T][n_blocks]]   (DS-MBNet++: stored depthwise filter size, route's kernel size)
 //  params: stem.w [27][stem_out] bf16, stem.scale, stem.shift,
-//          per block: dw.w [3][3][C_in] bf16, dw.scale, dw.shift [Tb][C_in], pw.w [C_out][C_in] bf16,
+//          per block: dw.w [k][k][C_in] bf16 (k = 3, or kfull of the block), dw.scale, dw.shift [Tb][C_in], pw.w [C_out][C_in] bf16,
 //                     pw.scale, pw.shift [Tb][C_out]   (Tb = 1 before the gate, T after),
 //          gate.w1, gate.b1, gate.w2, gate.b2, fc.w [classes][C_last] bf16, fc.b
 // =====================================================================================
 struct MbDesc {
     int image, stem_out, nb, gate_after, gate_hidden, T, classes;
     const int32_t *blk, *cin, *cout;
+    const int32_t *kfull, *ksize;   // null unless the depthwise filters are spatially sliced
 };
 
 bool parse_mb(const ds_net* net, MbDesc* d) {
@@ -99,11 +101,17 @@ bool parse_mb(const ds_net* net, MbDesc* d) {
     d->image = v[0]; d->stem_out = v[1]; d->nb = v[2]; d->gate_after = v[3]; d->gate_hidden = v[4]; d->T = v[5];
     d->classes = v[6];
     if (d->nb < 1 || d->nb > 64 || d->T < 1 || d->T > DS_MAX_GROUPS) return false;
-    if (net->n_ints != 7 + 3 * d->nb + 2 * d->T * d->nb) return false;
+    const int plain = 7 + 3 * d->nb + 2 * d->T * d->nb;
+    if (net->n_ints != plain && net->n_ints != plain + d->nb + d->T * d->nb) return false;
     if (net->n_params != 3 + 6 * d->nb + 6) return false;
     d->blk = v + 7;
     d->cin = d->blk + 3 * d->nb;
     d->cout = d->cin + d->T * d->nb;
+    d->kfull = d->ksize = nullptr;
+    if (net->n_ints != plain) {
+        d->kfull = d->cout + d->T * d->nb;
+        d->ksize = d->kfull + d->nb;
+    }
     return d->gate_after >= 1 && d->gate_after < d->nb;
 }
 
@@ -210,8 +218,20 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
         const bool first = (i == d.gate_after);
         ActView xv = {cur, first ? p.perm : nullptr, (int64_t)rin * rin * ci, (!phase || first) ? ci : 0};
         ActView yv = {oth, nullptr, (int64_t)r * r * ci, phase ? 0 : ci};
-        RC(ds_launch_dwconv(xv, yv, (const bf16_t*)Q[0], (const float*)Q[1], (const float*)Q[2], ci,
-                            phase ? p.slot_group : nullptr, gdw, B, ci, rin, rin, st, DS_ACT_RELU, s));
+        if (d.kfull) {
+            // the route's centred block of the stored filter at the padding that keeps the resolution
+            SpatialTable sp;
+            memset(&sp, 0, sizeof(sp));
+            for (int t = 0; t < (phase ? d.T : 1); ++t) {
+                const int k = d.ksize[t * d.nb + i];
+                sp.k0[t] = (d.kfull[i] - k) / 2; sp.n[t] = k; sp.l[t] = 1; sp.pad[t] = (k - 1) / 2;
+            }
+            RC(ds_launch_dwconv_spatial(xv, yv, (const bf16_t*)Q[0], d.kfull[i], (const float*)Q[1], (const float*)Q[2],
+                                        ci, phase ? p.slot_group : nullptr, gdw, sp, B, ci, rin, rin, st, DS_ACT_RELU, s));
+        } else {
+            RC(ds_launch_dwconv(xv, yv, (const bf16_t*)Q[0], (const float*)Q[1], (const float*)Q[2], ci,
+                                phase ? p.slot_group : nullptr, gdw, B, ci, rin, rin, st, DS_ACT_RELU, s));
+        }
         // pointwise
         RC(conv_gemm(oth, nullptr, (int64_t)r * r * ci, phase ? 0 : ci, (const bf16_t*)Q[3], ci, 1, 1, 0, r, r,
                      (const float*)Q[4], (const float*)Q[5], co, nullptr, cur, (int64_t)r * r * co, phase ? 0 : co,
@@ -720,6 +740,15 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
         if (d.stem_out % 8) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
         for (int i = 0; i < d.nb * (3 + 2 * d.T); ++i)
             if ((i >= 3 * d.nb || i % 3 != 2) && (d.blk[i] % 8)) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
+        if (d.kfull)
+            for (int i = 0; i < d.nb; ++i) {
+                const int kf = d.kfull[i];
+                if (kf < 1 || kf > 7 || !(kf & 1)) DS_FAIL(DS_EUNSUPPORTED, "%s: stored depthwise filter size %d (odd, at most 7)", who, kf);
+                for (int t = 0; t < d.T; ++t) {
+                    const int k = d.ksize[t * d.nb + i];
+                    if (k < 1 || k > kf || !(k & 1)) DS_FAIL(DS_EINVAL, "%s: kernel size %d is no centred block of %d", who, k, kf);
+                }
+            }
         plan_mb(d, B, bp, &p);
         return forward_mb(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);
     }

@@ -68,6 +68,8 @@ def build_mbnet(arch: dict, p: dict, device="cuda:0") -> Net:
     for ci, co, s in arch["blocks"]:
         ints += [ci, co, s]
     ints += arch["cin"].reshape(-1).tolist() + arch["cout"].reshape(-1).tolist()
+    if "ksize" in arch:
+        ints += [int(k) for k in arch["kfull"]] + arch["ksize"].reshape(-1).tolist()
     t = [_stem(p["stem.w"], device), *_fold(p["stem.bn"], eps, device)]
     for i in range(nb):
         t.append(_dev(np.transpose(p[f"ds{i}.dw.w"][:, 0], (1, 2, 0)), bf, device))

@@ -79,6 +79,28 @@ def test_mbnet_config3_batch256(gpu_lib):
     assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
 
 
+def test_mbnet_pp_small_all_samples(gpu_lib):
+    # DS-MBNet++: 5x5 depthwise filters before the gate, stored 7x7 filters used at kernel size 3, 5 or 7 after it
+    arch = WL.mbnet_pp_arch(image=64, width_div=2)
+    params = WL.mbnet_params(arch, S + 33)
+    B = 29
+    imgs = WL.images(S + 34, B, 64)
+    lb = WL.seeded_logit_bias(S + 35, B, arch["T"])
+    net, xg, lbg, logits, routes = _mb_case(gpu_lib, arch, params, imgs, lb, range(B))
+    assert len(set(routes.cpu().numpy()[0].tolist())) == arch["T"]
+
+
+def test_mbnet_pp_batch256(gpu_lib):
+    arch = WL.mbnet_pp_arch()
+    params = WL.mbnet_params(arch, S + 36)
+    B = 256
+    imgs = WL.images(S + 136, B)
+    lb = WL.seeded_logit_bias(S + 236, B, arch["T"])
+    target = np.argmax(lb, axis=1)
+    check = [int(np.where(target == t)[0][0]) for t in (0, 5, 11)]
+    _mb_case(gpu_lib, arch, params, imgs, lb, check)
+
+
 # ------------------------------------------------------------------ DS-ResNet
 def _rn_case(gpu_lib, arch, params, imgs, lb, check):
     net = gpu_lib.build_resnet(arch, params, DEV)
