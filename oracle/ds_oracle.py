@@ -250,6 +250,30 @@ def re_sbn(x, bn, t, eps):
     return g * ((x - mu) / sd) + b
 
 
+def re_sbn_recalibrate(samples, routes, T, C):
+    """Re-calibration of the split batch-norm statistics (the paragraph above Eq. 14): for every route t,
+    mu_t and sigma_t^2 of each valid channel are re-estimated over a calibration set, here as the mean and
+    the biased variance over all pixels of all samples that take route t (the population statistics; for
+    batches of equal size the mean is the average of the batch means, and the variance is the average of
+    the batch variances plus the variance of the batch means).
+    samples[b]: [c_b, H, W] pre-normalisation features with the valid channels of its route; routes[b] in
+    [0, T).  Returns (mean [T, C], var [T, C], count [T] pixels per route); entries of channels a route
+    does not reach, and of routes without samples, stay at mean 0, variance 1."""
+    mean = np.zeros((T, C), F64)
+    var = np.ones((T, C), F64)
+    count = np.zeros(T, np.int64)
+    for t in range(T):
+        xs = [np.asarray(x, F64) for x, r in zip(samples, routes) if int(r) == t]
+        if not xs:
+            continue
+        c = xs[0].shape[0]
+        flat = np.concatenate([x.reshape(c, -1) for x in xs], axis=1)        # [c, pixels of all samples]
+        count[t] = flat.shape[1]
+        mean[t, :c] = flat.mean(axis=1)
+        var[t, :c] = ((flat - mean[t, :c, None]) ** 2).mean(axis=1)
+    return mean, var, count
+
+
 def relu(x):
     return np.maximum(x, 0.0)
 

@@ -424,3 +424,39 @@ def test_attention_head_slice_equals_masked_full_width():
     # and the hidden vector is the one the routing head uses
     np.testing.assert_allclose(O.gate_hidden(O.gate_encoder(x[:c]), w1, b1),
                                np.maximum(w1[:, :c] @ x[:c].mean(axis=(1, 2)) + b1, 0.0), rtol=1e-12)
+
+
+# ------------------------------------------------------------------ Re-SBN re-calibration
+def test_re_sbn_recalibration_is_the_population_statistics_per_route():
+    rng = np.random.default_rng(17)
+    T, C, H, W = 3, 6, 5, 4
+    widths = [2, 4, 6]
+    routes = [0, 2, 1, 2, 2, 0, 1, 1]                 # route 1 and 2 have 3 samples, route 0 two
+    samples = [rng.standard_normal((widths[r], H, W)) * (1 + r) + 0.5 * r for r in routes]
+    mean, var, count = O.re_sbn_recalibrate(samples, routes, T, C)
+    assert count.tolist() == [2 * H * W, 3 * H * W, 3 * H * W]
+    for t in range(T):
+        xs = np.stack([s for s, r in zip(samples, routes) if r == t])          # [n, c, H, W]
+        c = widths[t]
+        # library: training-mode batch-norm with momentum 1 leaves the batch statistics in the running buffers
+        rm, rv = torch.zeros(c, dtype=torch.float64), torch.ones(c, dtype=torch.float64)
+        F.batch_norm(t64(xs), rm, rv, None, None, True, 1.0, 1e-5)
+        n = xs.shape[0] * H * W
+        np.testing.assert_allclose(mean[t, :c], rm.numpy(), rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(var[t, :c], rv.numpy() * (n - 1) / n, rtol=1e-12, atol=1e-12)   # running_var is unbiased
+        # cumulative average over equal batches: mean of batch means; total variance = mean of batch variances
+        # + variance of the batch means
+        bm = xs.mean(axis=(2, 3)).T                                             # [c, n] per-sample means
+        bv = xs.var(axis=(2, 3)).T
+        np.testing.assert_allclose(mean[t, :c], bm.mean(axis=1), rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(var[t, :c], bv.mean(axis=1) + bm.var(axis=1), rtol=1e-12, atol=1e-12)
+        # channels beyond the route's width keep the initial statistics
+        assert np.all(mean[t, c:] == 0) and np.all(var[t, c:] == 1)
+    # normalising the calibration data of a route with its new statistics gives mean 0, variance 1 (Eq. 14 with gamma 1, beta 0)
+    bn = {"gamma": np.ones(C), "beta": np.zeros(C), "mean": mean, "var": var}
+    z = np.concatenate([O.re_sbn(s, bn, 2, 0.0).reshape(6, -1) for s, r in zip(samples, routes) if r == 2], axis=1)
+    np.testing.assert_allclose(z.mean(axis=1), 0, atol=1e-12)
+    np.testing.assert_allclose(z.var(axis=1), 1, rtol=1e-12)
+    # a route without samples stays at its initial statistics
+    m2, v2, c2 = O.re_sbn_recalibrate(samples[:1], routes[:1], T, C)
+    assert c2.tolist() == [H * W, 0, 0] and np.all(m2[1:] == 0) and np.all(v2[1:] == 1)
