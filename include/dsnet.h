@@ -78,6 +78,26 @@ int32_t ds_version(void);
 int32_t ds_bn_fold(const float* gamma, const float* beta, const float* mean, const float* var,
                    float eps, int32_t T, int32_t C, float* scale, float* shift, void* stream);
 
+/* Re-calibration of the split batch-norm statistics (Section 3.3, the paragraph above Eq. 14:
+ * mu_t and sigma_t of every route are re-estimated over a calibration set after training).
+ * ds_bn_stats_accumulate streams one batch of pre-normalisation features: for each group t it
+ * adds, per valid channel c < k_in[t], the sum and the sum of squares over all pixels of the
+ * group's samples to sum[t, c] / sumsq[t, c] and the number of those pixels to count[t].
+ * x: device bf16 [B, HW, C] (channels-last, original sample order; group t's samples hold
+ * k_in[t] valid channels at channel stride C); sum, sumsq: device fp64 [T, C]; count: device
+ * int64 [T]; the caller zeroes all three before the first batch and keeps them across calls.
+ * The arithmetic is fp64 in a fixed order (no atomics), so a calibration pass is reproducible.
+ * ds_bn_stats_finish turns the totals into mean[t, c] = S / N and the biased variance
+ * var[t, c] = Q / N - mean^2 (device fp32 [T, C], ready for ds_bn_fold); width: host int32 [T],
+ * the valid channels of each route (NULL = C); a route without samples and the channels at or
+ * beyond a route's width get mean 0, variance 1.  T <= DS_MAX_GROUPS. */
+size_t ds_bn_stats_workspace(int32_t B, int32_t HW, int32_t C);
+int32_t ds_bn_stats_accumulate(const void* x, int32_t B, int32_t HW, int32_t C, const ds_groups* g,
+                               double* sum, double* sumsq, int64_t* count, void* ws, size_t ws_bytes,
+                               void* stream);
+int32_t ds_bn_stats_finish(const double* sum, const double* sumsq, const int64_t* count, int32_t T,
+                           int32_t C, const int32_t* width, float* mean, float* var, void* stream);
+
 /* Routing agent (Section 3.5).  Encoder: mean over H*W of each valid channel
  * (Eq. 21).  Head: logits = W2 . relu(W1[:, :c_in[b]] . pooled + b1) + b2
  * (+ logit_bias[b]); route = argmax (Eq. 22 at inference; ties -> lowest index, NaN

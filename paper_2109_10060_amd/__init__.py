@@ -29,7 +29,7 @@ DS_MAX_GROUPS = 64
 DS_ARCH_MBNET, DS_ARCH_RESNET, DS_ARCH_VIT, DS_ARCH_VIT_STEM = 1, 2, 3, 4
 
 EXPORTS = [
-    "ds_last_error", "ds_version", "ds_bn_fold", "ds_gate_workspace", "ds_gate", "ds_gate_double_workspace",
+    "ds_last_error", "ds_version", "ds_bn_fold", "ds_bn_stats_workspace", "ds_bn_stats_accumulate", "ds_bn_stats_finish", "ds_gate_workspace", "ds_gate", "ds_gate_double_workspace",
     "ds_gate_double", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
     "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_dwconv_spatial", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
@@ -74,7 +74,8 @@ def load(path: Optional[str] = None):
     lib = ctypes.CDLL(path)
     lib.ds_last_error.restype = ctypes.c_char_p
     for name in ("ds_gate_workspace", "ds_sliced_linear_workspace", "ds_sliced_conv_workspace",
-                 "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace", "ds_gate_double_workspace"):
+                 "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace", "ds_gate_double_workspace",
+                 "ds_bn_stats_workspace"):
         getattr(lib, name).restype = ctypes.c_size_t
     _lib = lib
     return lib
@@ -126,6 +127,27 @@ def ds_bn_fold(gamma, beta, mean, var, eps: float):
     _chk(load().ds_bn_fold(_ptr(gamma, torch.float32), _ptr(beta, torch.float32), _ptr(mean, torch.float32),
                            _ptr(var, torch.float32), ctypes.c_float(eps), T, C, _ptr(scale), _ptr(shift), _stream()))
     return scale, shift
+
+
+def ds_bn_stats_accumulate(x, groups: ds_groups, sum_, sumsq, count):
+    """x: [B, HW, C] bf16; sum_, sumsq: [T, C] fp64; count: [T] int64 (all device, updated in place)."""
+    lib = load()
+    B, HW, C = x.shape
+    ws = _ws(lib.ds_bn_stats_workspace(B, HW, C), x)
+    _chk(lib.ds_bn_stats_accumulate(_ptr(x, torch.bfloat16), B, HW, C, ctypes.byref(groups), _ptr(sum_, torch.float64),
+                                    _ptr(sumsq, torch.float64), _ptr(count, torch.int64), _ptr(ws),
+                                    ctypes.c_size_t(ws.numel()), _stream()))
+
+
+def ds_bn_stats_finish(sum_, sumsq, count, width: Optional[Sequence[int]] = None):
+    """Returns (mean, var) fp32 [T, C]."""
+    T, C = sum_.shape
+    mean = torch.empty((T, C), dtype=torch.float32, device=sum_.device)
+    var = torch.empty_like(mean)
+    w = (ctypes.c_int32 * T)(*[int(v) for v in width]) if width is not None else None
+    _chk(load().ds_bn_stats_finish(_ptr(sum_, torch.float64), _ptr(sumsq, torch.float64), _ptr(count, torch.int64), T, C, w,
+                                   _ptr(mean), _ptr(var), _stream()))
+    return mean, var
 
 
 def ds_gate(x, layout, w1, b1, w2, b2, T: int, logit_bias=None, c_in=None, B: Optional[int] = None):

@@ -105,7 +105,6 @@ __global__ __launch_bounds__(256, 3) void dwconv4_kernel(ActView x, ActView y, c
     const int xs = x.index ? x.index[slot] : slot;
     const int ys = y.index ? y.index[slot] : slot;
     const int xld = x.ld > 0 ? x.ld : c, yld = y.ld > 0 ? y.ld : c;
-    const bf16_t* xp = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride + ch;
     float acc[PX][8];
 #pragma unroll
     for (int p = 0; p < PX; ++p)

@@ -206,6 +206,115 @@ __global__ void bn_fold_kernel(const float* gamma, const float* beta, const floa
     shift[i] = beta[c] - mean[i] * s;
 }
 
+// ---- Re-SBN re-calibration (the paragraph above Eq. 14): streaming per-route channel statistics -------
+// Pass 1, grid (slots, splits): sum and sum of squares of every valid channel over the slot's share of the
+// pixels, in fp64, lanes laid out as in pool_nhwc_kernel.  Deterministic: fixed row order per lane, fixed
+// order in the LDS reduction.
+__global__ __launch_bounds__(256) void bn_partial_kernel(const bf16_t* x, const int32_t* index, int64_t sample_stride,
+                                                         int ld, const int32_t* slot_group, const GroupTable gt, int HW,
+                                                         int C, int splits, int lcl, double* psum, double* psq) {
+    __shared__ double red[256 * 9];
+    const int slot = blockIdx.x, sp = blockIdx.y;
+    const int c = gt.k_in[slot_group[slot]];
+    const int sample = index ? index[slot] : slot;
+    const bf16_t* xp = x + (int64_t)sample * sample_stride;
+    const int CL = 1 << lcl, R = 256 >> lcl, red_ld = CL * 8 + 1;
+    const int lane_c = threadIdx.x & (CL - 1), lane_r = threadIdx.x >> lcl;
+    const int per = (HW + splits - 1) / splits;
+    const int r0 = sp * per, r1 = min(HW, r0 + per);
+    for (int c0 = 0; c0 < c; c0 += CL * 8) {
+        const int ch = c0 + lane_c * 8;
+        double s[8] = {0, 0, 0, 0, 0, 0, 0, 0}, q[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (ch < c) {
+            // four rows in flight per lane; their sums are taken in fp32 (a bf16 square is exact there, the
+            // additions round at 2^-24) and go into the fp64 totals once per four rows
+            int r = r0 + lane_r;
+            for (; r + 3 * R < r1; r += 4 * R) {
+                float v[4][8];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) load8<bf16_t>(xp + (int64_t)(r + R * k) * ld + ch, v[k]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float s4 = (v[0][i] + v[1][i]) + (v[2][i] + v[3][i]);
+                    const float q4 = fmaf(v[0][i], v[0][i], v[1][i] * v[1][i]) + fmaf(v[2][i], v[2][i], v[3][i] * v[3][i]);
+                    s[i] += (double)s4;
+                    q[i] += (double)q4;
+                }
+            }
+            for (; r < r1; r += R) {
+                float v[8];
+                load8<bf16_t>(xp + (int64_t)r * ld + ch, v);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    s[i] += (double)v[i];
+                    q[i] += (double)(v[i] * v[i]);
+                }
+            }
+        }
+        const int cc = c0 + threadIdx.x;
+        const int64_t o = ((int64_t)slot * splits + sp) * C + cc;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) red[lane_r * red_ld + lane_c * 8 + i] = pass ? q[i] : s[i];
+            __syncthreads();
+            if (threadIdx.x < CL * 8 && cc < c) {
+                double t = 0.0;
+                for (int r = 0; r < R; ++r) t += red[r * red_ld + threadIdx.x];
+                (pass ? psq : psum)[o] = t;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Pass 2, grid (T, ceil(C / 16)), block 256 = 16 channels x 16 slot lanes: a slot lane adds the partial sums of
+// every 16th slot of the route (in slot, then split order), the 16 lane totals are added in lane order, and the
+// result goes onto the running totals.  Fixed order throughout, so the totals are reproducible.
+__global__ __launch_bounds__(256) void bn_combine_kernel(const int32_t* offsets, const GroupTable gt, int HW, int C,
+                                                         int splits, const double* psum, const double* psq,
+                                                         double* sum, double* sumsq, long long* count) {
+    __shared__ double rs[16][17], rq[16][17];
+    const int t = blockIdx.x, cl = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int c = blockIdx.y * 16 + cl;
+    const int j0 = offsets[t], j1 = offsets[t + 1];
+    if (blockIdx.y == 0 && threadIdx.x == 0) count[t] += (long long)(j1 - j0) * HW;
+    double s = 0.0, q = 0.0;
+    if (c < gt.k_in[t])
+        for (int j = j0 + sl; j < j1; j += 16)
+            for (int sp = 0; sp < splits; ++sp) {
+                const int64_t o = ((int64_t)j * splits + sp) * C + c;
+                s += psum[o];
+                q += psq[o];
+            }
+    rs[sl][cl] = s;
+    rq[sl][cl] = q;
+    __syncthreads();
+    if (sl == 0 && c < gt.k_in[t]) {
+        double ts = 0.0, tq = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            ts += rs[k][cl];
+            tq += rq[k][cl];
+        }
+        sum[(int64_t)t * C + c] += ts;
+        sumsq[(int64_t)t * C + c] += tq;
+    }
+}
+
+// mean = S / N, variance = Q / N - mean^2 (biased); a route without samples keeps mean 0, variance 1
+__global__ void bn_finish_kernel(const double* sum, const double* sumsq, const long long* count, const GroupTable gt,
+                                 int T, int C, float* mean, float* var) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T * C) return;
+    const long long n = count[i / C];
+    if (n <= 0 || i % C >= gt.k_in[i / C]) { mean[i] = 0.f; var[i] = 1.f; return; }
+    const double m = sum[i] / (double)n;
+    const double v = sumsq[i] / (double)n - m * m;
+    mean[i] = (float)m;
+    var[i] = (float)(v > 0.0 ? v : 0.0);
+}
+
 }  // namespace
 
 size_t ds_gate_partial_bytes(int32_t B, int32_t C) { return (size_t)B * C * (POOL_SPLIT_MAX + 1) * sizeof(float); }
@@ -278,6 +387,66 @@ extern "C" int32_t ds_bn_fold(const float* gamma, const float* beta, const float
     hipLaunchKernelGGL(bn_fold_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, gamma, beta, mean,
                        var, eps, T, C, scale, shift);
     DS_CHECK_LAUNCH("bn fold");
+    return DS_OK;
+}
+
+namespace {
+int bn_stats_splits(int HW) { return HW >= 2048 ? 8 : (HW >= 512 ? 4 : (HW >= 128 ? 2 : 1)); }
+}  // namespace
+
+extern "C" size_t ds_bn_stats_workspace(int32_t B, int32_t HW, int32_t C) {
+    if (B <= 0 || HW <= 0 || C <= 0) return 0;
+    return ds_align_up((size_t)B * 4 + 4, 256) + 2 * ds_align_up((size_t)B * bn_stats_splits(HW) * C * sizeof(double), 256);
+}
+
+extern "C" int32_t ds_bn_stats_accumulate(const void* x, int32_t B, int32_t HW, int32_t C, const ds_groups* g, double* sum,
+                                          double* sumsq, int64_t* count, void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "ds_bn_stats_accumulate";
+    if (B < 0 || HW < 1 || C < 1) DS_FAIL(DS_EINVAL, "%s: bad size", who);
+    if (!g || g->T < 1 || g->T > DS_MAX_GROUPS || !g->offsets) DS_FAIL(DS_EINVAL, "%s: bad groups", who);
+    GroupTable gt = {};
+    gt.T = g->T;
+    for (int t = 0; t < g->T; ++t) {
+        if (g->k_in[t] < 0 || g->k_in[t] > C || (g->k_in[t] % 8)) DS_FAIL(DS_EINVAL, "%s: group %d width %d (multiple of 8, at most %d)", who, t, g->k_in[t], C);
+        gt.k_in[t] = gt.k_out[t] = g->k_in[t];
+    }
+    if (B == 0) return DS_OK;
+    if (!x || !sum || !sumsq || !count) DS_FAIL(DS_EINVAL, "%s: null pointer", who);
+    if ((C % 8) || !ds_aligned16(x)) DS_FAIL(DS_EALIGN, "%s: needs C %% 8 == 0 and a 16-byte aligned x", who);
+    if (!ws || ws_bytes < ds_bn_stats_workspace(B, HW, C)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes", who, ds_bn_stats_workspace(B, HW, C));
+    hipStream_t s = (hipStream_t)stream;
+    const int splits = bn_stats_splits(HW);
+    int32_t* slot_group = (int32_t*)ws;
+    double* psum = (double*)((char*)ws + ds_align_up((size_t)B * 4 + 4, 256));
+    double* psq = (double*)((char*)psum + ds_align_up((size_t)B * splits * C * sizeof(double), 256));
+    int32_t rc = ds_launch_expand_groups(g->offsets, g->T, slot_group, s);
+    if (rc) return rc;
+    int lcl = 0;
+    while ((8 << lcl) < C && lcl < 5) ++lcl;
+    hipLaunchKernelGGL(bn_partial_kernel, dim3(B, splits), dim3(256), 0, s, (const bf16_t*)x, g->perm, (int64_t)HW * C, C,
+                       slot_group, gt, HW, C, splits, lcl, psum, psq);
+    DS_CHECK_LAUNCH("bn partial statistics");
+    hipLaunchKernelGGL(bn_combine_kernel, dim3(g->T, (C + 15) / 16), dim3(256), 0, s, g->offsets, gt, HW, C, splits, psum, psq,
+                       sum, sumsq, (long long*)count);
+    DS_CHECK_LAUNCH("bn combine statistics");
+    return DS_OK;
+}
+
+extern "C" int32_t ds_bn_stats_finish(const double* sum, const double* sumsq, const int64_t* count, int32_t T, int32_t C,
+                                      const int32_t* width, float* mean, float* var, void* stream) {
+    if (T < 0 || C < 0 || T > DS_MAX_GROUPS) DS_FAIL(DS_EINVAL, "ds_bn_stats_finish: T outside 0..%d or C < 0", DS_MAX_GROUPS);
+    if (T == 0 || C == 0) return DS_OK;
+    if (!sum || !sumsq || !count || !mean || !var) DS_FAIL(DS_EINVAL, "ds_bn_stats_finish: null pointer");
+    GroupTable gt = {};
+    gt.T = T;
+    for (int t = 0; t < T; ++t) {
+        gt.k_in[t] = width ? width[t] : C;
+        if (gt.k_in[t] < 0 || gt.k_in[t] > C) DS_FAIL(DS_EINVAL, "ds_bn_stats_finish: width[%d] = %d outside 0..%d", t, gt.k_in[t], C);
+    }
+    const int n = T * C;
+    hipLaunchKernelGGL(bn_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, sum, sumsq,
+                       (const long long*)count, gt, T, C, mean, var);
+    DS_CHECK_LAUNCH("bn finish statistics");
     return DS_OK;
 }
 

@@ -542,3 +542,37 @@ def test_sliced_conv_and_dwconv_with_an_empty_group_and_one_sample(gpu_lib):
     ydh = host(yd).transpose(0, 3, 1, 2)
     wantd = O.bf16_round(O.relu(O.re_sbn(O.sliced_dwconv2d(x[0, :48], wd, 1, 1), bnd, 2, 1e-5)))
     assert relerr(ydh[0, :48], wantd) < TOL_BF16 and np.all(np.isnan(ydh[0, 48:]))
+
+
+# ------------------------------------------------------------------ Re-SBN re-calibration
+@pytest.mark.parametrize("HW,C", [(28 * 28, 512), (56 * 56, 64), (7 * 7, 1024), (112 * 112, 24)])
+def test_bn_stats_streaming_recalibration(gpu_lib, HW, C):
+    # three batches of different sizes streamed through the accumulators; the result must be the population
+    # statistics per route over everything streamed (the oracle sees all samples at once)
+    T = 4
+    d = WL.nets.Draw(5000 + C)
+    widths = [max(8, C * q // 4 // 8 * 8) for q in (1, 2, 3, 4)]
+    acc_s = torch.zeros((T, C), dtype=torch.float64, device=DEV)
+    acc_q = torch.zeros((T, C), dtype=torch.float64, device=DEV)
+    cnt = torch.zeros((T,), dtype=torch.int64, device=DEV)
+    samples, routes = [], []
+    for B in (5, 9, 2):
+        route = d.randint(B, T - 1)                      # the last route never gets a sample
+        x = WL.nets.as_bf16_values(d.normal((B, HW, C), std=1.5, mean=0.3))
+        perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+        g = gpu_lib.make_groups(off, perm, widths)
+        gpu_lib.ds_bn_stats_accumulate(dev(x, torch.bfloat16), g, acc_s, acc_q, cnt)
+        for b in range(B):
+            c = widths[route[b]]
+            samples.append(x[b, :, :c].T.reshape(c, HW, 1))
+            routes.append(int(route[b]))
+    mean, var = gpu_lib.ds_bn_stats_finish(acc_s, acc_q, cnt, widths)
+    want_m, want_v, want_n = O.re_sbn_recalibrate(samples, routes, T, C)
+    assert cnt.cpu().numpy().tolist() == want_n.tolist()
+    m, v = host(mean), host(var)
+    assert np.max(np.abs(m - want_m)) < 1e-5 * max(1.0, np.max(np.abs(want_m)))
+    assert np.max(np.abs(v - want_v)) < 1e-5 * np.max(np.abs(want_v))
+    assert np.all(m[T - 1] == 0) and np.all(v[T - 1] == 1)
+    # the new tables go straight into the fold used by every sliced layer
+    scale, shift = gpu_lib.ds_bn_fold(torch.ones(C, device=DEV), torch.zeros(C, device=DEV), mean, var, 1e-5)
+    assert torch.isfinite(scale).all() and torch.isfinite(shift).all()
