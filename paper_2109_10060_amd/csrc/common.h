@@ -135,6 +135,12 @@ struct BucketArgs {
     int32_t *perm, *inv_perm, *offsets, *slot_group;   // inv_perm, slot_group nullable
     const int32_t* inv_prev;  // with src_index: src_index[slot] = inv_prev ? inv_prev[sample] : sample
     int32_t* src_index;       // nullable
+    // optional extras done by the same launch (T <= DS_MAX_GROUPS): up to two m-tile lists for the new offsets
+    // (as ds_build_mtiles writes them, for list_rows[i] rows per sample) and slot_lut[slot] = lut[group of slot]
+    int32_t n_lists, list_rows[2];
+    void* lists[2];
+    int32_t* slot_lut;        // nullable
+    int32_t lut[DS_MAX_GROUPS];
 };
 int32_t ds_launch_bucket_ex(const BucketArgs& a, hipStream_t s);
 int32_t ds_launch_bucket(const int32_t* route, int32_t B, int32_t T, int32_t* perm, int32_t* inv_perm,

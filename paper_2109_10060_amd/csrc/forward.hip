@@ -170,7 +170,7 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
     RC(ds_launch_stem(images, nullptr, p.bufA, (const bf16_t*)P[0], (const float*)P[1], (const float*)P[2], B, d.image,
                       d.image, 3, 2, 1, d.stem_out, s));
     bf16_t *cur = p.bufA, *oth = p.bufB;
-    int li = -1, last_rows = -1, last_phase = -1;
+    int li = -1, last_rows = -1, last_phase = -1, fused_lists = 0;
     MList ml = {nullptr, 0, 0};
     for (int i = 0; i < d.nb; ++i) {
         const int ci = d.blk[3 * i], co = d.blk[3 * i + 1], st = d.blk[3 * i + 2];
@@ -188,7 +188,25 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
             g.C_mlp = d.gate_hidden; g.T = d.T; g.logit_bias = logit_bias; g.route_override = route_override;
             g.logits = p.gate_logits; g.route = routes_out ? routes_out : p.route; g.partial = p.gate_partial;
             RC(ds_launch_gate(g, s));
-            RC(ds_launch_bucket(g.route, B, d.T, p.perm, p.inv, p.offs, p.slot_group, s));
+            // one launch: bucket order, the tile lists of the (up to two) resolutions the sliced blocks run at, and
+            // the classifier's input width per slot
+            BucketArgs ba = {};
+            ba.route = g.route; ba.mul = 1; ba.B = B; ba.T = d.T;
+            ba.perm = p.perm; ba.inv_perm = p.inv; ba.offsets = p.offs; ba.slot_group = p.slot_group;
+            int rr = rin, lrows = -1;
+            for (int k = i; k < d.nb && ba.n_lists < 2; ++k) {
+                rr = (rr + 2 - 3) / d.blk[3 * k + 2] + 1;
+                if (rr * rr != lrows) {
+                    lrows = rr * rr;
+                    ba.list_rows[ba.n_lists] = lrows;
+                    ba.lists[ba.n_lists] = p.lists[li + 1 + ba.n_lists];
+                    ++ba.n_lists;
+                }
+            }
+            fused_lists = ba.n_lists;
+            ba.slot_lut = p.slot_c;
+            for (int t = 0; t < d.T; ++t) ba.lut[t] = d.cout[t * d.nb + d.nb - 1];
+            RC(ds_launch_bucket_ex(ba, s));
         }
         GroupTable gdw, gpw;
         memset(&gdw, 0, sizeof(gdw));
@@ -210,7 +228,8 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
             ml.list = p.lists[li];
             ml.cap = (int)ds_mtile_capacity(B, r * r, phase ? d.T : 1);
             ml.rows = r * r;
-            RC(ds_build_mtiles(offsets, phase ? d.T : 1, r * r, ml.list, s));
+            if (phase && fused_lists > 0) --fused_lists;      // built together with the bucket order
+            else RC(ds_build_mtiles(offsets, phase ? d.T : 1, r * r, ml.list, s));
             last_rows = r * r;
             last_phase = phase;
         }
@@ -239,12 +258,7 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
     }
     const void* const* F = P + 3 + 6 * d.nb + 4;
     const int cl = d.blk[3 * (d.nb - 1) + 1];
-    GroupTable gh;
-    memset(&gh, 0, sizeof(gh));
-    gh.T = d.T;
-    for (int t = 0; t < d.T; ++t) gh.k_in[t] = gh.k_out[t] = d.cout[t * d.nb + d.nb - 1];
-    ActView xv = {cur, nullptr, (int64_t)r * r * cl, 0};
-    RC(ds_launch_lookup(p.slot_group, gh, 0, p.slot_c, B, s));
+    ActView xv = {cur, nullptr, (int64_t)r * r * cl, 0};   // slot_c holds the last block's width per slot
     return ds_launch_head(xv, r * r, (const bf16_t*)F[0], cl, (const float*)F[1], d.classes, p.slot_c, p.perm, logits,
                           p.head_partial, B, cl, s);
 }
@@ -371,12 +385,16 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         ba.perm = p.perm[st]; ba.inv_perm = p.inv[st]; ba.offsets = p.offs[st]; ba.slot_group = p.slot_group[st];
         ba.inv_prev = st > 0 ? p.inv[st - 1] : nullptr;
         ba.src_index = p.src_index;          // slot of this stage -> slot of the previous stage's layout
-        RC(ds_launch_bucket_ex(ba, s));
-        const int32_t* src = p.src_index;
+        // the same launch builds the tile lists at both resolutions and the per-slot output width of the stage
         MList ml_in = {p.lists[2 * st], (int)ds_mtile_capacity(B, rin * rin, G), rin * rin};
         MList ml_out = {p.lists[2 * st + 1], (int)ds_mtile_capacity(B, rout * rout, G), rout * rout};
-        RC(ds_build_mtiles(p.offs[st], G, rin * rin, ml_in.list, s));
-        RC(ds_build_mtiles(p.offs[st], G, rout * rout, ml_out.list, s));
+        ba.n_lists = 2;
+        ba.list_rows[0] = rin * rin; ba.lists[0] = ml_in.list;
+        ba.list_rows[1] = rout * rout; ba.lists[1] = ml_out.list;
+        ba.slot_lut = p.slot_c;
+        for (int id = 0; id < G; ++id) ba.lut[id] = d.out[st * T + id / T];
+        RC(ds_launch_bucket_ex(ba, s));
+        const int32_t* src = p.src_index;
         // ---- group tables: group id = q * T + q_prev
         GroupTable g1f, gpj, g1, g2, g3;
         memset(&g1f, 0, sizeof(g1f));
@@ -397,7 +415,6 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
             g3.k_in[id] = d.mid[st * T + q];
             g3.k_out[id] = d.out[st * T + q];
         }
-        const GroupTable g_out = g3;   // output widths of the stage, kept whole while the depth loop empties g3
         // buffers other than X: Y1, Y2, Pj, Z
         bf16_t* free4[4];
         for (int i = 0, k = 0; i < 5; ++i)
@@ -446,19 +463,13 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
                          (const float*)L[7], (const float*)L[8], 4 * w, shortcut, Z, (int64_t)rout * rout * 4 * w, 0,
                          p.offs[st], ml_out, g3, DS_ACT_RELU, s));
         }
-        RC(ds_launch_lookup(p.slot_group[st], g_out, 1, p.slot_c, B, s));
         X = Z;
         for (int i = 0; i < 5; ++i)
             if (p.buf[i] == Z) xi = i;
         c_prev_full = 4 * w;
         r = rout;
     }
-    GroupTable gh;
-    memset(&gh, 0, sizeof(gh));
-    gh.T = G;
-    for (int id = 0; id < G; ++id) gh.k_in[id] = gh.k_out[id] = d.out[3 * T + id / T];
-    ActView xv = {X, nullptr, (int64_t)r * r * c_prev_full, 0};
-    (void)gh;   // slot_c already holds the stage-4 output widths
+    ActView xv = {X, nullptr, (int64_t)r * r * c_prev_full, 0};   // slot_c holds the stage-4 output widths
     return ds_launch_head(xv, r * r, (const bf16_t*)Q[0], c_prev_full, (const float*)Q[1], d.classes, p.slot_c, p.perm[3],
                           logits, p.gate_partial, B, c_prev_full, s);
 }
@@ -609,11 +620,18 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
         g.C_mlp = d.gate_hidden; g.partial = p.gate_partial;
     }
     RC(ds_launch_gate(g, s));
-    RC(ds_launch_bucket(route, B, T, p.perm, p.inv, p.offs, p.slot_group, s));
+    // one launch: bucket order, the tile lists for the patch rows and the token rows, the embedding width per slot
     MList ml_p = {p.list_p, (int)ds_mtile_capacity(B, np, T), np};
     MList ml_t = {p.list_t, (int)ds_mtile_capacity(B, d.N, T), d.N};
-    RC(ds_build_mtiles(p.offs, T, np, ml_p.list, s));
-    RC(ds_build_mtiles(p.offs, T, d.N, ml_t.list, s));
+    BucketArgs ba = {};
+    ba.route = route; ba.mul = 1; ba.B = B; ba.T = T;
+    ba.perm = p.perm; ba.inv_perm = p.inv; ba.offsets = p.offs; ba.slot_group = p.slot_group;
+    ba.n_lists = 2;
+    ba.list_rows[0] = np; ba.lists[0] = ml_p.list;
+    ba.list_rows[1] = d.N; ba.lists[1] = ml_t.list;
+    ba.slot_lut = p.slot_c;
+    for (int t = 0; t < T; ++t) ba.lut[t] = d.routes[d.rs * t];
+    RC(ds_launch_bucket_ex(ba, s));
     GroupTable ge, gq, gp, g1, g2;
     memset(&ge, 0, sizeof(ge));
     ge.T = T;
@@ -686,7 +704,6 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
     }
     const void* const* F = P + 4 + 12 * d.depth;
     RC(ds_launch_layernorm(xv, av, (const float*)F[0], (const float*)F[1], eps, p.slot_group, fq, B, d.N, 0, 1, s));
-    RC(ds_launch_lookup(p.slot_group, fq, 0, p.slot_c, B, s));
     return ds_launch_head(av, 0, (const bf16_t*)F[2], d.D, (const float*)F[3], d.classes, p.slot_c, p.perm, logits, nullptr,
                           B, d.D, s);
 }

@@ -176,6 +176,31 @@ __global__ __launch_bounds__(1024) void bucket_kernel(const BucketArgs a) {
     }
     __syncthreads();
     for (int t = tid; t <= T; t += 1024) a.offsets[t] = base[t];
+    if (a.n_lists > 0) {
+        // m-tile lists of the grouped GEMM for these offsets: groups from the last to the first (widest slices
+        // first), DS_GEMM_BM rows per tile; entry = (group, first row inside the group, first slot, rows of the group)
+        __shared__ int pre[2][DS_MAX_GROUPS + 1];
+        if (tid < a.n_lists) {
+            int acc = 0;
+            for (int q = 0; q < T; ++q) {
+                const int g = T - 1 - q;
+                pre[tid][q] = acc;
+                acc += ((base[g + 1] - base[g]) * a.list_rows[tid] + DS_GEMM_BM - 1) / DS_GEMM_BM;
+            }
+            pre[tid][T] = acc;
+            *(int32_t*)a.lists[tid] = acc;
+        }
+        __syncthreads();
+        for (int li = 0; li < a.n_lists; ++li) {
+            int4* entries = (int4*)((char*)a.lists[li] + 16);
+            for (int q = 0; q < T; ++q) {
+                const int g = T - 1 - q;
+                const int n = pre[li][q + 1] - pre[li][q];
+                const int slot0 = base[g], rg = (base[g + 1] - slot0) * a.list_rows[li];
+                for (int i = tid; i < n; i += 1024) entries[pre[li][q] + i] = make_int4(g, i * DS_GEMM_BM, slot0, rg);
+            }
+        }
+    }
     for (int b0 = 0; b0 < B; b0 += 1024) {
         __syncthreads();
         const int b = b0 + tid;
@@ -190,6 +215,7 @@ __global__ __launch_bounds__(1024) void bucket_kernel(const BucketArgs a) {
             if (a.inv_perm) a.inv_perm[b] = pos;
             if (a.slot_group) a.slot_group[pos] = k;
             if (a.src_index) a.src_index[pos] = a.inv_prev ? a.inv_prev[b] : b;
+            if (a.slot_lut) a.slot_lut[pos] = a.lut[k];
         }
         __syncthreads();
         if (k >= 0) atomicAdd(&base[k], 1);
@@ -364,6 +390,8 @@ int32_t ds_launch_gate(const GateArgs& a, hipStream_t s) {
 }
 
 int32_t ds_launch_bucket_ex(const BucketArgs& a, hipStream_t s) {
+    if ((a.n_lists > 0 || a.slot_lut) && a.T > DS_MAX_GROUPS) DS_FAIL(DS_EINVAL, "route bucket: fused lists need T <= %d", DS_MAX_GROUPS);
+    if (a.n_lists < 0 || a.n_lists > 2) DS_FAIL(DS_EINVAL, "route bucket: at most two m-tile lists");
     ProfScope prof(DS_K_BUCKET, s);
     hipLaunchKernelGGL(bucket_kernel, dim3(1), dim3(1024), 0, s, a);
     DS_CHECK_LAUNCH("route bucket");
