@@ -229,6 +229,13 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
     }
 
     // ---- epilogue through LDS: each lane finishes 4 consecutive channels of one row -----------
+    // staging rows are private to a wavefront and the loop's last barrier has retired every read of the tiles they
+    // alias: between the passes only the compiler has to be kept from moving LDS accesses
+    auto wave_sync = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
     float* st = (float*)smem + wave * SROWS * ST_LD;
 #pragma unroll
     for (int ps = 0; ps < PASSES; ++ps) {
@@ -240,7 +247,7 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
                 const int lr = 8 * ((v >> 2) - ps * (4 / PASSES)) + 4 * lhi + (v & 3);
                 st[lr * ST_LD + tn * 32 + l32] = acc[tn][v];
             }
-        __syncthreads();
+        wave_sync();
         if (nok) {
 #pragma unroll
             for (int rr = rr0; rr < SROWS; rr += RPP) {
@@ -273,7 +280,7 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
                 }
             }
         }
-        __syncthreads();
+        wave_sync();
     }
 }
 

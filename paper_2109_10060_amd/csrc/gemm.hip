@@ -275,6 +275,14 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
     }
 
     // ---- epilogue through LDS: each lane finishes 4 consecutive channels of one row -----
+    // The staging rows belong to one wavefront (written and read back by its own lanes, and the main loop's last
+    // barrier has already retired every read of the operand tiles they alias), and a wavefront's LDS accesses
+    // complete in order, so the passes only need the compiler kept from moving LDS accesses across them.
+    auto wave_sync = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
     float* st = (float*)smem + wave * SROWS * ST_LD;
 #pragma unroll
     for (int tm = 0; tm < WMT; ++tm) {
@@ -288,7 +296,7 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
                     const int lr = 8 * ((v >> 2) - ps * (4 / PASSES)) + 4 * lhi + (v & 3);
                     st[lr * ST_LD + tn * 32 + l32] = acc[tm][tn][v];
                 }
-            __syncthreads();
+            wave_sync();
             if (nok) {
 #pragma unroll
                 for (int rr = rr0; rr < SROWS; rr += RPP) {
@@ -321,7 +329,7 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
                     }
                 }
             }
-            __syncthreads();
+            wave_sync();
         }
     }
 }
