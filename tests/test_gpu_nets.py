@@ -326,3 +326,25 @@ def test_vit_config5_batch256(gpu_lib):
     assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
     l4, _ = gpu_lib.ds_forward(net, xg, route_override=routes.clone())
     assert torch.equal(l4, logits)
+
+
+# ------------------------------------------------------------------ degenerate batches
+def test_single_sample_batches_all_networks(gpu_lib):
+    # one sample: every route group but one is empty, tile lists hold a single group, buckets have one slot
+    arch = WL.mbnet_arch(image=64, width_div=4)
+    params = WL.mbnet_params(arch, S + 30)
+    _mb_case(gpu_lib, arch, params, WL.images(S + 90, 1, 64), WL.seeded_logit_bias(S + 91, 1, arch["T"]), [0])
+    arch = WL.resnet_arch(image=64, width_div=2, blocks=(2, 1, 2, 1), routes="depth")
+    params = WL.resnet_params(arch, S + 40)
+    _rn_case(gpu_lib, arch, params, WL.images(S + 92, 1, 64), _rn_bias(S + 93, 1, 8), [0])
+    arch = WL.vit_arch(image=64, patch=16, depth=2, routes="cross")
+    params = WL.vit_params(arch, S + 50)
+    _vit_case(gpu_lib, arch, params, WL.images(S + 94, 1, 64), WL.seeded_logit_bias(S + 95, 1, arch["T"]), [0])
+    arch = WL.vit_arch(image=64, patch=8, embed=416, heads=8, head_dim=48, mlp=1664, depth=3, routes="pp", stem_dim=24)
+    params = WL.vit_params(arch, S + 80)
+    _vit_stem_case(gpu_lib, arch, params, WL.images(S + 96, 1, 64), WL.seeded_logit_bias(S + 97, 1, arch["T"], amp=16.0), [0])
+    # an empty batch is a no-op
+    net = gpu_lib.build_vit(arch, params, DEV)
+    empty = torch.zeros((0, 3, 64, 64), dtype=torch.bfloat16, device=DEV)
+    logits, routes = gpu_lib.ds_forward(net, empty, logit_bias=torch.zeros((1, 0, arch["T"]), dtype=torch.float32, device=DEV))
+    assert logits.shape == (0, arch["num_classes"]) and routes.shape == (1, 0)
