@@ -56,6 +56,42 @@ def test_host_validation_returns_codes_without_a_gpu():
     assert lib.ds_sliced_linear_workspace(64, 197, 4) >= 16 + 8 * (64 * 197 // 128 + 4)
 
 
+def test_host_validation_of_the_spatial_statistics_and_forward_entry_points():
+    lib = _lib()
+    g = ds.ds_groups()
+    g.T = 1
+    g.offsets = 1024  # never dereferenced on the host
+    g.k_in[0] = g.k_out[0] = 16
+    sp = ds.ds_spatial()
+    sp.ksize[0], sp.dilation[0], sp.pad[0] = 4, 1, 1                     # an even block is no centred crop of 7x7
+    args = lambda: (None, 2, 16, 8, 8, None, 7, None, None, ctypes.byref(g), ctypes.byref(sp), 1, 1, None,
+                    ctypes.c_int64(8 * 8 * 16), None, ctypes.c_size_t(0), None)
+    assert lib.ds_sliced_dwconv_spatial(*args()) == ds.DS_EINVAL and b"centred" in lib.ds_last_error()
+    sp.ksize[0], sp.dilation[0] = 3, 0
+    assert lib.ds_sliced_dwconv_spatial(*args()) == ds.DS_EINVAL
+    sp.dilation[0], sp.pad[0] = 1, 0
+    a = list(args()); a[6] = 4                                          # stored filter must be odd
+    assert lib.ds_sliced_dwconv_spatial(*a) == ds.DS_EUNSUPPORTED
+    a = list(args()); a[14] = ctypes.c_int64(16)                        # output block too small for 6x6x16
+    assert lib.ds_sliced_dwconv_spatial(*a) == ds.DS_ESHAPE
+    assert lib.ds_sliced_dwconv_spatial(*args()) == ds.DS_EINVAL        # everything consistent, tensors null
+    # statistics
+    assert lib.ds_bn_stats_accumulate(None, 2, 0, 16, ctypes.byref(g), None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
+    g.k_in[0] = 12
+    assert lib.ds_bn_stats_accumulate(None, 2, 4, 16, ctypes.byref(g), None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
+    w = (ctypes.c_int32 * 2)(8, 24)
+    assert lib.ds_bn_stats_finish(None, None, None, 2, 16, w, None, None, None) == ds.DS_EINVAL
+    assert lib.ds_bn_stats_workspace(4, 64, 32) > 0 and lib.ds_bn_stats_workspace(0, 64, 32) == 0
+    # forward: a description whose integer list does not fit the architecture
+    ints = (ctypes.c_int32 * 5)(224, 64, 4, 1000, 7)
+    params = (ctypes.c_void_p * 1)(0)
+    net = ds.ds_net(ds.DS_ARCH_RESNET, 5, ints, 1, params)
+    assert lib.ds_forward_workspace(ctypes.byref(net), 4) == 0
+    assert lib.ds_forward(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
+    assert lib.ds_forward(ctypes.byref(net), None, -1, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
+    assert lib.ds_forward(ctypes.byref(net), None, 0, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_OK
+
+
 def test_missing_library_fails_loudly(tmp_path):
     import importlib
     old = ds._lib
