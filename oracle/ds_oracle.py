@@ -385,6 +385,8 @@ def forward_resnet(arch, p, image, logit_bias=None, route_override=None, store="
     projection shortcut follow that route; later blocks inherit it.
     logit_bias / route_override: [4, T] / [4] per stage.  Returns (logits, routes[4], scores).
 
+    arch["single_gate"]: only the first stage's gate decides; the later stages follow its route
+    (their scores are still returned for reference).
     arch["nblk"][s][t], when present, is the number of blocks of stage s that route t runs
     (dynamic depth, Section 3.4 / Guideline I of Section 3.1): the first block always runs, since
     it changes resolution and width; the skipped later blocks are identities through their
@@ -400,6 +402,8 @@ def forward_resnet(arch, p, image, logit_bias=None, route_override=None, store="
         z = gate_logits(gate_encoder(x), p[pre + ".gate.w1"], p[pre + ".gate.b1"],
                         p[pre + ".gate.w2"], p[pre + ".gate.b2"], lb)
         t = gate_route(z) if route_override is None else int(route_override[s])
+        if arch.get("single_gate") and s > 0:
+            t = routes[0]          # DS-ResNet++: the gate of the first block steers all four stages (Section 5.2)
         routes.append(t)
         scores.append(z)
         mid, out = int(arch["mid"][s, t]), int(arch["out"][s, t])

@@ -346,3 +346,30 @@ def test_vit_stem_patch_projection_is_a_linear_layer_on_patches_and_gate_follows
         assert t == int(np.argmax(z)) == int(np.argmax(lb[b])) and z.shape == (arch["T"],)
         hi, _, _ = O.forward_vit_stem(arch, p, img[b], route_override=t, store="f64")
         assert np.max(np.abs(lo - hi)) / np.max(np.abs(hi)) < 2e-2
+
+
+def test_resnet_pp_single_gate_steers_every_stage():
+    # DS-ResNet++: the first block's gate decides width and depth of all four stages (Section 5.2); the table's ranges
+    blocks = (3, 4, 8, 3)
+    full = WL.resnet_arch(blocks=blocks, routes="pp")
+    assert full["T"] == 9 and full["single_gate"]
+    assert full["out"][0].tolist() == [128, 128, 160, 160, 192, 192, 224, 224, 256]
+    assert (full["out"][1][0], full["out"][1][-1], full["out"][2][0], full["out"][2][-1]) == (256, 512, 512, 1024)
+    assert (full["out"][3][0], full["out"][3][-1]) == (1024, 2048)
+    assert [(int(r.min()), int(r.max())) for r in full["nblk"]] == [(2, 3), (2, 4), (5, 8), (2, 3)]
+    arch = WL.resnet_arch(image=32, width_div=8, blocks=blocks, routes="pp")
+    p = WL.resnet_params(arch, 29)
+    img = WL.images(33, 1, 32)[0]
+    multi = {k: v for k, v in arch.items() if k != "single_gate"}
+    for t in (0, 4, 8):
+        lb = np.zeros((4, 9), np.float32)
+        lb[0, t] = 50.0                                    # stage-1 gate picks t
+        lb[1:, (t + 3) % 9] = 50.0                         # the other gates would pick something else
+        got, rt, zs = O.forward_resnet(arch, p, img, logit_bias=lb, store="f64")
+        assert rt == [t, t, t, t] and len(zs) == 4
+        want, _, _ = O.forward_resnet(multi, p, img, route_override=[t, t, t, t], store="f64")
+        np.testing.assert_array_equal(got, want)
+        # and against library layers on a network cut to the route's block counts
+        cut = {k: v for k, v in multi.items() if k != "nblk"}
+        cut["blocks"] = [int(arch["nblk"][s][t]) for s in range(4)]
+        np.testing.assert_allclose(got, _ref_resnet(cut, p, img, [t, t, t, t]), rtol=1e-9, atol=1e-9)

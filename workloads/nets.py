@@ -178,14 +178,29 @@ def resnet_arch(image: int = 224, width_div: int = 1, blocks=(3, 4, 6, 3), route
     """Bottleneck stages with mid width w*q/4 and output width 4w*q/4, q=1..4.
 
     mid[s][t], out[s][t] are the valid channel counts of stage s on route t.  The 7x7 stem and
-    the max-pool are never sliced.  routes="width": 4 routes, one per ratio; "depth": 8 routes,
+    the max-pool are never sliced.  routes="width": 4 routes, one per ratio; "pp": the 9 paths of
+    DS-ResNet++ under a single gate; "depth": 8 routes,
     route t has ratio index t // 2 and runs nblk[s][t] = blocks[s] - 1 + t % 2 (at least 1)
     blocks of stage s.
     """
     widths = [64 // width_div, 128 // width_div, 256 // width_div, 512 // width_div]
     mid = np.array([[w * q // 4 for q in (1, 2, 3, 4)] for w in widths], np.int32)
     extra = {}
-    if routes == "depth":
+    if routes == "pp":
+        # DS-ResNet++ (lower half of the DS-ResNet routing-space table): one gate in the first block steers the
+        # width and the number of blocks of all four stages; 9 nested paths along stage outputs [128:256:32],
+        # [256:512:32], [512:1024:64], [1024:2048:128] and block counts [2:3], [2:4], [5:8], [2:3]
+        # (use blocks=(3, 4, 8, 3)).  Stage 1 has five widths for nine paths: two paths share each.
+        d = width_div
+        outs = [[(128 + 32 * (i // 2)) // d for i in range(9)], [(256 + 32 * i) // d for i in range(9)],
+                [(512 + 64 * i) // d for i in range(9)], [(1024 + 128 * i) // d for i in range(9)]]
+        mid = np.array(outs, np.int32) // 4
+        nb = list(blocks)
+        extra["nblk"] = np.array([[nb[0] - 1 + (i >= 5) for i in range(9)], [nb[1] - 2 + i // 3 for i in range(9)],
+                                  [nb[2] - 3 + i // 3 + (i == 8) for i in range(9)], [nb[3] - 1 + (i >= 5) for i in range(9)]],
+                                 np.int32).clip(1, None)
+        extra["single_gate"] = True
+    elif routes == "depth":
         mid = np.repeat(mid, 2, axis=1)
         extra["nblk"] = np.array([[max(1, nb - 1 + t % 2) for t in range(8)] for nb in blocks], np.int32)
     else:
