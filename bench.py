@@ -43,6 +43,11 @@ def build_workload(name: str, B: int):
         params = WL.resnet_params(arch, S + 4)
         lb = np.stack([WL.seeded_logit_bias(S + 204 + s, B, 4, amp=16.0) for s in range(4)])
         label = "config4: DS-ResNet (ResNet-50-shaped, 4 gates x 4 width ratios), bf16"
+    elif name == "resnet_pp":
+        arch = WL.resnet_arch(blocks=(3, 4, 8, 3), routes="pp")
+        params = WL.resnet_params(arch, S + 9)
+        lb = np.stack([WL.seeded_logit_bias(S + 209 + s, B, 9, amp=16.0) for s in range(4)])
+        label = "DS-ResNet++ (one gate, 9 paths over stage widths [128:256:32] .. [1024:2048:128] and block counts), bf16"
     elif name == "vit":
         arch = WL.vit_arch()
         params = WL.vit_params(arch, S + 5)
@@ -61,7 +66,7 @@ def build_workload(name: str, B: int):
                  "8 nested routes), bf16")
     else:
         raise SystemExit(f"unknown workload {name}")
-    imgs = WL.images(S + 100 + {"mbnet": 3, "resnet": 4, "vit": 5, "vit_stem": 6, "vit_pp": 7, "mbnet_pp": 8}[name], B)
+    imgs = WL.images(S + 100 + {"mbnet": 3, "resnet": 4, "vit": 5, "vit_stem": 6, "vit_pp": 7, "mbnet_pp": 8, "resnet_pp": 9}[name], B)
     return arch, params, imgs, lb.astype("float32"), label
 
 
@@ -78,7 +83,7 @@ def cpu_baseline(name, arch, params, imgs, lb, budget_s=15.0):
     while n < imgs.shape[0] and (time.perf_counter() - t0 < budget_s or n < 2):
         if name in ("mbnet", "mbnet_pp"):
             O.forward_mbnet(arch, params, imgs[n], logit_bias=lb[0, n])
-        elif name == "resnet":
+        elif name in ("resnet", "resnet_pp"):
             O.forward_resnet(arch, params, imgs[n], logit_bias=lb[:, n])
         elif name in ("vit_stem", "vit_pp"):
             O.forward_vit_stem(arch, params, imgs[n], logit_bias=lb[0, n])
@@ -95,7 +100,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp"])
+    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp", "resnet_pp"])
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -127,7 +132,7 @@ def main():
         return
     B = args.batch
     arch, params, imgs, lb, label = build_workload(args.workload, B)
-    net = {"mbnet": ds.build_mbnet, "mbnet_pp": ds.build_mbnet, "resnet": ds.build_resnet, "vit": ds.build_vit,
+    net = {"mbnet": ds.build_mbnet, "mbnet_pp": ds.build_mbnet, "resnet": ds.build_resnet, "resnet_pp": ds.build_resnet, "vit": ds.build_vit,
            "vit_stem": ds.build_vit, "vit_pp": ds.build_vit}[args.workload](arch, params, dev)
     x = torch.from_numpy(imgs).to(dev).to(torch.bfloat16).contiguous()
     lbg = torch.from_numpy(lb).to(dev).contiguous()
@@ -167,7 +172,7 @@ def main():
     prof = ds.ds_profile_read() if sampled else {}
 
     rt = routes.cpu().numpy()
-    cost = {"mbnet": C.mbnet_cost, "mbnet_pp": C.mbnet_cost, "resnet": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost,
+    cost = {"mbnet": C.mbnet_cost, "mbnet_pp": C.mbnet_cost, "resnet": C.resnet_cost, "resnet_pp": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost,
             "vit_pp": C.vit_cost}[args.workload](arch, rt)
     roofline = None
     kernels = {}

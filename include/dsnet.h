@@ -239,7 +239,10 @@ int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D_e, const v
 /* DS_ARCH_RESNET: bottleneck ResNet, a gate in the first block of each of 4 stages (DS-ResNet).
  *   ints:   image, stem_out, T, num_classes, widths[4], blocks[4], gate_hidden[4], mid[4][T], out[4][T],
  *           optionally nblk[4][T]: route t runs only the first nblk[s][t] (1..blocks[s]) blocks of
- *           stage s (dynamic depth, Section 3.4); its slots pass through the later blocks unchanged
+ *           stage s (dynamic depth, Section 3.4); its slots pass through the later blocks unchanged;
+ *           after nblk optionally one flags word: bit 0 = the gate of the first stage decides for all
+ *           four stages (DS-ResNet++, Section 5.2), the other gates' parameters are not read and
+ *           routes_out repeats the first row
  *   params: stem.w bf16 [7*7*3][stem_out], stem.scale, stem.shift,
  *           per stage: gate.w1, gate.b1, gate.w2, gate.b2 (fp32), then per block
  *             c1.w bf16 [w][1][1][C_in], c1.scale, c1.shift fp32 [T][w],

@@ -70,16 +70,22 @@ def resnet_cost(arch, routes) -> Cost:
     for s, nb in enumerate(arch["blocks"]):
         mid = arch["mid"][s][routes[s]].astype(np.float64)
         out = arch["out"][s][routes[s]].astype(np.float64)
-        c.add("gate", 2.0 * r * r * cprev.sum(), 2.0 * r * r * cprev.sum())
+        if s == 0 or not arch.get("single_gate"):
+            c.add("gate", 2.0 * r * r * cprev.sum(), 2.0 * r * r * cprev.sum())
         for b in range(nb):
+            # dynamic depth: samples whose route has run its blocks of this stage contribute nothing
+            on = (arch["nblk"][s][routes[s]] > b).astype(np.float64) if arch.get("nblk") is not None else np.ones(B)
+            if not on.any():
+                break
             stride = 2 if (b == 0 and s > 0) else 1
             ro = _osz(r, 3, stride, 1)
-            cin = cprev if b == 0 else out
+            cin = (cprev if b == 0 else out) * on
+            m, o = mid * on, out * on
             if b == 0:
-                _gemm(c, "gemm", ro * ro, ro * ro, 1, cin, out)      # 1x1 projection reads only the strided pixels
-            _gemm(c, "gemm", r * r, r * r, 1, cin, mid)
-            _gemm(c, "gemm_taps", r * r, ro * ro, 9, mid, mid)
-            _gemm(c, "gemm", ro * ro, ro * ro, 1, mid, out, residual=True)
+                _gemm(c, "gemm", ro * ro, ro * ro, 1, cin, o)      # 1x1 projection reads only the strided pixels
+            _gemm(c, "gemm", r * r, r * r, 1, cin, m)
+            _gemm(c, "gemm_taps", r * r, ro * ro, 9, m, m)
+            _gemm(c, "gemm", ro * ro, ro * ro, 1, m, o, residual=True)
             r = ro
         cprev = out
     c.add("head", 2.0 * arch["num_classes"] * cprev.sum(),

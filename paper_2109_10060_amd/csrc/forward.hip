@@ -265,7 +265,7 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
 
 // =====================================================================================
 // DS-ResNet
-//  ints:   image, stem_out, T, num_classes, widths[4], blocks[4], gate_hidden[4], mid[4][T], out[4][T] [, nblk[4][T]]
+//  ints:   image, stem_out, T, num_classes, widths[4], blocks[4], gate_hidden[4], mid[4][T], out[4][T] [, nblk[4][T] [, flags]]
 //  params: stem.w [147][stem_out] bf16, stem.scale, stem.shift,
 //          per stage: gate.w1, gate.b1, gate.w2, gate.b2, then per block:
 //             c1.w [w][C_in] bf16, c1.scale, c1.shift [T][w], c2.w [w][3][3][w] bf16, c2.scale, c2.shift,
@@ -277,16 +277,24 @@ struct RnDesc {
     int image, stem_out, T, classes;
     const int32_t *widths, *blocks, *hidden, *mid, *out;
     const int32_t* nblk;     // [4][T] blocks of a stage that a route runs, or null: every stored block
+    int single_gate;         // 1: the first stage's gate decides for all four stages (DS-ResNet++)
 };
+
+// route groups of a stage: (this stage's route, previous stage's route) pairs, or the route alone when one gate
+// decides for every stage
+inline int rn_groups(const RnDesc& d) { return d.single_gate ? d.T : d.T * d.T; }
 
 bool parse_rn(const ds_net* net, RnDesc* d) {
     if (net->n_ints < 4) return false;
     const int32_t* v = net->ints;
     d->image = v[0]; d->stem_out = v[1]; d->T = v[2]; d->classes = v[3];
-    if (d->T < 1 || d->T * d->T > DS_MAX_GROUPS) return false;
-    if (net->n_ints != 4 + 12 + 8 * d->T && net->n_ints != 4 + 12 + 12 * d->T) return false;
+    if (d->T < 1 || d->T > DS_MAX_GROUPS) return false;
+    const int base = 4 + 12 + 8 * d->T, deep = base + 4 * d->T;
+    if (net->n_ints != base && net->n_ints != deep && net->n_ints != deep + 1) return false;
     d->widths = v + 4; d->blocks = v + 8; d->hidden = v + 12; d->mid = v + 16; d->out = d->mid + 4 * d->T;
-    d->nblk = net->n_ints == 4 + 12 + 12 * d->T ? d->out + 4 * d->T : nullptr;
+    d->nblk = net->n_ints >= deep ? d->out + 4 * d->T : nullptr;
+    d->single_gate = net->n_ints == deep + 1 ? (v[deep] & 1) : 0;
+    if (rn_groups(*d) > DS_MAX_GROUPS) return false;
     if (d->nblk)
         for (int st = 0; st < 4; ++st)
             for (int q = 0; q < d->T; ++q)
@@ -321,7 +329,7 @@ void plan_rn(const RnDesc& d, int B, Bump& bp, RnPlan* p) {
     p->gate_partial = bp.take<float>(ds_gate_partial_bytes(B, cmax) / sizeof(float));
     p->off1 = bp.take<int32_t>(2);
     for (int s = 0; s < 4; ++s) {
-        p->offs[s] = bp.take<int32_t>(d.T * d.T + 1);
+        p->offs[s] = bp.take<int32_t>(rn_groups(d) + 1);
         p->perm[s] = bp.take<int32_t>(B);
         p->inv[s] = bp.take<int32_t>(B);
         p->slot_group[s] = bp.take<int32_t>(B);
@@ -332,16 +340,17 @@ void plan_rn(const RnDesc& d, int B, Bump& bp, RnPlan* p) {
     p->slot_c = bp.take<int32_t>(B);
     r = r2;
     for (int s = 0; s < 4; ++s) {
-        p->lists[2 * s] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 16);  // input resolution
+        p->lists[2 * s] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, rn_groups(d)) * 16);  // input resolution
         if (s > 0) r = (r + 2 - 3) / 2 + 1;
-        p->lists[2 * s + 1] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, d.T * d.T) * 16);  // output resolution
+        p->lists[2 * s + 1] = bp.take<char>(16 + ds_mtile_capacity(B, r * r, rn_groups(d)) * 16);  // output resolution
     }
 }
 
 int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int B, const int32_t* route_override,
                    const float* logit_bias, float* logits, int32_t* routes_out, const RnPlan& p, hipStream_t s) {
     const void* const* P = net->params;
-    const int T = d.T, G = T * T;
+    const int T = d.T, G = rn_groups(d);
+    const bool pairs = !d.single_gate;      // group id = q * T + q_prev, or q alone (then q_prev = q)
     const int r1 = (d.image + 6 - 7) / 2 + 1;
     int r = (r1 + 2 - 3) / 2 + 1;
     // stem and max-pool in one kernel where the shape allows, else one after the other
@@ -376,12 +385,17 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         g.out_index = st > 0 ? p.perm[st - 1] : nullptr;
         g.route_override = route_override ? route_override + (size_t)st * B : nullptr;
         g.logits = p.gate_logits; g.route = route; g.partial = p.gate_partial;
+        if (d.single_gate && st > 0) {
+            // the first stage's decision stands: no pooling, no MLP, the route is copied
+            g.x = nullptr; g.logit_bias = nullptr; g.out_index = nullptr;
+            g.route_override = routes_out ? routes_out : p.route[0];
+        }
         RC(ds_launch_gate(g, s));
         Q += 4;
         // ---- bucket by (this stage's route, previous stage's route)
         const int32_t* route_prev = st > 0 ? (routes_out ? routes_out + (size_t)(st - 1) * B : p.route[st - 1]) : nullptr;
         BucketArgs ba = {};
-        ba.route = route; ba.lo = route_prev; ba.mul = T; ba.B = B; ba.T = G;
+        ba.route = route; ba.lo = pairs ? route_prev : nullptr; ba.mul = pairs ? T : 1; ba.B = B; ba.T = G;
         ba.perm = p.perm[st]; ba.inv_perm = p.inv[st]; ba.offsets = p.offs[st]; ba.slot_group = p.slot_group[st];
         ba.inv_prev = st > 0 ? p.inv[st - 1] : nullptr;
         ba.src_index = p.src_index;          // slot of this stage -> slot of the previous stage's layout
@@ -392,23 +406,22 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         ba.list_rows[0] = rin * rin; ba.lists[0] = ml_in.list;
         ba.list_rows[1] = rout * rout; ba.lists[1] = ml_out.list;
         ba.slot_lut = p.slot_c;
-        for (int id = 0; id < G; ++id) ba.lut[id] = d.out[st * T + id / T];
+        for (int id = 0; id < G; ++id) ba.lut[id] = d.out[st * T + (pairs ? id / T : id)];
         RC(ds_launch_bucket_ex(ba, s));
         const int32_t* src = p.src_index;
         // ---- group tables: group id = q * T + q_prev
         GroupTable g1f, gpj, g1, g2, g3;
         memset(&g1f, 0, sizeof(g1f));
         g1f.T = G;
-        for (int q = 0; q < T; ++q)
-            for (int qp = 0; qp < T; ++qp) {
-                const int id = q * T + qp;
-                g1f.k_in[id] = st > 0 ? d.out[(st - 1) * T + qp] : d.stem_out;
-                g1f.k_out[id] = d.mid[st * T + q];
-                g1f.row[id] = q;
-            }
+        for (int id = 0; id < G; ++id) {
+            const int q = pairs ? id / T : id, qp = pairs ? id % T : id;
+            g1f.k_in[id] = st > 0 ? d.out[(st - 1) * T + qp] : d.stem_out;
+            g1f.k_out[id] = d.mid[st * T + q];
+            g1f.row[id] = q;
+        }
         gpj = g1f; g1 = g1f; g2 = g1f; g3 = g1f;
         for (int id = 0; id < G; ++id) {
-            const int q = id / T;
+            const int q = pairs ? id / T : id;
             gpj.k_out[id] = d.out[st * T + q];
             g1.k_in[id] = d.out[st * T + q];
             g2.k_in[id] = g2.k_out[id] = d.mid[st * T + q];
@@ -432,7 +445,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
                 // kernels leave its slots of Z as they are (the block is an identity through its residual)
                 bool any = false;
                 for (int id = 0; id < G; ++id) {
-                    if (d.nblk[st * T + id / T] > b) { any = true; continue; }
+                    if (d.nblk[st * T + (pairs ? id / T : id)] > b) { any = true; continue; }
                     g1.k_in[id] = g1.k_out[id] = g2.k_in[id] = g2.k_out[id] = g3.k_in[id] = g3.k_out[id] = 0;
                 }
                 if (!any) continue;

@@ -90,6 +90,8 @@ def build_resnet(arch: dict, p: dict, device="cuda:0") -> Net:
             *arch["gate_hidden"], *arch["mid"].reshape(-1).tolist(), *arch["out"].reshape(-1).tolist()]
     if arch.get("nblk") is not None:
         ints += [int(v) for v in arch["nblk"].reshape(-1)]
+        if arch.get("single_gate"):
+            ints.append(1)
     t = [_stem(p["stem.w"], device), *_fold(p["stem.bn"], eps, device)]
     for s, nb in enumerate(arch["blocks"]):
         t += [_dev(p[f"s{s}.gate.{k}"], f32, device) for k in ("w1", "b1", "w2", "b2")]

@@ -167,6 +167,28 @@ def test_resnet_dynamic_depth_small_all_samples(gpu_lib):
         gpu_lib.ds_forward(gpu_lib.build_resnet(bad, params, DEV), xg, logit_bias=lbg)
 
 
+def test_resnet_pp_single_gate_small_and_batch256(gpu_lib):
+    # DS-ResNet++: one gate steers width and block count of all four stages (9 paths)
+    arch = WL.resnet_arch(image=64, blocks=(3, 4, 8, 3), routes="pp")     # full widths: the table's steps of 32 need them
+    params = WL.resnet_params(arch, S + 48)
+    B = 19
+    imgs = WL.images(S + 49, B, 64)
+    lb = _rn_bias(S + 50, B, 9)
+    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, range(B))
+    rt = routes.cpu().numpy()
+    assert (rt == rt[0]).all() and len(set(rt[0].tolist())) == 9
+    arch = WL.resnet_arch(blocks=(3, 4, 8, 3), routes="pp")
+    params = WL.resnet_params(arch, S + 51)
+    B = 256
+    imgs = WL.images(S + 151, B)
+    lb = _rn_bias(S + 251, B, 9)
+    target = np.argmax(lb[0], axis=1)
+    check = [int(np.where(target == t)[0][0]) for t in (0, 8)]
+    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, check)
+    rt = routes.cpu().numpy()
+    assert (rt == rt[0]).all() and np.array_equal(rt[0], target)
+
+
 def test_resnet_config4_batch256(gpu_lib):
     arch = WL.resnet_arch()
     params = WL.resnet_params(arch, S + 4)
