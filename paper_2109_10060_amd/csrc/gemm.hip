@@ -194,7 +194,22 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
 
-    // epilogue constants, loaded early so their latency hides behind the main loop
+    // operand rows of this lane: row (32 t + l32) of the wave's A / B block; with 128-byte rows the
+    // swizzle key of row + 32 t is the key of the row ^ (4 t & 7), with 64-byte rows it does not change
+    const bf16_t* as = As + (wm * WMT * 32 + l32) * LDS_LD;
+    const bf16_t* bs = Bs + (wn * WNT * 32 + l32) * LDS_LD;
+    const int fa = swz<BK>(wm * WMT * 32 + l32), fb = swz<BK>(wn * WNT * 32 + l32);
+    constexpr int TK = BK == 64 ? 4 : 0;
+
+    const int kchunks = (k_in + BK - 1) / BK;
+    const int nk = a.K * a.K * kchunks;
+    int tap = 0, kc = 0;
+    set_tap(0);
+    load_global(0, 0);
+
+    // The first operand slab is requested before anything else: loads return in order, so whatever is issued
+    // ahead of it would have to arrive before the slab can go to LDS.
+    // epilogue constants, loaded now so their latency hides behind the main loop
     constexpr int COLS = TL::COLS, SROWS = TL::SROWS, ST_LD = TL::ST_LD;
     constexpr int CG = COLS / 4, RPP = 64 / CG, PASSES = 32 / SROWS, VPP = 16 / PASSES;
     const int cg = lane % CG, rr0 = lane / CG;
@@ -230,18 +245,6 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
                 }
     }
 
-    // operand rows of this lane: row (32 t + l32) of the wave's A / B block; with 128-byte rows the
-    // swizzle key of row + 32 t is the key of the row ^ (4 t & 7), with 64-byte rows it does not change
-    const bf16_t* as = As + (wm * WMT * 32 + l32) * LDS_LD;
-    const bf16_t* bs = Bs + (wn * WNT * 32 + l32) * LDS_LD;
-    const int fa = swz<BK>(wm * WMT * 32 + l32), fb = swz<BK>(wn * WNT * 32 + l32);
-    constexpr int TK = BK == 64 ? 4 : 0;
-
-    const int kchunks = (k_in + BK - 1) / BK;
-    const int nk = a.K * a.K * kchunks;
-    int tap = 0, kc = 0;
-    set_tap(0);
-    load_global(0, 0);
     store_lds();
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
