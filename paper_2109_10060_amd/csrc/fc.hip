@@ -226,6 +226,106 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
     }
 }
 
+// Matrix-core variant for the classifier (bf16 weights, fp32 pooled vector or bf16 rows, fp32 accumulation, no
+// activation, one partial sum per channel): v_mfma_f32_32x32x2_f32 on a tile of 32 items x 32 outputs.  The four
+// wavefronts of a workgroup take interleaved 16-channel steps of the reduction and their tiles are added in
+// wavefront order, so the result does not depend on timing.  Within a step the lower half of the lanes feeds channels
+// k .. k+7 and the upper half k+8 .. k+15 (one matrix instruction per channel pair), so a lane loads 8 consecutive
+// channels of its item and of its output's weight row.  Channels at or beyond the item's width enter as zeros.
+__global__ __launch_bounds__(256) void fc_mfma_kernel(const FcArgs a) {
+    __shared__ float red[3][32][33];
+    __shared__ int cs[32];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    const int o0 = blockIdx.x * 32, i0 = blockIdx.y * 32;
+    if (tid < 32) {
+        const int item = i0 + tid;
+        cs[tid] = item < a.items ? (a.c_item ? a.c_item[item] : a.C) : 0;
+    }
+    __syncthreads();
+    int cmax = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) cmax = max(cmax, cs[i]);
+    const int item = i0 + l32, c = cs[l32];
+    const int o = o0 + l32;
+    const bool ook = o < a.n_out;
+    const bf16_t* wrow = (const bf16_t*)a.w + (int64_t)(ook ? o : 0) * a.w_ld;
+    const int nsteps = (cmax + 15) / 16;
+    f32x16_t acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    auto fetch = [&](int step, float (&av)[8], uint4& bw) {
+        const int k = step * 16 + 8 * lhi;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) av[q] = 0.f;
+        bw = make_uint4(0, 0, 0, 0);
+        if (k < cmax) {                       // cmax <= C, C % 8 == 0: the 8 channels are inside the row
+            if (ook) bw = *(const uint4*)(wrow + k);
+            if (k < c) {
+                if (a.v_rows) {
+                    const uint4 t = *(const uint4*)(a.v_rows + (int64_t)item * a.v_row_stride + k);
+                    const uint32_t w4[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        av[2 * q] = __uint_as_float(w4[q] << 16);
+                        av[2 * q + 1] = __uint_as_float(w4[q] & 0xffff0000u);
+                    }
+                } else {
+                    const float4 t0 = *(const float4*)(a.v_partial + (int64_t)item * a.C + k);
+                    const float4 t1 = *(const float4*)(a.v_partial + (int64_t)item * a.C + k + 4);
+                    av[0] = t0.x * a.v_scale; av[1] = t0.y * a.v_scale; av[2] = t0.z * a.v_scale; av[3] = t0.w * a.v_scale;
+                    av[4] = t1.x * a.v_scale; av[5] = t1.y * a.v_scale; av[6] = t1.z * a.v_scale; av[7] = t1.w * a.v_scale;
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (k + q >= c) av[q] = 0.f;
+            }
+        }
+    };
+    // FPF steps of this wavefront in flight: a step's matrix instructions take ~500 cycles, a load a few thousand
+    constexpr int FPF = 6;
+    float av[FPF][8];
+    uint4 bw[FPF];
+#pragma unroll
+    for (int st = 0; st < FPF; ++st)
+        if (wave + 4 * st < nsteps) fetch(wave + 4 * st, av[st], bw[st]);
+    for (int base = wave; base < nsteps; base += 4 * FPF) {
+#pragma unroll
+        for (int st = 0; st < FPF; ++st) {
+            const int step = base + 4 * st;
+            if (step < nsteps) {                 // uniform over the wavefront
+                const uint32_t w4[4] = {bw[st].x, bw[st].y, bw[st].z, bw[st].w};
+                float cv[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) cv[q] = av[st][q];
+                if (step + 4 * FPF < nsteps) fetch(step + 4 * FPF, av[st], bw[st]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(cv[2 * q], __uint_as_float(w4[q] << 16), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(cv[2 * q + 1], __uint_as_float(w4[q] & 0xffff0000u), acc, 0, 0, 0);
+                }
+            }
+        }
+    }
+    // acc[e] = out[item i0 + 8 (e >> 2) + 4 lhi + (e & 3)][output o0 + l32], this wavefront's share of the channels
+    if (wave > 0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[wave - 1][8 * (e >> 2) + 4 * lhi + (e & 3)][l32] = acc[e];
+    }
+    __syncthreads();
+    if (wave == 0 && ook) {
+        const float b = a.bias ? a.bias[o] : 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int r = 8 * (e >> 2) + 4 * lhi + (e & 3);
+            const int it = i0 + r;
+            if (it >= a.items) continue;
+            const float v = ((acc[e] + red[0][r][l32]) + red[1][r][l32]) + red[2][r][l32] + b;
+            const int row = a.out_index ? a.out_index[it] : it;
+            a.out[(int64_t)row * a.out_ld + o] = v;
+        }
+    }
+}
+
 }  // namespace
 
 int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t kind, hipStream_t s) {
@@ -235,6 +335,17 @@ int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t k
     const unsigned gy = (unsigned)((a.items + TI - 1) / TI);
     ProfScope prof(kind, s);
     const bool vec = (a.C % 8) == 0 && (a.w_ld % 8) == 0 && (a.v_rows == nullptr || (a.v_row_stride % 4) == 0);
+    static const int use_mfma = [] {
+        const char* e = getenv("DSNET_FC_MFMA");        // tuning knob: 0 keeps the classifier on the vector kernel
+        return e ? atoi(e) : 1;
+    }();
+    if (use_mfma && vec && w_bf16 && !acc_f64 && a.relu == 0 && (a.v_rows ? (a.v_row_stride % 8) == 0 : a.splits == 1) &&
+        a.items >= 32) {
+        const dim3 grid((unsigned)((a.n_out + 31) / 32), (unsigned)((a.items + 31) / 32));
+        hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(256), 0, s, a);
+        DS_CHECK_LAUNCH("fc (matrix cores)");
+        return DS_OK;
+    }
     if (vec) {
         // narrow output tiles when 64-wide ones would leave most compute units without a workgroup
         const bool narrow = (long long)((a.n_out + 63) / 64) * gy < 256;
