@@ -326,6 +326,97 @@ __global__ __launch_bounds__(256) void fc_mfma_kernel(const FcArgs a) {
     }
 }
 
+// Matrix-core variant for the hidden layer of the gate (fp32 weights, fp64 accumulation over the pool's partial
+// sums): v_mfma_f64_16x16x4_f64 on a tile of 16 items x 16 outputs per workgroup, the reduction dealt to the four
+// wavefronts in interleaved 16-channel steps and their tiles added in wavefront order.  Lane (i, kq) of a wavefront
+// feeds item i / output i and the channels k + 4 kq .. k + 4 kq + 3 of a step, one matrix instruction per channel.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void fc_mfma64_kernel(const FcArgs a) {
+    __shared__ double red[3][16][17];
+    __shared__ int cs[16];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l16 = lane & 15, kq = lane >> 4;
+    const int o0 = blockIdx.x * 16, i0 = blockIdx.y * 16;
+    if (tid < 16) {
+        const int item = i0 + tid;
+        cs[tid] = item < a.items ? (a.c_item ? a.c_item[item] : a.C) : 0;
+    }
+    __syncthreads();
+    int cmax = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) cmax = max(cmax, cs[i]);
+    const int item = i0 + l16, c = cs[l16];
+    const int o = o0 + l16;
+    const bool ook = o < a.n_out;
+    const float* wrow = (const float*)a.w + (int64_t)(ook ? o : 0) * a.w_ld;
+    const int nsteps = (cmax + 15) / 16;
+    f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
+    auto fetch = [&](int step, double (&av)[4], float4& bw) {
+        const int k = step * 16 + 4 * kq;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) av[q] = 0.0;
+        bw = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < cmax) {                       // cmax <= C, C % 4 == 0: the 4 channels are inside the row
+            if (ook) bw = *(const float4*)(wrow + k);
+            if (k < c) {
+                float4 t[POOL_SPLIT_MAX];
+#pragma unroll
+                for (int sp = 0; sp < POOL_SPLIT_MAX; ++sp) {
+                    const int q = sp < a.splits ? sp : a.splits - 1;
+                    t[sp] = *(const float4*)(a.v_partial + ((int64_t)item * a.splits + q) * a.C + k);
+                }
+#pragma unroll
+                for (int sp = 0; sp < POOL_SPLIT_MAX; ++sp)
+                    if (sp < a.splits) {
+                        av[0] += t[sp].x; av[1] += t[sp].y; av[2] += t[sp].z; av[3] += t[sp].w;
+                    }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) av[q] = k + q < c ? (double)(float)(av[q] * (double)a.v_scale) : 0.0;
+            }
+        }
+    };
+    constexpr int FPF = 4;
+    double av[FPF][4];
+    float4 bw[FPF];
+#pragma unroll
+    for (int st = 0; st < FPF; ++st)
+        if (wave + 4 * st < nsteps) fetch(wave + 4 * st, av[st], bw[st]);
+    for (int base = wave; base < nsteps; base += 4 * FPF) {
+#pragma unroll
+        for (int st = 0; st < FPF; ++st) {
+            const int step = base + 4 * st;
+            if (step < nsteps) {                 // uniform over the wavefront
+                const double cv[4] = {av[st][0], av[st][1], av[st][2], av[st][3]};
+                const double cw[4] = {(double)bw[st].x, (double)bw[st].y, (double)bw[st].z, (double)bw[st].w};
+                if (step + 4 * FPF < nsteps) fetch(step + 4 * FPF, av[st], bw[st]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(cv[q], cw[q], acc, 0, 0, 0);
+            }
+        }
+    }
+    // acc[e] = out[item i0 + 4 e + kq][output o0 + l16] (the fp64 tile interleaves its rows over the lane quarters),
+    // this wavefront's share of the channels
+    if (wave > 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[wave - 1][4 * e + kq][l16] = acc[e];
+    }
+    __syncthreads();
+    if (wave == 0 && ook) {
+        const double b = a.bias ? (double)a.bias[o] : 0.0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r = 4 * e + kq;
+            const int it = i0 + r;
+            if (it >= a.items) continue;
+            double v = ((acc[e] + red[0][r][l16]) + red[1][r][l16]) + red[2][r][l16] + b;
+            if (a.relu == 1 && v < 0.0) v = 0.0;
+            else if (a.relu == 2) v = 1.0 + tanh(v);
+            const int row = a.out_index ? a.out_index[it] : it;
+            a.out[(int64_t)row * a.out_ld + o] = (float)v;
+        }
+    }
+}
+
 }  // namespace
 
 int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t kind, hipStream_t s) {
@@ -344,6 +435,12 @@ int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t k
         const dim3 grid((unsigned)((a.n_out + 31) / 32), (unsigned)((a.items + 31) / 32));
         hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(256), 0, s, a);
         DS_CHECK_LAUNCH("fc (matrix cores)");
+        return DS_OK;
+    }
+    if (use_mfma && vec && !w_bf16 && acc_f64 && !a.v_rows && a.items >= 16) {
+        const dim3 grid((unsigned)((a.n_out + 15) / 16), (unsigned)((a.items + 15) / 16));
+        hipLaunchKernelGGL(fc_mfma64_kernel, grid, dim3(256), 0, s, a);
+        DS_CHECK_LAUNCH("fc (fp64 matrix cores)");
         return DS_OK;
     }
     if (vec) {
