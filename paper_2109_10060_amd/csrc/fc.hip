@@ -227,13 +227,14 @@ __global__ __launch_bounds__(256) void fc_tile_vec_kernel(const FcArgs a) {
 }
 
 // Matrix-core variant for the classifier (bf16 weights, fp32 pooled vector or bf16 rows, fp32 accumulation, no
-// activation, one partial sum per channel): v_mfma_f32_32x32x2_f32 on a tile of 32 items x 32 outputs.  The four
+// activation, one partial sum per channel): v_mfma_f32_32x32x2_f32 on a tile of 32 items x 32 outputs.  The
 // wavefronts of a workgroup take interleaved 16-channel steps of the reduction and their tiles are added in
 // wavefront order, so the result does not depend on timing.  Within a step the lower half of the lanes feeds channels
 // k .. k+7 and the upper half k+8 .. k+15 (one matrix instruction per channel pair), so a lane loads 8 consecutive
 // channels of its item and of its output's weight row.  Channels at or beyond the item's width enter as zeros.
-__global__ __launch_bounds__(256) void fc_mfma_kernel(const FcArgs a) {
-    __shared__ float red[3][32][33];
+constexpr int FC_NW = 8;   // wavefronts per workgroup of the classifier kernel
+__global__ __launch_bounds__(64 * FC_NW) void fc_mfma_kernel(const FcArgs a) {
+    __shared__ float red[FC_NW - 1][32][33];
     __shared__ int cs[32];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int o0 = blockIdx.x * 32, i0 = blockIdx.y * 32;
@@ -282,22 +283,22 @@ __global__ __launch_bounds__(256) void fc_mfma_kernel(const FcArgs a) {
         }
     };
     // FPF steps of this wavefront in flight: a step's matrix instructions take ~500 cycles, a load a few thousand
-    constexpr int FPF = 6;
+    constexpr int FPF = 4;
     float av[FPF][8];
     uint4 bw[FPF];
 #pragma unroll
     for (int st = 0; st < FPF; ++st)
-        if (wave + 4 * st < nsteps) fetch(wave + 4 * st, av[st], bw[st]);
-    for (int base = wave; base < nsteps; base += 4 * FPF) {
+        if (wave + FC_NW * st < nsteps) fetch(wave + FC_NW * st, av[st], bw[st]);
+    for (int base = wave; base < nsteps; base += FC_NW * FPF) {
 #pragma unroll
         for (int st = 0; st < FPF; ++st) {
-            const int step = base + 4 * st;
+            const int step = base + FC_NW * st;
             if (step < nsteps) {                 // uniform over the wavefront
                 const uint32_t w4[4] = {bw[st].x, bw[st].y, bw[st].z, bw[st].w};
                 float cv[8];
 #pragma unroll
                 for (int q = 0; q < 8; ++q) cv[q] = av[st][q];
-                if (step + 4 * FPF < nsteps) fetch(step + 4 * FPF, av[st], bw[st]);
+                if (step + FC_NW * FPF < nsteps) fetch(step + FC_NW * FPF, av[st], bw[st]);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(cv[2 * q], __uint_as_float(w4[q] << 16), acc, 0, 0, 0);
@@ -319,7 +320,10 @@ __global__ __launch_bounds__(256) void fc_mfma_kernel(const FcArgs a) {
             const int r = 8 * (e >> 2) + 4 * lhi + (e & 3);
             const int it = i0 + r;
             if (it >= a.items) continue;
-            const float v = ((acc[e] + red[0][r][l32]) + red[1][r][l32]) + red[2][r][l32] + b;
+            float v = acc[e];
+#pragma unroll
+            for (int w = 0; w < FC_NW - 1; ++w) v += red[w][r][l32];
+            v += b;
             const int row = a.out_index ? a.out_index[it] : it;
             a.out[(int64_t)row * a.out_ld + o] = v;
         }
@@ -433,7 +437,7 @@ int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t k
     if (use_mfma && vec && w_bf16 && !acc_f64 && a.relu == 0 && (a.v_rows ? (a.v_row_stride % 8) == 0 : a.splits == 1) &&
         a.items >= 32) {
         const dim3 grid((unsigned)((a.n_out + 31) / 32), (unsigned)((a.items + 31) / 32));
-        hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(256), 0, s, a);
+        hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(64 * FC_NW), 0, s, a);
         DS_CHECK_LAUNCH("fc (matrix cores)");
         return DS_OK;
     }
