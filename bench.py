@@ -95,12 +95,101 @@ def cpu_baseline(name, arch, params, imgs, lb, budget_s=15.0):
             "sample": f"first {n} images of the same batch, one by one, float64 numpy ({dt:.1f} s)"}
 
 
+def run_linear(args):
+    """Config 2: the sliced linear sweep (64 images x 197 tokens, embedding slices 192..384, output slices 4x that).
+    A step buckets the images by their slice and runs the one grouped GEMM over the four buckets."""
+    import numpy as np
+    import torch
+    import workloads as WL
+    import paper_2109_10060_amd as ds
+
+    ds.load()
+    dev = "cuda:0"
+    B = 64 if args.batch == 256 else args.batch          # config 2 is defined at 64 images; --batch overrides
+    c = WL.config2(B=B)
+    x = torch.from_numpy(c["x"]).to(dev).to(torch.bfloat16).contiguous()
+    w = torch.from_numpy(c["w"]).to(dev).to(torch.bfloat16).contiguous()
+    bias = torch.from_numpy(c["bias"]).to(dev).contiguous()
+    route = torch.from_numpy(c["route"]).to(dev).contiguous()
+    y = torch.zeros((B, c["N"], 4 * c["K"]), dtype=torch.bfloat16, device=dev)
+
+    def step():
+        perm, _inv, off = ds.ds_route_bucket(route, c["T"])
+        g = ds.make_groups(off, perm, c["k_in"].tolist(), c["k_out"].tolist())
+        ds.ds_sliced_linear(x, w, bias, g, y=y)
+
+    for _ in range(args.warmup):
+        step()
+    ds.ds_profile_reset()
+    every = max(1, args.event_every)
+    sampled = 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        on = (not args.no_kernel_events) and i % every == every // 2
+        if on:
+            ds.ds_profile_enable(True)
+            sampled += 1
+        step()
+        if on:
+            ds.ds_profile_enable(False)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / args.steps
+    prof = ds.ds_profile_read() if sampled else {}
+    k_in = c["k_in"][c["route"]].astype(np.float64)
+    k_out = c["k_out"][c["route"]].astype(np.float64)
+    flops = 2.0 * c["N"] * float(np.sum(k_in * k_out))
+    nbytes = 2.0 * c["N"] * float(np.sum(k_in) + np.sum(k_out)) + 2.0 * float(k_in.max() * k_out.max())
+    roofline = None
+    if prof and prof["gemm"][1]:
+        ms, n = prof["gemm"]
+        tf = flops * sampled / (ms * 1e-3) / 1e12
+        gbs = nbytes * sampled / (ms * 1e-3) / 1e9
+        # 240 FLOP per byte: below the ridge, so the bound that applies is HBM; both views are given
+        roofline = {"kernel": "gemm_kernel", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": gbs / PEAK_HBM_GBS, "traffic": None, "algorithmic_bytes_per_launch": nbytes,
+                    "launches_per_step": n / sampled, "avg_launch_us": ms * 1e3 / n, "steps_sampled": sampled,
+                    "share_of_step": ms / (ms_per_step * sampled),
+                    "mfma_view": {"achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": tf / PEAK_MFMA_BF16_TFLOPS}}
+    out = {
+        "metric": "images/sec at batch 256 (mixed gate widths)", "value": B / (ms_per_step * 1e-3), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config2: sliced linear sweep (197 tokens per image, slices 192/256/320/384 -> 4x), "
+                               "bucket + one grouped GEMM, operands warm in the caches", "batch": B,
+                   "route_histogram": [np.bincount(c["route"], minlength=4).tolist()]},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import ds_oracle as O
+        t1 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t1 < 10.0:             # whole passes over the batch, about 10 s of CPU work
+            for i in range(B):
+                t = int(c["route"][i])
+                O.sliced_linear(c["x"][i][:, :c["k_in"][t]], c["w"], c["bias"], int(c["k_out"][t]))
+            n += B
+        dt = time.perf_counter() - t1
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        out["cpu_baseline"] = {"value": n / dt, "unit": "images/s", "cores": int(threads), "kind": "oracle",
+                               "sample": f"{n // B} passes over the same {B} images, one by one, float64 numpy ({dt:.1f} s)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp", "resnet_pp"])
+    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp", "resnet_pp", "linear"])
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -113,6 +202,9 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
+
+    if args.workload == "linear" and not args.copy_calibration:
+        return run_linear(args)
 
     import numpy as np
     import torch
