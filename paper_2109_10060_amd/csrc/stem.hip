@@ -68,7 +68,16 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
     constexpr int W_LD = KP + 8, TH = 8, TW = 16, PR = 2 * TH + KS - 2, PC = 40, CBASE = 4 - PAD - 1;
     __shared__ __attribute__((aligned(16))) bf16_t Wl[COUT * W_LD];
     __shared__ __attribute__((aligned(16))) bf16_t patch[3 * PR * PC];
+    // output tile, one row of S_LD channels per pixel: a lane finishes runs of four channels of its own pixel (8-byte
+    // writes), then the tile leaves as 16-byte pieces, 16 consecutive pixels of a map row making one contiguous run
+    constexpr int S_LD = COUT + 8;
+    __shared__ __attribute__((aligned(16))) bf16_t stile[TH * TW * S_LD];
+    __shared__ __attribute__((aligned(16))) float scl[COUT], shl[COUT];
     const int tid = threadIdx.x;
+    if (tid < COUT) {
+        scl[tid] = tid < cout ? scale[tid] : 0.f;
+        shl[tid] = tid < cout ? shift[tid] : 0.f;
+    }
     // filter bank: Wl[n][(c*KS + u)*VP + e] = w[u][e-1][c][n] for 1 <= e <= KS, else 0
     for (int i = tid; i < COUT * KP; i += 256) {
         const int n = i / KP, k = i - n * KP;
@@ -80,12 +89,7 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
     }
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int py = wave * 2 + (l32 >> 4), px = l32 & 15;
-    float sc[NTILES], sh[NTILES];
-#pragma unroll
-    for (int t = 0; t < NTILES; ++t) {
-        sc[t] = t * 32 + l32 < cout ? scale[t * 32 + l32] : 0.f;
-        sh[t] = t * 32 + l32 < cout ? shift[t * 32 + l32] : 0.f;
-    }
+    const int chunks = cout >> 3;                       // 16-byte pieces per output pixel
     PatchLoader<PR, PC, 256, 4> pl;
     pl.init(tid, H, W);
     auto fetch = [&](int tile) {
@@ -125,19 +129,29 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
             for (int t = 0; t < NTILES; ++t) {
                 const bf16x8_t bfr = *(const bf16x8_t*)(Wl + (t * 32 + l32) * W_LD + kbase);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.v, bfr, acc[t], 0, 0, 0);
+                // filters as the row operand: the accumulator holds this lane's pixel (column l32) and channels
+                // 32 t + 8 g + 4 lhi + 0..3 in elements 4 g .. 4 g + 3
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af.v, acc[t], 0, 0, 0);
             }
         }
+        // batch-norm, ReLU, bf16 rounding into the tile
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int i = 8 * (e >> 2) + 4 * lhi + (e & 3);
-            const int oy = oy0 + wave * 2 + (i >> 4), ox = ox0 + (i & 15);
-            if (oy < Ho && ox < Wo) {
-                bf16_t* op = y + (((int64_t)slot * Ho + oy) * Wo + ox) * cout + l32;
+        for (int t = 0; t < NTILES; ++t)
 #pragma unroll
-                for (int t = 0; t < NTILES; ++t)
-                    if (t * 32 + l32 < cout) op[t * 32] = f2bf(fmaxf(acc[t][e] * sc[t] + sh[t], 0.f));
+            for (int g = 0; g < 4; ++g) {
+                const int ch = t * 32 + g * 8 + lhi * 4;
+                const float4 s4 = *(const float4*)(scl + ch), h4 = *(const float4*)(shl + ch);
+                uint2 o;
+                o.x = f2bf2(fmaxf(acc[t][4 * g] * s4.x + h4.x, 0.f), fmaxf(acc[t][4 * g + 1] * s4.y + h4.y, 0.f));
+                o.y = f2bf2(fmaxf(acc[t][4 * g + 2] * s4.z + h4.z, 0.f), fmaxf(acc[t][4 * g + 3] * s4.w + h4.w, 0.f));
+                *(uint2*)(stile + (wave * 32 + l32) * S_LD + ch) = o;
             }
+        __syncthreads();
+        for (int c = tid; c < TH * TW * chunks; c += 256) {
+            const int pix = c / chunks, ch = (c - pix * chunks) * 8;
+            const int oy = oy0 + (pix >> 4), ox = ox0 + (pix & 15);
+            if (oy < Ho && ox < Wo)
+                *(uint4*)(y + (((int64_t)slot * Ho + oy) * Wo + ox) * cout + ch) = *(const uint4*)(stile + pix * S_LD + ch);
         }
     }
 }
@@ -316,7 +330,7 @@ int32_t ds_launch_stem_mfma(const bf16_t* img, const int32_t* index, bf16_t* y, 
                             int32_t pad, int32_t Cout, hipStream_t s) {
     if (stride != 2 || (W % 4) != 0) return DS_EUNSUPPORTED;
     const int Ho = (H + 2 * pad - K) / 2 + 1, Wo = (W + 2 * pad - K) / 2 + 1;
-    if (Cout < 1 || Cout > 64) return DS_EUNSUPPORTED;
+    if (Cout < 8 || Cout > 64 || (Cout % 8) != 0) return DS_EUNSUPPORTED;  // the tile leaves in 8-channel pieces
     if (K == 7 && pad == 3 && Cout > 32) return launch_stem<7, 3, 8, 2>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, Cout, s);
     if (K == 7 && pad == 3) return launch_stem<7, 3, 8, 1>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, Cout, s);
     if (K == 3 && pad == 1 && Cout > 32) return launch_stem<3, 1, 4, 2>(img, index, y, w, scale, shift, B, H, W, Ho, Wo, Cout, s);
