@@ -24,44 +24,51 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16 matrix-core peak of MI355X
 PEAK_HBM_GBS = 8000.0
 
 
-def build_workload(name: str, B: int):
+def build_workload(name: str, B: int, mix: str = "uniform"):
     import numpy as np
     import workloads as WL
     S = WL.BASE_SEED
+
+    def bias(seed, T, amp=4.0, late=False):
+        # "skewed": half of the batch takes the smallest route at an early (or only) gate and the
+        # largest route at a late gate; the other half stays spread over all routes
+        favour = -1 if mix == "uniform" else (T - 1 if late else 0)
+        return WL.seeded_logit_bias(seed, B, T, amp=amp, favour=favour)
+
     if name == "mbnet":
         arch = WL.mbnet_arch()
         params = WL.mbnet_params(arch, S + 3)
-        lb = WL.seeded_logit_bias(S + 203, B, arch["T"])[None]
+        lb = bias(S + 203, arch["T"])[None]
         label = "config3: DS-MBNet (MobileNetV1-shaped, 14 width routes), bf16"
     elif name == "mbnet_pp":
         arch = WL.mbnet_pp_arch()
         params = WL.mbnet_params(arch, S + 8)
-        lb = WL.seeded_logit_bias(S + 208, B, arch["T"])[None]
+        lb = bias(S + 208, arch["T"])[None]
         label = "DS-MBNet++ (12 routes over channels [288:640:32] / [800:1152:32] and depthwise kernel size 3/5/7), bf16"
     elif name == "resnet":
         arch = WL.resnet_arch()
         params = WL.resnet_params(arch, S + 4)
-        lb = np.stack([WL.seeded_logit_bias(S + 204 + s, B, 4, amp=16.0) for s in range(4)])
+        lb = np.stack([bias(S + 204 + s, 4, amp=16.0, late=s >= 2) for s in range(4)])
         label = "config4: DS-ResNet (ResNet-50-shaped, 4 gates x 4 width ratios), bf16"
     elif name == "resnet_pp":
         arch = WL.resnet_arch(blocks=(3, 4, 8, 3), routes="pp")
         params = WL.resnet_params(arch, S + 9)
-        lb = np.stack([WL.seeded_logit_bias(S + 209 + s, B, 9, amp=16.0) for s in range(4)])
+        lb = np.stack([bias(S + 209 + s, 9, amp=16.0) for s in range(4)])
         label = "DS-ResNet++ (one gate, 9 paths over stage widths [128:256:32] .. [1024:2048:128] and block counts), bf16"
     elif name == "vit":
         arch = WL.vit_arch()
         params = WL.vit_params(arch, S + 5)
-        lb = WL.seeded_logit_bias(S + 205, B, arch["T"])[None]
+        lb = bias(S + 205, arch["T"])[None]
         label = "config5: DS-ViT (DeiT-S-shaped, 48 routes over embed/heads/MLP), bf16"
     elif name == "vit_stem":
         arch = WL.vit_arch(stem_dim=24, patch=8)
         params = WL.vit_params(arch, S + 6)
-        lb = WL.seeded_logit_bias(S + 206, B, arch["T"], amp=16.0)[None]
+        lb = bias(S + 206, arch["T"], amp=16.0)[None]
         label = "DS-ViT++ stem (conv + 2 depthwise-separable blocks at 24 channels, gate on its map) + config5's network, bf16"
     elif name == "vit_pp":
         arch = WL.vit_arch(embed=416, heads=8, head_dim=48, mlp=1664, depth=14, routes="pp", stem_dim=24, patch=8)
         params = WL.vit_params(arch, S + 7)
-        lb = WL.seeded_logit_bias(S + 207, B, arch["T"], amp=16.0)[None]
+        lb = bias(S + 207, arch["T"], amp=16.0)[None]
         label = ("DS-ViT++ supernet (stem, embed 192..416, 4..8 heads of 48, MLP ratio 3..4, depth 12..14; "
                  "8 nested routes), bf16")
     else:
@@ -191,6 +198,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp", "resnet_pp", "linear"])
     ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--mix", default="uniform", choices=["uniform", "skewed"],
+                    help="route mix: every route about equally often (default), or half of the batch on the smallest "
+                         "route at early gates / the largest route at late gates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernel launches with HIP events (roofline is then null)")
@@ -223,7 +233,7 @@ def main():
         print(json.dumps({"copy_bytes": n, "repeats": 5}))
         return
     B = args.batch
-    arch, params, imgs, lb, label = build_workload(args.workload, B)
+    arch, params, imgs, lb, label = build_workload(args.workload, B, args.mix)
     net = {"mbnet": ds.build_mbnet, "mbnet_pp": ds.build_mbnet, "resnet": ds.build_resnet, "resnet_pp": ds.build_resnet, "vit": ds.build_vit,
            "vit_stem": ds.build_vit, "vit_pp": ds.build_vit}[args.workload](arch, params, dev)
     x = torch.from_numpy(imgs).to(dev).to(torch.bfloat16).contiguous()
@@ -312,7 +322,7 @@ def main():
         "metric": "images/sec at batch 256 (mixed gate widths)", "value": B / (ms_per_step * 1e-3), "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": label, "batch": B, "image": arch["image"],
+        "config": {"workload": label, "batch": B, "image": arch["image"], "route_mix": args.mix,
                    "route_histogram": [np.bincount(r, minlength=net.T).tolist() for r in rt]},
         "roofline": roofline,
         "kernels": kernels,

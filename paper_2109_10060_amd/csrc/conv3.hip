@@ -28,8 +28,10 @@ constexpr int SMEM = MAIN_BYTES + TABLE_BYTES;
 constexpr int NR = (RMAX * 4 + NT - 1) / NT;   // 16-byte patch loads per thread and chunk
 
 // chunk c of a 64-byte LDS row r is stored at position c ^ sw(r): any run of consecutive rows read
-// with one chunk column spreads over the banks, whatever row the run starts at
-__device__ __forceinline__ int sw(int r) { return (r >> 1) & 3; }
+// with one chunk column spreads over the banks, whatever row the run starts at, for access groups of
+// 8 lanes (128 bytes) and of 16 lanes (256 bytes) alike -- a key of (r >> 1) & 3 serves only the former
+// and cost 40 % of the LDS cycles in conflicts
+__device__ __forceinline__ int sw(int r) { return ((r >> 1) ^ (r >> 2)) & 3; }
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
 template <bool HASR>

@@ -60,14 +60,19 @@ def bn_tables(d: Draw, T: int, C: int) -> dict:
     }
 
 
-def seeded_logit_bias(seed: int, B: int, T: int, amp: float = 4.0) -> np.ndarray:
+def seeded_logit_bias(seed: int, B: int, T: int, amp: float = 4.0, favour: int = -1, share: float = 0.5) -> np.ndarray:
     """Per-sample additive gate logits: small noise plus `amp` on a seeded target route,
-    so that every route occurs about B/T times and margins are far above rounding noise."""
+    so that every route occurs about B/T times and margins are far above rounding noise.
+    With favour >= 0 the first `share` of a seeded order of the samples targets route `favour`
+    instead (a skewed mix: about share + (1 - share)/T of the batch on one route)."""
     d = Draw(seed)
     noise = d.normal((B, T), std=0.1)
     pi = d.permutation(B)
+    target = (pi % T).astype(np.int64)
+    if favour >= 0:
+        target[pi < int(round(share * B))] = favour
     bias = noise.copy()
-    bias[np.arange(B), (pi % T).astype(np.int64)] += float(amp)
+    bias[np.arange(B), target] += float(amp)
     return bias.astype(np.float32)
 
 
