@@ -86,19 +86,23 @@ constexpr int DW_PX_S2 = 2;   // output pixels per thread at stride 2 (4 at stri
 // Same layer, PX consecutive output pixels of a row per thread: the 3 x (3 + 3 STRIDE) input window
 // and the 9 filter chunks are loaded once for 4 outputs, which cuts the load instructions per
 // output from 18 to 6.75 (stride 1) / 9 (stride 2).
-// grid (ceil(Ho * ceil(Wo/4) * C/8 / 256), B)
+// one-dimensional grid of ceil(Ho * ceil(Wo/PX) * C/8 / 256) tiles x (B rounded up to 8) slots, slot fastest
 template <int STRIDE, int PX>
 __global__ __launch_bounds__(256, 3) void dwconv4_kernel(ActView x, ActView y, const bf16_t* w, const float* scale,
                                                       const float* shift, int tab_ld, const int32_t* slot_group,
                                                       const GroupTable gt, int C, int H, int W, int Ho, int Wo,
-                                                      int act) {
+                                                      int act, int B, int slots8) {
     constexpr int NCOL = (PX - 1) * STRIDE + 3;
-    const int slot = blockIdx.y;
+    // The slot is the fastest index of the launch order (padded to a multiple of 8): workgroups go to the 8 dies
+    // in turn, so every tile of one sample lands on the same die and the rows that vertically neighbouring
+    // tiles share are served by that die's L2 instead of being fetched from memory once per die.
+    const int slot = blockIdx.x % slots8;
+    if (slot >= B) return;
     const int g = slot_group ? slot_group[slot] : 0;
     const int c = gt.k_in[g];
     const int chunks = c >> 3;
     const int xgroups = (Wo + PX - 1) / PX;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int idx = (blockIdx.x / slots8) * 256 + threadIdx.x;
     if (idx >= Ho * xgroups * chunks) return;
     const int pg = idx / chunks, ch = (idx - pg * chunks) * 8;
     const int oy = pg / xgroups, ox0 = (pg - oy * xgroups) * PX;
@@ -189,7 +193,7 @@ __global__ __launch_bounds__(256, 3) void dwconv4_kernel(ActView x, ActView y, c
 // ---- depthwise convolution with a spatially sliced filter (Section 3.2, Eq. 11-13) --------------
 // The filter is stored once as KS x KS taps ([KS][KS][C]); a route uses the centred k x k block of it
 // (Eq. 11), every l-th tap of that block at dilation l (Eq. 12) and its own padding (Eq. 13), which also
-// sets its output resolution.  One slot per blockIdx.y, so the route's tap count N is uniform over the
+// sets its output resolution.  One slot per workgroup, so the route's tap count N is uniform over the
 // workgroup and picks a fully unrolled row routine: the N input pixels and N filter taps of a row are
 // all requested (branch-free buffer loads, zeros outside the image) before the first multiply.
 // A lane owns 8 channels of one output pixel; the output is packed [Ho_t][Wo_t][width] per slot.
@@ -276,8 +280,10 @@ __global__ __launch_bounds__(256) void dwconv_spatial_kernel(ActView x, ActView 
                                                              const float* scale, const float* shift, int tab_ld,
                                                              const int32_t* slot_group, const GroupTable gt,
                                                              const SpatialTable st, int C, int H, int W, int stride,
-                                                             int act) {
-    const int slot = blockIdx.y;
+                                                             int act, int B, int slots8) {
+    // slot-fastest launch order, as in dwconv4_kernel: a sample's tiles share one die's L2
+    const int slot = blockIdx.x % slots8;
+    if (slot >= B) return;
     const int g = slot_group ? slot_group[slot] : 0;
     const int c = gt.k_in[g];
     const int chunks = c >> 3;
@@ -288,7 +294,7 @@ __global__ __launch_bounds__(256) void dwconv_spatial_kernel(ActView x, ActView 
     const bool wide = STRIDE > 0 && l == 1;                     // uniform over the workgroup
     const int px = wide ? PX : 1;
     const int xgroups = (Wo + px - 1) / px;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int idx = (blockIdx.x / slots8) * 256 + threadIdx.x;
     if (Ho <= 0 || Wo <= 0 || idx >= Ho * xgroups * chunks) return;
     const int pg = idx / chunks, ch = (idx - pg * chunks) * 8;
     const int oy = pg / xgroups, ox0 = (pg - oy * xgroups) * px;
@@ -692,14 +698,17 @@ int32_t ds_launch_dwconv(ActView x, ActView y, const bf16_t* w, const float* sca
     const int px = stride == 1 ? 4 : DW_PX_S2;
     const int64_t n = (int64_t)Ho * ((Wo + px - 1) / px) * (cmax / 8);
     if (n <= 0) return DS_OK;
-    dim3 grid((unsigned)((n + 255) / 256), (unsigned)B);
+    const int slots8 = (B + 7) & ~7;
+    const int64_t nwg = ((n + 255) / 256) * slots8;
+    if (nwg > 0x7fffffffll) DS_FAIL(DS_ESHAPE, "depthwise conv: %lld workgroups exceed the launch limit", (long long)nwg);
+    dim3 grid((unsigned)nwg);
     ProfScope prof(DS_K_DWCONV, s);
     if (stride == 1)
         hipLaunchKernelGGL((dwconv4_kernel<1, 4>), grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
-                           Ho, Wo, act);
+                           Ho, Wo, act, B, slots8);
     else
         hipLaunchKernelGGL((dwconv4_kernel<2, DW_PX_S2>), grid, dim3(256), 0, s, x, y, w, scale, shift, tab_ld, slot_group, gt, C, H, W,
-                           Ho, Wo, act);
+                           Ho, Wo, act, B, slots8);
     DS_CHECK_LAUNCH("depthwise conv");
     return DS_OK;
 }
@@ -719,17 +728,20 @@ int32_t ds_launch_dwconv_spatial(ActView x, ActView y, const bf16_t* w, int32_t 
         nmax = n > nmax ? n : nmax;
     }
     if (nmax <= 0) return DS_OK;
-    dim3 grid((unsigned)((nmax + 255) / 256), (unsigned)B);
+    const int slots8 = (B + 7) & ~7;
+    const int64_t nwg = ((nmax + 255) / 256) * slots8;
+    if (nwg > 0x7fffffffll) DS_FAIL(DS_ESHAPE, "spatial depthwise conv: %lld workgroups exceed the launch limit", (long long)nwg);
+    dim3 grid((unsigned)nwg);
     ProfScope prof(DS_K_DWCONV, s);
     if (stride == 1)
         hipLaunchKernelGGL((dwconv_spatial_kernel<1, DWS_PX>), grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld,
-                           slot_group, gt, st, C, H, W, stride, act);
+                           slot_group, gt, st, C, H, W, stride, act, B, slots8);
     else if (stride == 2)
         hipLaunchKernelGGL((dwconv_spatial_kernel<2, DWS_PX>), grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld,
-                           slot_group, gt, st, C, H, W, stride, act);
+                           slot_group, gt, st, C, H, W, stride, act, B, slots8);
     else
         hipLaunchKernelGGL((dwconv_spatial_kernel<0, 1>), grid, dim3(256), 0, s, x, y, w, KS, scale, shift, tab_ld,
-                           slot_group, gt, st, C, H, W, stride, act);
+                           slot_group, gt, st, C, H, W, stride, act, B, slots8);
     DS_CHECK_LAUNCH("spatial depthwise conv");
     return DS_OK;
 }

@@ -57,11 +57,22 @@ struct PatchLoader {
     }
 };
 
+// Tile order.  Workgroups are dealt to the 8 dies in turn (blockIdx.x % 8), each die with an L2 of its own, and the
+// input patches of neighbouring tiles overlap (the filter's halo, and 64-byte lines shared across a tile edge): with
+// tiles walked in plain order every die fetches those lines from memory for itself, about four times the image in
+// all.  With by_die (grid and batch multiples of 8) walk index v stands for tile (v / 8) % tiles_per_image of sample
+// v % 8 + 8 * (v / 8 / tiles_per_image), so every tile of one sample is worked on by the same die.
+__device__ __forceinline__ int tile_of(int v, int tiles_per_image, bool by_die) {
+    if (!by_die) return v;
+    const int vq = v >> 3, s8 = vq / tiles_per_image;
+    return ((v & 7) + 8 * s8) * tiles_per_image + (vq - s8 * tiles_per_image);
+}
+
 template <int KS, int PAD, int VP, int NTILES>
 __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict__ img, const int32_t* index,
                                                         bf16_t* __restrict__ y, const bf16_t* __restrict__ w,
                                                         const float* scale, const float* shift, int H, int W, int Ho,
-                                                        int Wo, int tiles_x, int tiles_y, int total_tiles, int cout) {
+                                                        int Wo, int tiles_x, int tiles_y, int total_tiles, int cout, int by_die) {
     // cout <= COUT filters are stored ([taps][cout]) and written (cout channels per pixel); the matrix
     // columns beyond them carry zero weights and are dropped
     constexpr int COUT = NTILES * 32, PAIRS = 3 * KS, KP = ((PAIRS * VP + 15) / 16) * 16, KSTEPS = KP / 16;
@@ -99,7 +110,8 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(const bf16_t* __restrict
         const int sample = __builtin_amdgcn_readfirstlane(index ? index[slot] : slot);
         pl.issue(img, sample, ty * TH * 2 - PAD, tx * TW * 2, H, W);
     };
-    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+    for (int v = blockIdx.x; v < total_tiles; v += gridDim.x) {
+        const int tile = tile_of(v, tiles_x * tiles_y, by_die);
         const int slot = tile / (tiles_x * tiles_y);
         const int t2 = tile - slot * tiles_x * tiles_y;
         const int ty = t2 / tiles_x, tx = t2 - ty * tiles_x;
@@ -168,7 +180,7 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
                                                         bf16_t* __restrict__ y, const bf16_t* __restrict__ w,
                                                         const float* scale, const float* shift, int H, int W, int Ho,
                                                         int Wo, int Hp, int Wp, int tiles_x, int tiles_y,
-                                                        int total_tiles) {
+                                                        int total_tiles, int by_die) {
     constexpr int KS = 7, PAD = 3, VP = 8, NTH = 320;
     constexpr int COUT = NTILES * 32, PAIRS = 3 * KS, KP = ((PAIRS * VP + 15) / 16) * 16, KSTEPS = KP / 16;
     constexpr int W_LD = KP + 8, CH = 9, CW = 17, NPIX = CH * CW, PR = 2 * CH + KS - 2, PC = 48, CBASE = 2;
@@ -211,8 +223,9 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
         const int sample = __builtin_amdgcn_readfirstlane(index ? index[slot] : slot);
         pl.issue(img, sample, (8 * ty - 1) * 2 - PAD, (16 * tx - 1) * 2, H, W);
     };
-    if ((int)blockIdx.x < total_tiles) fetch(blockIdx.x);
-    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+    if ((int)blockIdx.x < total_tiles) fetch(tile_of(blockIdx.x, tiles_x * tiles_y, by_die));
+    for (int v = blockIdx.x; v < total_tiles; v += gridDim.x) {
+        const int tile = tile_of(v, tiles_x * tiles_y, by_die);
         const int slot = tile / (tiles_x * tiles_y);
         const int t2 = tile - slot * tiles_x * tiles_y;
         const int ty = t2 / tiles_x, tx = t2 - ty * tiles_x;
@@ -221,7 +234,7 @@ __global__ __launch_bounds__(320) void stem_pool_kernel(const bf16_t* __restrict
         __syncthreads();  // filter bank ready / previous patch and conv tile no longer read
         pl.store(patch);
         __syncthreads();
-        if (tile + (int)gridDim.x < total_tiles) fetch(tile + gridDim.x);   // in flight during this tile's arithmetic
+        if (v + (int)gridDim.x < total_tiles) fetch(tile_of(v + gridDim.x, tiles_x * tiles_y, by_die));   // in flight during this tile's arithmetic
         f32x16_t acc[NTILES];
 #pragma unroll
         for (int t = 0; t < NTILES; ++t)
@@ -296,9 +309,10 @@ int32_t launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const bf
     const int tiles_x = (Wo + 15) / 16, tiles_y = (Ho + 7) / 8;
     const long long total = (long long)B * tiles_x * tiles_y;
     const int grid = (int)(total < 256 * 5 ? total : 256 * 5);
+    const int by_die = (B % 8) == 0 && (grid % 8) == 0;
     ProfScope prof(DS_K_STEM, s);
     hipLaunchKernelGGL((stem_mfma_kernel<KS, PAD, VP, NTILES>), dim3(grid), dim3(256), 0, s, img, index, y, w, scale, shift,
-                       H, W, Ho, Wo, tiles_x, tiles_y, (int)total, cout);
+                       H, W, Ho, Wo, tiles_x, tiles_y, (int)total, cout, by_die);
     DS_CHECK_LAUNCH("stem conv (mfma)");
     return DS_OK;
 }
@@ -317,9 +331,10 @@ int32_t ds_launch_stem_pool(const bf16_t* img, const int32_t* index, bf16_t* y, 
     const long long total = (long long)B * tiles_x * tiles_y;
     if (total <= 0) return DS_OK;
     const int grid = (int)(total < 256 * 3 ? total : 256 * 3);
+    const int by_die = (B % 8) == 0 && (grid % 8) == 0;
     ProfScope prof(DS_K_STEM, s);
     hipLaunchKernelGGL((stem_pool_kernel<2>), dim3(grid), dim3(320), 0, s, img, index, y, w, scale, shift, H, W, Ho, Wo, Hp,
-                       Wp, tiles_x, tiles_y, (int)total);
+                       Wp, tiles_x, tiles_y, (int)total, by_die);
     DS_CHECK_LAUNCH("stem conv + max-pool");
     return DS_OK;
 }
