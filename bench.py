@@ -211,7 +211,7 @@ def main():
                     help="only run a plain device copy of MIB mebibytes 5 times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
+        raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (--gpus must be 1)")
 
     if args.workload == "linear" and not args.copy_calibration:
         return run_linear(args)
