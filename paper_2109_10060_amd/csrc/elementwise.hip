@@ -449,9 +449,12 @@ __global__ __launch_bounds__(256) void layernorm_kernel(ActView x, ActView y, co
 
 // Narrow rows (d <= 512): 16 lanes per row, 4 rows per wavefront, so a wavefront keeps four
 // independent rows of loads in flight and the reductions take 4 exchange steps instead of 6.
+// gamma and beta (fp32, four times the bytes of a bf16 row between them) go through LDS once per
+// workgroup instead of through the vector cache once per row.
 __global__ __launch_bounds__(256) void layernorm16_kernel(ActView x, ActView y, const float* gamma,
                                                           const float* beta, float eps, const int32_t* slot_group,
-                                                          const GroupTable gt, int B, int row0, int n_rows) {
+                                                          const GroupTable gt, int B, int row0, int n_rows, int dmax) {
+    __shared__ __attribute__((aligned(16))) float gl[512], bl[512];
     const int r = blockIdx.x * 16 + (threadIdx.x >> 4);
     const int l16 = threadIdx.x & 15;
     const bool live = r < B * n_rows;
@@ -464,6 +467,13 @@ __global__ __launch_bounds__(256) void layernorm16_kernel(ActView x, ActView y, 
     const bf16_t* xr = (const bf16_t*)x.p + (int64_t)xs * x.sample_stride + (int64_t)p * xld;
     bf16_t* yr = (bf16_t*)y.p + (int64_t)ys * y.sample_stride + (int64_t)p * yld;
     constexpr int MAXC = 4;
+    // the affine parameters: one float2 of each per thread (256 threads x 2 = 512 channels), requested with the row
+    const int pc = threadIdx.x * 2;
+    float2 gq = make_float2(0.f, 0.f), bq = make_float2(0.f, 0.f);
+    if (pc < dmax) {
+        gq = *(const float2*)(gamma + pc);
+        bq = *(const float2*)(beta + pc);
+    }
     float v[MAXC][8];
     float s = 0.f;
 #pragma unroll
@@ -475,6 +485,8 @@ __global__ __launch_bounds__(256) void layernorm16_kernel(ActView x, ActView y, 
             for (int i = 0; i < 8; ++i) s += v[k][i];
         }
     }
+    *(float2*)(gl + pc) = gq;
+    *(float2*)(bl + pc) = bq;
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 16);
     const float mu = s / (float)d;
@@ -493,13 +505,16 @@ __global__ __launch_bounds__(256) void layernorm16_kernel(ActView x, ActView y, 
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) q += __shfl_xor(q, o, 16);
     const float rstd = 1.0f / sqrtf(q / (float)d + eps);
+    __syncthreads();
 #pragma unroll
     for (int k = 0; k < MAXC; ++k) {
         const int ch = (k * 16 + l16) * 8;
         if (live && ch < d) {
-            float gm[8], bt[8], o8[8];
-            loadf8(gamma + ch, gm);
-            loadf8(beta + ch, bt);
+            float o8[8];
+            const float4 g0 = *(const float4*)(gl + ch), g1 = *(const float4*)(gl + ch + 4);
+            const float4 b0 = *(const float4*)(bl + ch), b1 = *(const float4*)(bl + ch + 4);
+            const float gm[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+            const float bt[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
             for (int i = 0; i < 8; ++i) o8[i] = (v[k][i] - mu) * rstd * gm[i] + bt[i];
             *(uint4*)(yr + ch) = pack8(o8);
@@ -779,7 +794,7 @@ int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const floa
     for (int t = 0; t < gt.T; ++t) dmax = gt.k_in[t] > dmax ? gt.k_in[t] : dmax;
     if (dmax <= 512) {
         hipLaunchKernelGGL(layernorm16_kernel, dim3((unsigned)((total + 15) / 16)), dim3(256), 0, s, x, y, gamma, beta, eps,
-                           slot_group, gt, B, row0, n_rows);
+                           slot_group, gt, B, row0, n_rows, dmax);
         DS_CHECK_LAUNCH("layernorm");
         return DS_OK;
     }
