@@ -286,6 +286,19 @@ size_t ds_forward_workspace(const ds_net* net, int32_t B);
 int32_t ds_forward(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
                    const float* logit_bias, float* logits, int32_t* routes_out, void* ws,
                    size_t ws_bytes, void* stream);
+/* The same forward pass with the batch run as `parts` (1..4) concurrent pieces: samples are independent (Section 3.1,
+ * Eq. 1: the route and the sliced computation are per input), so the batch is cut into equal shares (rounded up to
+ * a multiple of 8 samples), each share is gated, bucketed and computed on its own — the first on `stream`, the others
+ * on streams the library creates on first use (up to 3 per device, default priority, kept until the process ends) —
+ * and the launch ramps and tails of one share's kernels are filled by the other's.  The side streams start after the
+ * work already queued on `stream` and `stream` continues after them, so to the caller the call is one piece of work
+ * on `stream`.  Arguments, results and errors as ds_forward (every output is per sample, hence identical); ws needs
+ * ds_forward_parts_workspace(net, B, parts) bytes (0 for parts outside 1..4).  parts = 1 is ds_forward.
+ * Calls that overlap in time on one device share the side streams and are serialised by them. */
+size_t ds_forward_parts_workspace(const ds_net* net, int32_t B, int32_t parts);
+int32_t ds_forward_parts(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
+                         const float* logit_bias, float* logits, int32_t* routes_out, void* ws,
+                         size_t ws_bytes, int32_t parts, void* stream);
 
 /* Instrumentation: while recording is on, every kernel launch is bracketed by a pair of HIP
  * events on its stream.  The event packets keep consecutive kernels from overlapping their

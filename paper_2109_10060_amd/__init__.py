@@ -33,7 +33,7 @@ EXPORTS = [
     "ds_gate_double", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
     "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_dwconv_spatial", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
-    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
+    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_forward_parts_workspace", "ds_forward_parts", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
 ]
 
 
@@ -74,7 +74,7 @@ def load(path: Optional[str] = None):
     lib = ctypes.CDLL(path)
     lib.ds_last_error.restype = ctypes.c_char_p
     for name in ("ds_gate_workspace", "ds_sliced_linear_workspace", "ds_sliced_conv_workspace",
-                 "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace", "ds_gate_double_workspace",
+                 "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace", "ds_forward_parts_workspace", "ds_gate_double_workspace",
                  "ds_bn_stats_workspace"):
         getattr(lib, name).restype = ctypes.c_size_t
     _lib = lib
@@ -326,6 +326,23 @@ def ds_forward(net: "Net", images, route_override=None, logit_bias=None, logits=
         ws = net.workspace(B)
     _chk(lib.ds_forward(ctypes.byref(net.c_struct), _ptr(images, torch.bfloat16), B, _ptr(route_override),
                         _ptr(logit_bias), _ptr(logits), _ptr(routes), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return logits, routes
+
+
+def ds_forward_parts(net: "Net", images, parts: int, route_override=None, logit_bias=None, logits=None, routes=None, ws=None):
+    """ds_forward with the batch run as `parts` concurrent pieces (the first on the current stream, the others on
+    streams of the library).  Same results; ws needs net.workspace(B, parts)."""
+    lib = load()
+    B = images.shape[0]
+    if logits is None:
+        logits = torch.empty((B, net.num_classes), dtype=torch.float32, device=images.device)
+    if routes is None:
+        routes = torch.empty((net.n_gates, B), dtype=torch.int32, device=images.device)
+    if ws is None:
+        ws = net.workspace(B, parts)
+    _chk(lib.ds_forward_parts(ctypes.byref(net.c_struct), _ptr(images, torch.bfloat16), B, _ptr(route_override),
+                              _ptr(logit_bias), _ptr(logits), _ptr(routes), _ptr(ws), ctypes.c_size_t(ws.numel()),
+                              int(parts), _stream()))
     return logits, routes
 
 

@@ -346,7 +346,9 @@ void plan_rn(const RnDesc& d, int B, Bump& bp, RnPlan* p) {
     }
 }
 
-int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int B, const int32_t* route_override,
+// Bs: batch stride of the caller's gate-major arrays (route_override, logit_bias, routes_out); B when the whole batch
+// is run as one part
+int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int B, int Bs, const int32_t* route_override,
                    const float* logit_bias, float* logits, int32_t* routes_out, const RnPlan& p, hipStream_t s) {
     const void* const* P = net->params;
     const int T = d.T, G = rn_groups(d);
@@ -372,7 +374,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         const int rin = r;
         const int stride = st > 0 ? 2 : 1;
         const int rout = (rin + 2 - 3) / stride + 1;
-        int32_t* route = routes_out ? routes_out + (size_t)st * B : p.route[st];
+        int32_t* route = routes_out ? routes_out + (size_t)st * Bs : p.route[st];
         // ---- gate on the stage input (previous slot order), routes land in original sample order
         GateArgs g;
         memset(&g, 0, sizeof(g));
@@ -381,9 +383,9 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         g.x_sample_stride = (int64_t)rin * rin * c_prev_full; g.x_ld = 0;
         g.w1 = (const float*)Q[0]; g.b1 = (const float*)Q[1]; g.w2 = (const float*)Q[2]; g.b2 = (const float*)Q[3];
         g.C_mlp = d.hidden[st]; g.T = T;
-        g.logit_bias = logit_bias ? logit_bias + (size_t)st * B * T : nullptr;
+        g.logit_bias = logit_bias ? logit_bias + (size_t)st * Bs * T : nullptr;
         g.out_index = st > 0 ? p.perm[st - 1] : nullptr;
-        g.route_override = route_override ? route_override + (size_t)st * B : nullptr;
+        g.route_override = route_override ? route_override + (size_t)st * Bs : nullptr;
         g.logits = p.gate_logits; g.route = route; g.partial = p.gate_partial;
         if (d.single_gate && st > 0) {
             // the first stage's decision stands: no pooling, no MLP, the route is copied
@@ -393,7 +395,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         RC(ds_launch_gate(g, s));
         Q += 4;
         // ---- bucket by (this stage's route, previous stage's route)
-        const int32_t* route_prev = st > 0 ? (routes_out ? routes_out + (size_t)(st - 1) * B : p.route[st - 1]) : nullptr;
+        const int32_t* route_prev = st > 0 ? (routes_out ? routes_out + (size_t)(st - 1) * Bs : p.route[st - 1]) : nullptr;
         BucketArgs ba = {};
         ba.route = route; ba.lo = pairs ? route_prev : nullptr; ba.mul = pairs ? T : 1; ba.B = B; ba.T = G;
         ba.perm = p.perm[st]; ba.inv_perm = p.inv[st]; ba.offsets = p.offs[st]; ba.slot_group = p.slot_group[st];
@@ -747,10 +749,10 @@ extern "C" size_t ds_forward_workspace(const ds_net* net, int32_t B) {
     return ds_align_up(bp.off, 256);
 }
 
-extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
-                              const float* logit_bias, float* logits, int32_t* routes_out, void* ws, size_t ws_bytes,
-                              void* stream) {
-    const char* who = "ds_forward";
+namespace {
+
+// argument and description checks shared by the entry points; on success *image_elems is the size of one image
+int32_t check_forward(const char* who, const ds_net* net, const void* images, int32_t B, const float* logits) {
     if (!net || !net->ints || !net->params) DS_FAIL(DS_EINVAL, "%s: null net", who);
     if (B < 0) DS_FAIL(DS_EINVAL, "%s: B < 0", who);
     if (B == 0) return DS_OK;
@@ -758,14 +760,9 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
     if (!ds_aligned16(images)) DS_FAIL(DS_EALIGN, "%s: images need 16-byte alignment", who);
     for (int i = 0; i < net->n_params; ++i)
         if (!net->params[i] || !ds_aligned16(net->params[i])) DS_FAIL(DS_EINVAL, "%s: parameter %d null or misaligned", who, i);
-    const size_t need = ds_forward_workspace(net, B);
-    if (need == 0) DS_FAIL(DS_ESHAPE, "%s: network description inconsistent with arch %d", who, net->arch);
-    if (!ws || ws_bytes < need || (((uintptr_t)ws) & 255u)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
-    hipStream_t s = (hipStream_t)stream;
-    Bump bp = {(char*)ws, 0};
+    if (ds_forward_workspace(net, B) == 0) DS_FAIL(DS_ESHAPE, "%s: network description inconsistent with arch %d", who, net->arch);
     if (net->arch == DS_ARCH_MBNET) {
         MbDesc d;
-        MbPlan p;
         parse_mb(net, &d);
         if (d.stem_out % 8) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
         for (int i = 0; i < d.nb * (3 + 2 * d.T); ++i)
@@ -779,21 +776,17 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
                     if (k < 1 || k > kf || !(k & 1)) DS_FAIL(DS_EINVAL, "%s: kernel size %d is no centred block of %d", who, k, kf);
                 }
             }
-        plan_mb(d, B, bp, &p);
-        return forward_mb(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);
+        return DS_OK;
     }
     if (net->arch == DS_ARCH_RESNET) {
         RnDesc d;
-        RnPlan p;
         parse_rn(net, &d);
         if (d.stem_out % 8) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
         for (int i = 0; i < 8 * d.T; ++i)
             if (d.mid[i] % 8) DS_FAIL(DS_EALIGN, "%s: channel counts must be multiples of 8", who);
-        plan_rn(d, B, bp, &p);
-        return forward_rn(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);
+        return DS_OK;
     }
     VitDesc d;
-    VitPlan p;
     parse_vit(net, &d);
     const bool dh_ok = d.dh == 32 || d.dh == 48 || d.dh == 64;
     if (d.stem_dim) {
@@ -813,6 +806,121 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
             DS_FAIL(DS_EALIGN, "%s: route widths must be multiples of 8 within the stored widths", who);
         if (d.rs == 4 && (r[3] < 0 || r[3] > d.depth)) DS_FAIL(DS_EINVAL, "%s: route depth outside 0..%d", who, d.depth);
     }
-    plan_vit(d, B, bp, &p);
-    return forward_vit(net, d, (const bf16_t*)images, B, route_override, logit_bias, logits, routes_out, p, s);
+    return DS_OK;
+}
+
+// Samples b0 .. b0 + Bp - 1 of a batch of Bs (a checked description): the caller's arrays are addressed at the
+// part's offset, the gate-major ones with the whole batch as their stride; ws holds ds_forward_workspace(net, Bp).
+int32_t run_part(const ds_net* net, const bf16_t* images, int b0, int Bp, int Bs, const int32_t* route_override,
+                 const float* logit_bias, float* logits, int32_t* routes_out, void* ws, hipStream_t s) {
+    Bump bp = {(char*)ws, 0};
+    if (net->arch == DS_ARCH_MBNET) {
+        MbDesc d;
+        MbPlan p;
+        parse_mb(net, &d);
+        plan_mb(d, Bp, bp, &p);
+        return forward_mb(net, d, images + (size_t)b0 * 3 * d.image * d.image, Bp, route_override ? route_override + b0 : nullptr,
+                          logit_bias ? logit_bias + (size_t)b0 * d.T : nullptr, logits + (size_t)b0 * d.classes,
+                          routes_out ? routes_out + b0 : nullptr, p, s);
+    }
+    if (net->arch == DS_ARCH_RESNET) {
+        RnDesc d;
+        RnPlan p;
+        parse_rn(net, &d);
+        plan_rn(d, Bp, bp, &p);
+        return forward_rn(net, d, images + (size_t)b0 * 3 * d.image * d.image, Bp, Bs, route_override ? route_override + b0 : nullptr,
+                          logit_bias ? logit_bias + (size_t)b0 * d.T : nullptr, logits + (size_t)b0 * d.classes,
+                          routes_out ? routes_out + b0 : nullptr, p, s);
+    }
+    VitDesc d;
+    VitPlan p;
+    parse_vit(net, &d);
+    plan_vit(d, Bp, bp, &p);
+    return forward_vit(net, d, images + (size_t)b0 * 3 * d.image * d.image, Bp, route_override ? route_override + b0 : nullptr,
+                       logit_bias ? logit_bias + (size_t)b0 * d.T : nullptr, logits + (size_t)b0 * d.classes,
+                       routes_out ? routes_out + b0 : nullptr, p, s);
+}
+
+// side streams and fork / join events of ds_forward_parts, made on first use, one set per device, kept until the
+// process ends (default priority, no device memory)
+constexpr int MAX_PARTS = 4, MAX_DEVICES = 16;
+struct PartStreams {
+    bool ready;
+    hipStream_t side[MAX_PARTS - 1];
+    hipEvent_t fork, join[MAX_PARTS - 1];
+};
+PartStreams g_part_streams[MAX_DEVICES];
+
+int32_t part_streams(PartStreams** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) DS_FAIL(DS_EHIP, "ds_forward_parts: no current device");
+    PartStreams& ps = g_part_streams[dev];
+    if (!ps.ready) {
+        if (hipEventCreateWithFlags(&ps.fork, hipEventDisableTiming) != hipSuccess) DS_FAIL(DS_EHIP, "ds_forward_parts: event creation failed");
+        for (int i = 0; i < MAX_PARTS - 1; ++i)
+            if (hipStreamCreateWithFlags(&ps.side[i], hipStreamNonBlocking) != hipSuccess ||
+                hipEventCreateWithFlags(&ps.join[i], hipEventDisableTiming) != hipSuccess)
+                DS_FAIL(DS_EHIP, "ds_forward_parts: stream creation failed");
+        ps.ready = true;
+    }
+    *out = &ps;
+    return DS_OK;
+}
+
+int part_size(int B, int parts) {          // samples per part: equal shares rounded up to a multiple of 8
+    return (((B + parts - 1) / parts) + 7) & ~7;
+}
+
+}  // namespace
+
+extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
+                              const float* logit_bias, float* logits, int32_t* routes_out, void* ws, size_t ws_bytes,
+                              void* stream) {
+    const char* who = "ds_forward";
+    const int32_t rc = check_forward(who, net, images, B, logits);
+    if (rc || B == 0) return rc;
+    const size_t need = ds_forward_workspace(net, B);
+    if (!ws || ws_bytes < need || (((uintptr_t)ws) & 255u)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    return run_part(net, (const bf16_t*)images, 0, B, B, route_override, logit_bias, logits, routes_out, ws, (hipStream_t)stream);
+}
+
+extern "C" size_t ds_forward_parts_workspace(const ds_net* net, int32_t B, int32_t parts) {
+    if (B <= 0 || parts < 1 || parts > MAX_PARTS) return 0;
+    const int h = part_size(B, parts);
+    const size_t one = ds_forward_workspace(net, h < B ? h : B);
+    return one * (size_t)((B + h - 1) / h);
+}
+
+extern "C" int32_t ds_forward_parts(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
+                                    const float* logit_bias, float* logits, int32_t* routes_out, void* ws, size_t ws_bytes,
+                                    int32_t parts, void* stream) {
+    const char* who = "ds_forward_parts";
+    if (parts < 1 || parts > MAX_PARTS) DS_FAIL(DS_EINVAL, "%s: parts outside 1..%d", who, MAX_PARTS);
+    const int32_t rc = check_forward(who, net, images, B, logits);
+    if (rc || B == 0) return rc;
+    const int h = part_size(B, parts), n = (B + h - 1) / h;
+    const size_t one = ds_forward_workspace(net, h < B ? h : B), need = one * (size_t)n;
+    if (!ws || ws_bytes < need || (((uintptr_t)ws) & 255u)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    hipStream_t s = (hipStream_t)stream;
+    if (n == 1) return run_part(net, (const bf16_t*)images, 0, B, B, route_override, logit_bias, logits, routes_out, ws, s);
+    PartStreams* ps = nullptr;
+    RC(part_streams(&ps));
+    // the side streams start after everything already queued on the caller's stream and the caller's stream continues
+    // after them: to the caller the call is one piece of work on its stream
+    if (hipEventRecord(ps->fork, s) != hipSuccess) DS_FAIL(DS_EHIP, "%s: event record failed", who);
+    int32_t first_err = DS_OK;
+    for (int i = 0; i < n; ++i) {
+        hipStream_t si = i == 0 ? s : ps->side[i - 1];
+        if (i > 0 && hipStreamWaitEvent(si, ps->fork, 0) != hipSuccess) DS_FAIL(DS_EHIP, "%s: stream wait failed", who);
+        const int b0 = i * h, Bp = b0 + h <= B ? h : B - b0;
+        const int32_t r = run_part(net, (const bf16_t*)images, b0, Bp, B, route_override, logit_bias, logits, routes_out,
+                                   (char*)ws + one * (size_t)i, si);
+        if (r && !first_err) first_err = r;
+        if (i > 0) {
+            // joined even after an error, so that no side stream is left running behind the caller's back
+            if (hipEventRecord(ps->join[i - 1], si) != hipSuccess || hipStreamWaitEvent(s, ps->join[i - 1], 0) != hipSuccess)
+                DS_FAIL(DS_EHIP, "%s: join failed", who);
+        }
+    }
+    return first_err;
 }

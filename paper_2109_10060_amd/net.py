@@ -35,12 +35,14 @@ class Net:
                                len(self.tensors), ctypes.cast(self._ptrs, ctypes.POINTER(ctypes.c_void_p)))
         self.device = self.tensors[0].device
 
-    def workspace_bytes(self, B: int) -> int:
+    def workspace_bytes(self, B: int, parts: int = 1) -> int:
         from . import load
-        return int(load().ds_forward_workspace(ctypes.byref(self.c_struct), B))
+        if parts == 1:
+            return int(load().ds_forward_workspace(ctypes.byref(self.c_struct), B))
+        return int(load().ds_forward_parts_workspace(ctypes.byref(self.c_struct), B, parts))
 
-    def workspace(self, B: int) -> torch.Tensor:
-        return torch.empty(max(self.workspace_bytes(B), 256), dtype=torch.uint8, device=self.device)
+    def workspace(self, B: int, parts: int = 1) -> torch.Tensor:
+        return torch.empty(max(self.workspace_bytes(B, parts), 256), dtype=torch.uint8, device=self.device)
 
 
 def _fold(bn, eps, device):

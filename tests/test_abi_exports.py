@@ -90,6 +90,11 @@ def test_host_validation_of_the_spatial_statistics_and_forward_entry_points():
     assert lib.ds_forward(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
     assert lib.ds_forward(ctypes.byref(net), None, -1, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
     assert lib.ds_forward(ctypes.byref(net), None, 0, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_OK
+    assert lib.ds_forward_parts_workspace(ctypes.byref(net), 4, 2) == 0 and lib.ds_forward_parts_workspace(ctypes.byref(net), 4, 5) == 0
+    assert lib.ds_forward_parts(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), 0, None) == ds.DS_EINVAL
+    assert lib.ds_forward_parts(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), 5, None) == ds.DS_EINVAL
+    assert lib.ds_forward_parts(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), 2, None) == ds.DS_EINVAL
+    assert lib.ds_forward_parts(ctypes.byref(net), None, 0, None, None, None, None, None, ctypes.c_size_t(0), 2, None) == ds.DS_OK
 
 
 def test_missing_library_fails_loudly(tmp_path):

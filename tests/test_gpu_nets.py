@@ -370,3 +370,50 @@ def test_single_sample_batches_all_networks(gpu_lib):
     empty = torch.zeros((0, 3, 64, 64), dtype=torch.bfloat16, device=DEV)
     logits, routes = gpu_lib.ds_forward(net, empty, logit_bias=torch.zeros((1, 0, arch["T"]), dtype=torch.float32, device=DEV))
     assert logits.shape == (0, arch["num_classes"]) and routes.shape == (1, 0)
+
+
+# ------------------------------------------------------------------ the batch as concurrent parts
+@pytest.mark.gpu
+@pytest.mark.parametrize("kind", ["resnet", "mbnet", "vit"])
+def test_forward_parts_equals_forward(gpu_lib, kind):
+    """ds_forward_parts cuts the batch into shares that run on streams of the library; every output is per sample,
+    so logits and routes must equal ds_forward's (the gate's pooled sums are split differently for another batch
+    size, hence a rounding-level tolerance on the logits), the caller's gate-major arrays are addressed with the
+    whole batch as their stride, and bytes beyond the arrays stay untouched."""
+    B = 37
+    if kind == "resnet":
+        arch = WL.resnet_arch(image=64, width_div=2, blocks=(2, 2, 2, 2))
+        params = WL.resnet_params(arch, S + 40)
+        lb = _rn_bias(S + 42, B, 4)
+        net = gpu_lib.build_resnet(arch, params, DEV)
+    elif kind == "mbnet":
+        arch = WL.mbnet_arch(image=64, width_div=4)
+        params = WL.mbnet_params(arch, S + 30)
+        lb = WL.seeded_logit_bias(S + 32, B, arch["T"])[None]
+        net = gpu_lib.build_mbnet(arch, params, DEV)
+    else:
+        arch = WL.vit_arch(image=64, patch=16, depth=2, routes="diag")
+        params = WL.vit_params(arch, S + 50)
+        lb = WL.seeded_logit_bias(S + 52, B, arch["T"])[None]
+        net = gpu_lib.build_vit(arch, params, DEV)
+    imgs = WL.images(S + 41, B, 64)
+    xg = torch.from_numpy(imgs).to(DEV).to(torch.bfloat16).contiguous()
+    lbg = torch.from_numpy(np.ascontiguousarray(lb, dtype=np.float32)).to(DEV)
+    want_l, want_r = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
+    torch.cuda.synchronize()
+    for parts in (1, 2, 3, 4):
+        logits = torch.full((B + 1, net.num_classes), float("nan"), dtype=torch.float32, device=DEV)
+        routes = torch.full((net.n_gates, B), -7, dtype=torch.int32, device=DEV)
+        gpu_lib.ds_forward_parts(net, xg, parts, logit_bias=lbg, logits=logits, routes=routes)
+        # two calls in a row share the side streams; the second must wait for the first
+        gpu_lib.ds_forward_parts(net, xg, parts, logit_bias=lbg, logits=logits, routes=routes)
+        torch.cuda.synchronize()
+        assert torch.equal(routes, want_r), parts
+        assert torch.all(torch.isnan(logits[B]))
+        assert relerr(logits[:B].cpu().numpy(), want_l.cpu().numpy()) < 1e-5, parts
+    # teacher-forced routes through the parts path
+    l2, r2 = gpu_lib.ds_forward_parts(net, xg, 3, route_override=want_r.clone(), logit_bias=lbg)
+    assert torch.equal(r2, want_r) and relerr(l2.cpu().numpy(), want_l.cpu().numpy()) < 1e-5
+    # too small a workspace is refused before anything is launched
+    with pytest.raises(gpu_lib.DsError):
+        gpu_lib.ds_forward_parts(net, xg, 2, logit_bias=lbg, ws=torch.empty(256, dtype=torch.uint8, device=DEV))
