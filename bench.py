@@ -198,6 +198,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp", "resnet_pp", "linear"])
     ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--parts", type=int, default=1,
+                    help="run the batch as this many concurrent shares (ds_forward_parts, 1..4); 1 = ds_forward")
     ap.add_argument("--mix", default="uniform", choices=["uniform", "skewed"],
                     help="route mix: every route about equally often (default), or half of the batch on the smallest "
                          "route at early gates / the largest route at late gates")
@@ -240,10 +242,13 @@ def main():
     lbg = torch.from_numpy(lb).to(dev).contiguous()
     logits = torch.empty((B, net.num_classes), dtype=torch.float32, device=dev)
     routes = torch.empty((net.n_gates, B), dtype=torch.int32, device=dev)
-    ws = net.workspace(B)
+    ws = net.workspace(B, args.parts)
 
     def step():
-        ds.ds_forward(net, x, logit_bias=lbg, logits=logits, routes=routes, ws=ws)
+        if args.parts == 1:
+            ds.ds_forward(net, x, logit_bias=lbg, logits=logits, routes=routes, ws=ws)
+        else:
+            ds.ds_forward_parts(net, x, args.parts, logit_bias=lbg, logits=logits, routes=routes, ws=ws)
 
     for _ in range(args.warmup):
         step()
@@ -322,7 +327,7 @@ def main():
         "metric": "images/sec at batch 256 (mixed gate widths)", "value": B / (ms_per_step * 1e-3), "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": label, "batch": B, "image": arch["image"], "route_mix": args.mix,
+        "config": {"workload": label, "batch": B, "image": arch["image"], "route_mix": args.mix, "parts": args.parts,
                    "route_histogram": [np.bincount(r, minlength=net.T).tolist() for r in rt]},
         "roofline": roofline,
         "kernels": kernels,
