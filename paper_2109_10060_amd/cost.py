@@ -48,8 +48,16 @@ def mbnet_cost(arch, routes) -> Cost:
         r = _osz(r, 3, s, 1)
         ci, co = arch["cin"][routes, i].astype(np.float64), arch["cout"][routes, i].astype(np.float64)
         kk = arch["ksize"][routes, i].astype(np.float64) ** 2 if "ksize" in arch else 9.0
-        c.add("dwconv", 2.0 * r * r * (kk * ci).sum(), 2.0 * (rin * rin + r * r) * ci.sum())
-        _gemm(c, "gemm", r * r, r * r, 1, ci, co)
+        cif, cof = int(_ci), int(_co)
+        if (i < arch["gate_after"] and "ksize" not in arch and cif % 32 == 0 and cif <= 128 and cof % 64 == 0
+                and cof <= 128 and r % (4 if s == 1 else 2) == 0):
+            # an unsliced block the library runs as one kernel (depthwise map kept in LDS): counted as one launch
+            # of the depthwise class that reads the block's input and writes the pointwise output
+            c.add("dwconv", 2.0 * r * r * (kk * ci).sum() + 2.0 * r * r * np.sum(ci * co),
+                  2.0 * rin * rin * ci.sum() + 2.0 * r * r * co.sum() + 2.0 * cif * cof)
+        else:
+            c.add("dwconv", 2.0 * r * r * (kk * ci).sum(), 2.0 * (rin * rin + r * r) * ci.sum())
+            _gemm(c, "gemm", r * r, r * r, 1, ci, co)
         if i == arch["gate_after"] - 1:
             c.add("gate", 2.0 * B * (r * r * co[0]), 2.0 * B * r * r * co[0])
     cl = arch["cout"][routes, -1].astype(np.float64)

@@ -170,6 +170,11 @@ int32_t ds_launch_layernorm(ActView x, ActView y, const float* gamma, const floa
 int32_t ds_launch_stem(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
                        const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
                        int32_t pad, int32_t Cout, hipStream_t s);
+// 3x3 depthwise + batch-norm + ReLU and 1x1 pointwise + batch-norm + ReLU of an unsliced block in one kernel
+// (x [B][H][W][C] -> y [B][Ho][Wo][N]); DS_EUNSUPPORTED when the shape has no fused variant
+int32_t ds_launch_dwpw(const bf16_t* x, int32_t B, int32_t H, int32_t W, int32_t C, int32_t stride, const bf16_t* wd,
+                       const float* sd, const float* hd, const bf16_t* wp, int32_t w_ld, int32_t N, const float* sp,
+                       const float* hp, bf16_t* y, hipStream_t s);
 int32_t ds_launch_stem_mfma(const bf16_t* img, const int32_t* index, bf16_t* y, const bf16_t* w, const float* scale,
                             const float* shift, int32_t B, int32_t H, int32_t W, int32_t K, int32_t stride,
                             int32_t pad, int32_t Cout, hipStream_t s);

@@ -222,6 +222,17 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
             gpw = gdw;
             for (int t = 0; t < d.T; ++t) gpw.k_out[t] = d.cout[t * d.nb + i];
         }
+        if (!phase && !d.kfull) {
+            // an unsliced block: depthwise and pointwise in one kernel where the shape allows, the depthwise map stays in LDS
+            const int32_t rc = ds_launch_dwpw(cur, B, rin, rin, ci, st, (const bf16_t*)Q[0], (const float*)Q[1],
+                                              (const float*)Q[2], (const bf16_t*)Q[3], ci, co, (const float*)Q[4],
+                                              (const float*)Q[5], oth, s);
+            if (rc == DS_OK) {
+                bf16_t* t = cur; cur = oth; oth = t;
+                continue;
+            }
+            if (rc != DS_EUNSUPPORTED) return rc;
+        }
         const int32_t* offsets = phase ? p.offs : p.off1;
         if (r * r != last_rows || phase != last_phase) {
             ++li;

@@ -61,6 +61,18 @@ def test_mbnet_small_all_samples(gpu_lib):
     assert len(set(routes.cpu().numpy()[0].tolist())) == arch["T"]       # every width occurs
 
 
+@pytest.mark.parametrize("B", [16, 5])
+def test_mbnet_full_width_small_images_all_samples(gpu_lib, B):
+    # the stored widths of the paper's network (32 .. 1024) on 64x64 images: the unsliced blocks in front of the gate
+    # take the fused depthwise + pointwise kernel on 32x32, 16x16 and 8x8 maps (whole tiles, two tiles per sample, and
+    # a ragged tile of 64 pixels), with whole samples per die (B = 16) and in plain tile order (B = 5)
+    arch = WL.mbnet_arch(image=64)
+    params = WL.mbnet_params(arch, S + 33)
+    imgs = WL.images(S + 34, B, 64)
+    lb = WL.seeded_logit_bias(S + 35, B, arch["T"])
+    _mb_case(gpu_lib, arch, params, imgs, lb, range(B))
+
+
 def test_mbnet_config3_batch256(gpu_lib):
     arch = WL.mbnet_arch()
     params = WL.mbnet_params(arch, S + 3)
