@@ -98,6 +98,9 @@ size_t ds_mtile_capacity(int32_t B, int32_t rows, int32_t T);
 // builds the m-tile list for (offsets, rows); list needs ds_mtile_capacity()*16 + 16 bytes
 int32_t ds_build_mtiles(const int32_t* offsets, int32_t T, int32_t rows, void* list, hipStream_t s);
 int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
+// 1x1 / linear layers with input slices of at most 64 channels and several 64-column passes: one workgroup per 128 rows
+// and all their columns; DS_EUNSUPPORTED otherwise
+int32_t ds_launch_thin(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
 // 3x3 stride-1 padding-1 layers on maps up to 59 pixels wide; DS_EUNSUPPORTED for any other shape
 int32_t ds_launch_conv3(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
 

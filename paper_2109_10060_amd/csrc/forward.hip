@@ -76,6 +76,11 @@ int32_t conv_gemm(const bf16_t* A, const int32_t* a_index, int64_t a_sstride, in
     a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.K = K; a.stride = stride; a.pad = pad; a.rows = Ho * Wo;
     a.offsets = offsets; a.mtiles = ds_mtile_entries(ml.list); a.n_mtiles = ds_mtile_count(ml.list);
     a.act = act; a.out_f32 = 0; a.gt = gt;
+    {
+        // short reductions with several column passes stream best with one workgroup per row tile
+        const int32_t rc = ds_launch_thin(a, ml.cap, max_out(gt), s);
+        if (rc != DS_EUNSUPPORTED) return rc;
+    }
     return ds_launch_gemm(a, ml.cap, max_out(gt), s);
 }
 
