@@ -299,7 +299,7 @@ def main():
         if n and ms > 0:
             tf = flops / (ms * 1e-3) / 1e12
             gbs = nbytes / (ms * 1e-3) / 1e9
-            roofline = {"kernel": "gemm_kernel+conv3_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS,
+            roofline = {"kernel": "gemm_kernel+conv3_kernel+thin_kernel", "bound": "mfma", "achieved": tf, "peak": PEAK_MFMA_BF16_TFLOPS,
                         "unit": "TFLOP/s", "frac": tf / PEAK_MFMA_BF16_TFLOPS, "traffic": traffic,
                         "algorithmic_bytes_per_launch": nbytes / n,
                         "launches_per_step": n / sampled, "avg_launch_us": ms * 1e3 / n,

@@ -18,10 +18,11 @@ import os
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-KERNEL_SOURCES = ["csrc/gemm.hip", "csrc/conv3.hip", "csrc/common.h"]
-# the grouped GEMM is two kernels: gemm_kernel (linear, 1x1, strided and KxK layers) and conv3_kernel
-# (3x3 stride-1 layers); the summaries treat them as one kernel class, as bench.py does
-GEMM_KERNELS = ("gemm_kernel", "conv3_kernel")
+KERNEL_SOURCES = ["csrc/gemm.hip", "csrc/conv3.hip", "csrc/thin.hip", "csrc/common.h"]
+# the grouped GEMM is three kernels: gemm_kernel (linear, 1x1, strided and KxK layers), conv3_kernel (3x3 stride-1
+# layers) and thin_kernel (1x1 layers with at most 64 / 128 input channels); the summaries treat them as one kernel
+# class, as bench.py does
+GEMM_KERNELS = ("gemm_kernel", "conv3_kernel", "thin_kernel")
 
 
 def kernel_source_hash() -> str:
@@ -68,7 +69,7 @@ def traffic(fetch_csv, write_csv, copy_fetch_csv, copy_write_csv, copy_bytes, ou
     ff, fw = copy_kib / cf, copy_kib / cw
     gf, n = _per_launch(fetch_csv, "FETCH_SIZE", GEMM_KERNELS)
     gw, _ = _per_launch(write_csv, "WRITE_SIZE", GEMM_KERNELS)
-    out = {"kernel": "gemm_kernel+conv3_kernel", "source_hash": kernel_source_hash(), "launches_sampled": n,
+    out = {"kernel": "gemm_kernel+conv3_kernel+thin_kernel", "source_hash": kernel_source_hash(), "launches_sampled": n,
            "fetch_kib_per_launch": gf, "write_kib_per_launch": gw, "fetch_factor": ff, "write_factor": fw,
            "hbm_bytes_per_launch": (gf * ff + gw * fw) * 1024.0, "commands": commands}
     json.dump(out, open(out_json, "w"), indent=1)
