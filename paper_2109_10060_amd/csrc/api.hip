@@ -96,6 +96,11 @@ extern "C" int32_t ds_sliced_linear(const void* x, int64_t x_ld, const void* w, 
     a.offsets = g->offsets; a.mtiles = ds_mtile_entries(ws); a.n_mtiles = ds_mtile_count(ws);
     a.act = act; a.out_f32 = y_dtype == DS_F32;
     a.gt = gt;
+    {
+        // thin reductions with several column passes have a kernel of their own
+        const int32_t rt = ds_launch_thin(a, (int32_t)ds_mtile_capacity(B, rows, g->T), mo, s);
+        if (rt != DS_EUNSUPPORTED) return rt;
+    }
     return ds_launch_gemm(a, (int32_t)ds_mtile_capacity(B, rows, g->T), mo, s);
 }
 
@@ -151,6 +156,11 @@ extern "C" int32_t ds_sliced_conv(const void* x, int32_t dtype, int32_t layout, 
     a.offsets = g->offsets; a.mtiles = ds_mtile_entries(ws); a.n_mtiles = ds_mtile_count(ws);
     a.act = act; a.out_f32 = 0;
     a.gt = gt;
+    {
+        // thin reductions with several column passes have a kernel of their own
+        const int32_t rt = ds_launch_thin(a, (int32_t)ds_mtile_capacity(B, rows, g->T), mo, s);
+        if (rt != DS_EUNSUPPORTED) return rt;
+    }
     return ds_launch_gemm(a, (int32_t)ds_mtile_capacity(B, rows, g->T), mo, s);
 }
 

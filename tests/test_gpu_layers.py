@@ -262,6 +262,10 @@ def test_config1_forced_routes_cover_all_ratios(gpu_lib):
 @pytest.mark.parametrize("K,stride,pad,H,CI,CO,res", [(3, 1, 1, 14, 64, 64, False), (3, 2, 1, 15, 48, 80, False),
                                                        (1, 1, 0, 9, 96, 40, True), (1, 2, 0, 14, 64, 128, False),
                                                        (3, 1, 1, 7, 136, 24, True),
+                                                       # 1x1 layers with a thin reduction and several 64-column passes: the
+                                                       # streaming kernel (up to 64 input channels; up to 128 with a residual)
+                                                       (1, 1, 0, 13, 64, 200, True), (1, 1, 0, 9, 40, 136, False),
+                                                       (1, 1, 0, 11, 128, 264, True), (1, 1, 0, 11, 128, 264, False),
                                                        # 3x3 stride 1 on wide maps: the patch-staged kernel up to 59 pixels,
                                                        # the tap-walking kernel beyond
                                                        (3, 1, 1, 56, 32, 72, False), (3, 1, 1, 59, 32, 16, True),
