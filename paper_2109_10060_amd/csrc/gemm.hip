@@ -400,9 +400,15 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
         const char* e = getenv("DSNET_GEMM_TILE");   // tuning knob: force the n-tile width (64, 128, 256)
         return e ? atoi(e) : 0;
     }();
-    // ragged route slices and short reductions favour narrow tiles at high occupancy: measured on the
-    // three batch-256 networks, every layer ran fastest with the 128x64 tile (32-deep slabs, 5 waves/SIMD)
-    const int bn = forced ? forced : 32;
+    // ragged route slices favour the narrow 128x64 tile at high occupancy in every layer of the batch-256 networks.
+    // Its slabs are 32 deep for short reductions and 64 deep from 256 reduction steps on: half the barriers and
+    // twice the bytes in flight per workgroup outweigh the lower residency there (measured per layer: ViT MLP
+    // down-projection 62 -> 52 us, ResNet stage-4 strided 3x3 83 -> 66 us; 128-step layers 44 -> 48 us the other way)
+    // (a slab never crosses a filter tap: with fewer than 64 channels per tap the deep slab would be mostly padding --
+    // the 8x8 patch embedding over 24 channels ran 144 -> 226 us with it)
+    int kmax = 0;
+    for (int t = 0; t < a.gt.T; ++t) kmax = a.gt.k_in[t] > kmax ? a.gt.k_in[t] : kmax;
+    const int bn = forced ? forced : ((kmax >= 64 && kmax * a.K * a.K >= 256) ? 64 : 32);
     // 32-bit byte offsets inside the kernel: the operands must span less than 2 GiB
     const long long slots = (long long)max_mtiles * BM / (a.rows > 0 ? a.rows : 1) + 1;
     if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL)
