@@ -50,7 +50,7 @@ struct Tile {
     static constexpr int LOOP_BYTES = (BM + BN) * LDS_LD * 2;
     static constexpr int STAGE_BYTES = 4 * SROWS * ST_LD * 4;
     static constexpr int MAIN_BYTES = LOOP_BYTES > STAGE_BYTES ? LOOP_BYTES : STAGE_BYTES;
-    static constexpr int TABLE_BYTES = BM * (4 + 8 + 8 + 8);
+    static constexpr int TABLE_BYTES = BM * (4 + 8 + 8 + 8) + 2 * BN * 4;   // row tables + scale / shift of the tile's columns
     static constexpr int SMEM = MAIN_BYTES + TABLE_BYTES;
     static_assert(WROWS * WCOLS == 4 && WROWS * WMT * 32 == BM, "4 wavefronts cover a 128-row tile");
 };
@@ -66,6 +66,7 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
     long long* rowR = rowC + BM;
     int2* rowYX = (int2*)(rowR + BM);
     uint32_t* rowA = (uint32_t*)(rowYX + BM);
+    float* scl = (float*)(rowA + BM);                 // [BN] scale, then [BN] shift of this tile's output columns
     // operands are fetched with buffer loads: 32-bit byte offsets against a uniform base, and an
     // offset beyond the descriptor's range returns zeros, which supplies every tail (rows beyond
     // the group, channels beyond the slice, taps outside the image) without branches
@@ -215,17 +216,17 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
     const int cg = lane % CG, rr0 = lane / CG;
     const int ncol = n0 + wn * COLS + cg * 4;
     const bool nok = ncol < k_out;
-    float sc[4] = {1.f, 1.f, 1.f, 1.f}, sh[4] = {0.f, 0.f, 0.f, 0.f};
-    if (nok) {
-        const long long ti = (long long)a.gt.row[g] * a.tab_ld + (long long)seg * a.tab_seg_stride + ncol;
-        if (a.scale) {
-            const float4 t = *(const float4*)(a.scale + ti);
-            sc[0] = t.x; sc[1] = t.y; sc[2] = t.z; sc[3] = t.w;
+    // scale and shift of the tile's columns wait in LDS, not in registers, until the epilogue (registers set the residency)
+    if (tid < BN) {
+        const int n = n0 + tid;
+        float vs = 1.f, vh = 0.f;
+        if (n < k_out) {
+            const long long ti = (long long)a.gt.row[g] * a.tab_ld + (long long)seg * a.tab_seg_stride + n;
+            if (a.scale) vs = a.scale[ti];
+            if (a.shift) vh = a.shift[ti];
         }
-        if (a.shift) {
-            const float4 t = *(const float4*)(a.shift + ti);
-            sh[0] = t.x; sh[1] = t.y; sh[2] = t.z; sh[3] = t.w;
-        }
+        scl[tid] = vs;
+        scl[BN + tid] = vh;
     }
 
     // the residual rows this lane will add are fetched now, so that their latency hides behind the
@@ -307,7 +308,8 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
                     const long long coff = rowC[r];
                     if (coff < 0) continue;
                     const float4 t = *(const float4*)(st + rr * ST_LD + cg * 4);
-                    float val[4] = {t.x * sc[0] + sh[0], t.y * sc[1] + sh[1], t.z * sc[2] + sh[2], t.w * sc[3] + sh[3]};
+                    const float4 s4 = *(const float4*)(scl + wn * COLS + cg * 4), h4 = *(const float4*)(scl + BN + wn * COLS + cg * 4);
+                    float val[4] = {t.x * s4.x + h4.x, t.y * s4.y + h4.y, t.z * s4.z + h4.z, t.w * s4.w + h4.w};
                     if constexpr (HASR) {
                         const uint2 q = rres[(tm * PASSES + ps) * (SROWS / RPP) + (rr - rr0) / RPP];
                         val[0] += __uint_as_float(q.x << 16);
