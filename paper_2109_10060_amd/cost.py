@@ -49,7 +49,7 @@ def mbnet_cost(arch, routes) -> Cost:
         ci, co = arch["cin"][routes, i].astype(np.float64), arch["cout"][routes, i].astype(np.float64)
         kk = arch["ksize"][routes, i].astype(np.float64) ** 2 if "ksize" in arch else 9.0
         cif, cof = int(_ci), int(_co)
-        if (i < arch["gate_after"] and "ksize" not in arch and cif % 32 == 0 and cif <= 128 and cof % 64 == 0
+        if (i < arch["gate_after"] and "ksize" not in arch and cif % 8 == 0 and cif <= 128 and cof % 8 == 0
                 and cof <= 128 and r % (4 if s == 1 else 2) == 0):
             # an unsliced block the library runs as one kernel (depthwise map kept in LDS): counted as one launch
             # of the depthwise class that reads the block's input and writes the pointwise output
@@ -114,8 +114,12 @@ def vit_cost(arch, routes) -> Cost:
         full = np.full(B, C, np.float64)
         c.add("stem", 2.0 * B * r * r * 147 * C, B * (3 * arch["image"] ** 2 * 2 + r * r * C * 2))
         for _ in range(2):
-            c.add("dwconv", 2.0 * B * r * r * 9 * C, 2.0 * 2 * B * r * r * C)
-            _gemm(c, "gemm", r * r, r * r, 1, full, full)
+            if C % 8 == 0 and C <= 128 and r % 4 == 0:
+                # the block runs as one kernel (depthwise map kept in LDS): one launch of the depthwise class
+                c.add("dwconv", 2.0 * B * r * r * 9 * C + 2.0 * B * r * r * C * C, 2.0 * 2 * B * r * r * C + 2.0 * C * C)
+            else:
+                c.add("dwconv", 2.0 * B * r * r * 9 * C, 2.0 * 2 * B * r * r * C)
+                _gemm(c, "gemm", r * r, r * r, 1, full, full)
         c.add("gate", 2.0 * B * r * r * C, 2.0 * B * r * r * C)
         # the patch projection reads every pixel of the stem's map once
         _gemm(c, "gemm_taps", (N - 1) * arch["patch"] ** 2, N - 1, 1, full, de)

@@ -44,13 +44,14 @@ __device__ __forceinline__ int tile_of(int v, int tiles_per_image, bool by_die) 
     return ((v & 7) + 8 * s8) * tiles_per_image + (vq - s8 * tiles_per_image);
 }
 
-// RT: 32-pixel row tiles per wavefront; the workgroup's tile is TPX = 128 RT consecutive output pixels
-template <int STRIDE, int PX, int RT>
+// RT: 32-pixel row tiles per wavefront; the workgroup's tile is TPX = 128 RT consecutive output pixels.
+// KCH: 32-channel chunks of the reduction (the last may be partly zeros)
+template <int STRIDE, int PX, int RT, int KCH>
 __global__ __launch_bounds__(256, 3) void dwpw_kernel(const DwPwArgs a) {
     constexpr int NCOL = (PX - 1) * STRIDE + 3, TPX = 128 * RT;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int C = a.C, N = a.N, Wo = a.Wo, H = a.H, W = a.W;
-    const int kch = C >> 5;                                // 32-channel chunks of the reduction
+    constexpr int kch = KCH;
     char* As = smem;                                       // [kch][128][32] bf16
     char* Bs = smem + kch * TPX * 64;                      // [kch][64][32] bf16, later the staging tile [128][S_LD]
     const int tid = threadIdx.x;
@@ -61,22 +62,28 @@ __global__ __launch_bounds__(256, 3) void dwpw_kernel(const DwPwArgs a) {
 
     // pointwise weights of the first 64 filters and their batch-norm constants: requested now, parked in registers
     // during phase 1, so that the tile's only exposed memory round trip is the one of its input window
-    const int wchunks = C >> 3;                            // 16-byte pieces per weight row
-    const int wpieces = 64 * wchunks;                      // per 64-filter tile; a multiple of 256 (C % 32 == 0), at most 1024
-    uint4 wreg0, wreg1, wreg2, wreg3;
-    float4 creg;
-    // piece e of the 64-filter tile at n0 (the pieces beyond the tile repeat piece 0 and are not stored)
+    const int wchunks = C >> 3;                            // 16-byte pieces of real channels per weight row
+    constexpr int wslots = KCH * 4;                        // pieces per row of the LDS tile (those past wchunks are zeros)
+    constexpr int wpieces = 64 * wslots;                   // per 64-filter tile: 256 KCH, KCH per lane
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.wp, 0, 0x7fffffff, 0x00020000);
+    uint4 wreg0 = make_uint4(0, 0, 0, 0), wreg1 = wreg0, wreg2 = wreg0, wreg3 = wreg0;
+    float creg;
+    // piece e of the 64-filter tile at n0: filter n0 + e / wslots, channels 8 (e % wslots) ..; zeros past N or C
 #define DWPW_WLOAD(e_, n0_)                                                                            \
     ([&] {                                                                                             \
-        const int ee = (e_) < wpieces ? (e_) : 0;                                                      \
-        const int nl = ee / wchunks, c8 = ee - nl * wchunks;                                           \
-        return *(const uint4*)(a.wp + (int64_t)((n0_) + nl) * a.w_ld + c8 * 8);                        \
+        const int nl = (e_) / wslots, c8 = (e_) - nl * wslots;                                         \
+        const bool ok = (e_) < wpieces && (n0_) + nl < N && c8 < wchunks;                              \
+        const auto t = __builtin_amdgcn_raw_buffer_load_b128(                                          \
+            rsrc_w, (int)(ok ? (uint32_t)((((n0_) + nl) * a.w_ld + c8 * 8) * 2) : OOB), 0, 0);         \
+        return make_uint4(t[0], t[1], t[2], t[3]);                                                     \
     }())
 #define DWPW_FETCH(n0_)                                                                                \
     do {                                                                                               \
-        wreg0 = DWPW_WLOAD(tid, n0_); wreg1 = DWPW_WLOAD(tid + 256, n0_);                              \
-        wreg2 = DWPW_WLOAD(tid + 512, n0_); wreg3 = DWPW_WLOAD(tid + 768, n0_);                        \
-        creg = *(const float4*)(((tid & 31) < 16 ? a.sp : a.hp) + (n0_) + (tid & 15) * 4);             \
+        wreg0 = DWPW_WLOAD(tid, n0_);                                                                  \
+        if constexpr (KCH > 1) wreg1 = DWPW_WLOAD(tid + 256, n0_);                                     \
+        if constexpr (KCH > 2) { wreg2 = DWPW_WLOAD(tid + 512, n0_); wreg3 = DWPW_WLOAD(tid + 768, n0_); } \
+        creg = 0.f;                                                                                    \
+        if (tid < 128 && (n0_) + (tid & 63) < N) creg = (tid < 64 ? a.sp : a.hp)[(n0_) + (tid & 63)];  \
     } while (0)
     DWPW_FETCH(0);
 
@@ -86,6 +93,11 @@ __global__ __launch_bounds__(256, 3) void dwpw_kernel(const DwPwArgs a) {
             (void*)(a.x + (int64_t)slot * H * W * C), 0, 0x7fffffff, 0x00020000);
         const int chunks = C >> 3;
         const int items = (TPX / PX) * chunks;
+        // the last 32-channel chunk of a width that is no multiple of 32: its missing channels multiply as zeros
+        for (int e = tid; e < TPX * (kch * 4 - chunks); e += 256) {
+            const int row = e / (kch * 4 - chunks), c8 = chunks + (e - row * (kch * 4 - chunks));
+            *(uint4*)(As + ((c8 >> 2) * TPX + row) * 64 + (((c8 & 3) ^ swz(row)) * 16)) = make_uint4(0, 0, 0, 0);
+        }
         for (int e = tid; e < items; e += 256) {
             const int gl = e / chunks, c8 = e - gl * chunks, ch = c8 * 8;
             const int pl = gl * PX, p = p0 + pl;
@@ -173,15 +185,15 @@ __global__ __launch_bounds__(256, 3) void dwpw_kernel(const DwPwArgs a) {
         {
             const uint4 wr[4] = {wreg0, wreg1, wreg2, wreg3};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < KCH; ++i) {
                 const int e = tid + 256 * i;
-                if (e < wpieces) {
-                    const int nl = e / wchunks, c8 = e - nl * wchunks;
+                {
+                    const int nl = e / wslots, c8 = e - nl * wslots;
                     *(uint4*)(Bs + ((c8 >> 2) * 64 + nl) * 64 + (((c8 & 3) ^ swz(nl)) * 16)) = wr[i];
                 }
             }
         }
-        if (tid < 32) *(float4*)(cst + tid * 4) = creg;
+        if (tid < 128) cst[tid] = creg;
         __syncthreads();
         if (n0 + 64 < N) DWPW_FETCH(n0 + 64);              // the next pass's weights travel during this pass
         f32x16_t acc[RT][2];
@@ -231,7 +243,7 @@ __global__ __launch_bounds__(256, 3) void dwpw_kernel(const DwPwArgs a) {
         bf16_t* yp = a.y + ((int64_t)slot * HoWo + p0) * N + n0;
         for (int c = tid; c < TPX * 8; c += 256) {
             const int pix = c >> 3, ch = (c & 7) * 8;
-            if (p0 + pix < HoWo) *(uint4*)(yp + (int64_t)pix * N + ch) = *(const uint4*)(stile + pix * S_LD + ch);
+            if (p0 + pix < HoWo && n0 + ch < N) *(uint4*)(yp + (int64_t)pix * N + ch) = *(const uint4*)(stile + pix * S_LD + ch);
         }
     }
 }
@@ -247,29 +259,37 @@ int32_t ds_launch_dwpw(const bf16_t* x, int32_t B, int32_t H, int32_t W, int32_t
     if (B <= 0) return DS_OK;
     const int Ho = (H + 2 - 3) / stride + 1, Wo = (W + 2 - 3) / stride + 1;
     const int px = stride == 1 ? 4 : 2;
-    if ((stride != 1 && stride != 2) || (C % 32) || C > 128 || (N % 64) || N > 128 || (w_ld % 8) || (Wo % px) || Ho < 1 ||
+    if ((stride != 1 && stride != 2) || (C % 8) || C < 8 || C > 128 || (N % 8) || N < 8 || N > 128 || (w_ld % 8) || (Wo % px) || Ho < 1 ||
         (int64_t)H * W * C * 2 >= 0x7fffffffll)
         return DS_EUNSUPPORTED;
     DwPwArgs a;
     a.x = x; a.y = y; a.wd = wd; a.sd = sd; a.hd = hd; a.wp = wp; a.sp = sp; a.hp = hp;
     a.B = B; a.H = H; a.W = W; a.C = C; a.Ho = Ho; a.Wo = Wo; a.N = N; a.w_ld = w_ld;
     // 32 channels: 256-pixel tiles, so that every lane has a run of 4 pixels x 8 channels to compute
-    const int rt = (stride == 1 && C == 32) ? 2 : 1, tpx = 128 * rt;
+    const int rt = (stride == 1 && C <= 32) ? 2 : 1, tpx = 128 * rt;
     a.tiles_per_image = (Ho * Wo + tpx - 1) / tpx;
     const int64_t grid = (int64_t)B * a.tiles_per_image;
     if (grid > 0x7fffffffll) return DS_EUNSUPPORTED;
     a.by_die = (B % 8) == 0;
-    const int kch = C / 32;
+    const int kch = C <= 32 ? 1 : (C <= 64 ? 2 : 4);
     const int b_bytes = kch * 64 * 64, st_bytes = tpx * S_LD * 2;
     const int smem = kch * tpx * 64 + (b_bytes > st_bytes ? b_bytes : st_bytes) + 2 * 64 * 4;
     ProfScope prof(DS_K_DWCONV, s);
+    const dim3 g((unsigned)grid), b(256);
+#define DWPW_LAUNCH(S_, P_, R_)                                                                         \
+    do {                                                                                               \
+        if (kch == 1) hipLaunchKernelGGL((dwpw_kernel<S_, P_, R_, 1>), g, b, smem, s, a);              \
+        else if (kch == 2) hipLaunchKernelGGL((dwpw_kernel<S_, P_, R_, 2>), g, b, smem, s, a);         \
+        else hipLaunchKernelGGL((dwpw_kernel<S_, P_, R_, 4>), g, b, smem, s, a);                       \
+    } while (0)
     if (stride == 1 && rt == 2) {
-        hipLaunchKernelGGL((dwpw_kernel<1, 4, 2>), dim3((unsigned)grid), dim3(256), smem, s, a);
+        hipLaunchKernelGGL((dwpw_kernel<1, 4, 2, 1>), g, b, smem, s, a);
     } else if (stride == 1) {
-        hipLaunchKernelGGL((dwpw_kernel<1, 4, 1>), dim3((unsigned)grid), dim3(256), smem, s, a);
+        DWPW_LAUNCH(1, 4, 1);
     } else {
-        hipLaunchKernelGGL((dwpw_kernel<2, 2, 1>), dim3((unsigned)grid), dim3(256), smem, s, a);
+        DWPW_LAUNCH(2, 2, 1);
     }
+#undef DWPW_LAUNCH
     DS_CHECK_LAUNCH("depthwise + pointwise");
     return DS_OK;
 }

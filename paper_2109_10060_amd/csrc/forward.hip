@@ -638,6 +638,20 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
         const GroupTable g1c = table1(C, C);
         for (int i = 0; i < 2; ++i) {
             const void* const* Q = S + 3 + 6 * i;
+            // the block as one kernel where the shape allows (the depthwise map stays in LDS); it cannot run in place,
+            // so two fused blocks in a row go sa -> sb -> sa and the map ends where the layers below expect it
+            int32_t fused = DS_EUNSUPPORTED;
+            if (i == 0) {
+                fused = ds_launch_dwpw(p.sa, B, sr, sr, C, 1, (const bf16_t*)Q[0], (const float*)Q[1], (const float*)Q[2],
+                                       (const bf16_t*)Q[3], C, C, (const float*)Q[4], (const float*)Q[5], p.sb, s);
+                if (fused == DS_OK) {
+                    const void* const* Q1 = S + 3 + 6;
+                    RC(ds_launch_dwpw(p.sb, B, sr, sr, C, 1, (const bf16_t*)Q1[0], (const float*)Q1[1], (const float*)Q1[2],
+                                      (const bf16_t*)Q1[3], C, C, (const float*)Q1[4], (const float*)Q1[5], p.sa, s));
+                    break;
+                }
+                if (fused != DS_EUNSUPPORTED) return fused;
+            }
             ActView xv = {p.sa, nullptr, map, C}, yv = {p.sb, nullptr, map, C};
             RC(ds_launch_dwconv(xv, yv, (const bf16_t*)Q[0], (const float*)Q[1], (const float*)Q[2], C, nullptr, g1c, B, C,
                                 sr, sr, 1, DS_ACT_RELU, s));
