@@ -86,6 +86,7 @@ struct GemmArgs {
     int32_t n_seg, tab_ld, tab_seg_stride;
     // geometry: rows of a sample are the Ho*Wo output pixels of a KxK convolution over HxW
     int32_t H, W, Ho, Wo, K, stride, pad, rows;
+    int32_t Kw, stride_w;    // filter width and horizontal stride where they differ from K / stride (0 = the same)
     // schedule
     const int32_t* offsets;  // device [T+1] slots
     const int4* mtiles;      // device [(group, first row inside group, first slot, rows of group)]

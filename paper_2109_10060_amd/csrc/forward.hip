@@ -701,11 +701,16 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
         a.scale = nullptr; a.shift = (const float*)P[1]; a.tab_ld = 0;
         a.a_index = p.perm; a.c_index = nullptr;
         a.a_sample_stride = (int64_t)sr * sr * C; a.c_sample_stride = x_ss; a.r_sample_stride = 0;
-        a.a_ld = C; a.c_ld = 0; a.r_ld = d.D; a.c_row0 = 1; a.r_use_index = 0;
-        a.w_ld = (int64_t)d.patch * d.patch * C; a.w_tap_stride = C; a.n_seg = 1;
-        a.H = sr; a.W = sr; a.Ho = gw; a.Wo = gw; a.K = d.patch; a.stride = d.patch; a.pad = 0; a.rows = np;
+        // A patch row is patch x C contiguous values and so is the matching row of a filter: the map is read as
+        // [sr][sr / patch] pixels of patch * C channels under a patch x 1 filter (vertical stride patch, horizontal 1),
+        // which makes the reduction patch taps of patch * C channels instead of patch^2 taps of C (24) channels
+        a.a_ld = d.patch * C; a.c_ld = 0; a.r_ld = d.D; a.c_row0 = 1; a.r_use_index = 0;
+        a.w_ld = (int64_t)d.patch * d.patch * C; a.w_tap_stride = d.patch * C; a.n_seg = 1;
+        a.H = sr; a.W = gw; a.Ho = gw; a.Wo = gw; a.K = d.patch; a.Kw = 1; a.stride = d.patch; a.stride_w = 1; a.pad = 0;
+        a.rows = np;
         a.offsets = p.offs; a.mtiles = ds_mtile_entries(ml_p.list); a.n_mtiles = ds_mtile_count(ml_p.list);
         a.act = DS_ACT_NONE; a.out_f32 = 0; a.gt = ge;
+        for (int t = 0; t < T; ++t) a.gt.k_in[t] = d.patch * C;
         RC(ds_launch_gemm(a, ml_p.cap, max_out(ge), s));
     } else {
         RC(ds_launch_patchify(images, p.perm, p.patches, B, d.image, d.image, d.patch, s));

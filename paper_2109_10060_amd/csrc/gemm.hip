@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
             const int oy = p / a.Wo, ox = p - oy * a.Wo;
             // byte offset of the sample (convolution) or of the row itself (linear layers)
             ra = (uint32_t)(((long long)sa * a.a_sample_stride + (CONV ? 0 : (long long)p * a_ld)) * 2);
-            yx = make_int2(oy * a.stride - a.pad, ox * a.stride - a.pad);
+            yx = make_int2(oy * a.stride - a.pad, ox * (a.stride_w > 0 ? a.stride_w : a.stride) - a.pad);
             const long long pc = p + a.c_row0;
             rc = (long long)cs * a.c_sample_stride + pc * c_ld + (long long)seg * a.c_seg_stride;
             rr = (long long)(a.r_use_index ? cs : 0) * a.r_sample_stride + pc * r_ld;
@@ -144,7 +144,8 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
     // per filter tap: byte offset of the input pixel each owned row reads (OOB outside the image)
     auto set_tap = [&](int tap) {
         if constexpr (CONV) {
-            const int u = tap / a.K, v = tap - u * a.K;
+            const int kw = a.Kw > 0 ? a.Kw : a.K;
+            const int u = tap / kw, v = tap - u * kw;
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
                 const int iy = ayx[i].x + u, ix = ayx[i].y + v;
@@ -203,7 +204,7 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
     constexpr int TK = BK == 64 ? 4 : 0;
 
     const int kchunks = (k_in + BK - 1) / BK;
-    const int nk = a.K * a.K * kchunks;
+    const int nk = a.K * (a.Kw > 0 ? a.Kw : a.K) * kchunks;
     int tap = 0, kc = 0;
     set_tap(0);
     load_global(0, 0);
@@ -410,7 +411,7 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     // the 8x8 patch embedding over 24 channels ran 144 -> 226 us with it)
     int kmax = 0;
     for (int t = 0; t < a.gt.T; ++t) kmax = a.gt.k_in[t] > kmax ? a.gt.k_in[t] : kmax;
-    const int bn = forced ? forced : ((kmax >= 64 && kmax * a.K * a.K >= 256) ? 64 : 32);
+    const int bn = forced ? forced : ((kmax >= 64 && kmax * a.K * (a.Kw > 0 ? a.Kw : a.K) >= 256) ? 64 : 32);
     // 32-bit byte offsets inside the kernel: the operands must span less than 2 GiB
     const long long slots = (long long)max_mtiles * BM / (a.rows > 0 ? a.rows : 1) + 1;
     if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL)
