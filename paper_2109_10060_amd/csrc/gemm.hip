@@ -56,7 +56,7 @@ struct Tile {
 };
 
 template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV, bool HASR>
-__global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ? 5 : 6) : 1) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
+__global__ __launch_bounds__(NT, (WMT * WNT == 2 && !CONV) ? (BK == 32 ? (HASR ? 5 : 6) : 5) : 1) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     constexpr int BN = TL::BN, LDS_LD = BK, CPR = BK / 8, RPT = NT / CPR;   // chunks per row, rows per pass
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -230,10 +230,12 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
         scl[BN + tid] = vh;
     }
 
-    // the residual rows this lane will add are fetched now, so that their latency hides behind the
-    // main loop instead of sitting between the last matrix instruction and the stores
+    // the residual rows this lane will add are fetched ahead of the main loop, so that their latency hides behind it
+    // instead of sitting between the last matrix instruction and the stores -- except with the 64-deep slabs, where
+    // their 16 registers would cost a resident workgroup: there they are requested right after the loop
+    constexpr bool RES_EARLY = BK == 32;
     uint2 rres[HASR ? WMT * PASSES * (SROWS / RPP) : 1];
-    if constexpr (HASR) {
+    auto fetch_residual = [&]() {
 #pragma unroll
         for (int tm = 0; tm < WMT; ++tm)
 #pragma unroll
@@ -245,7 +247,8 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
                     if (nok && rowC[r] >= 0) t = *(const uint2*)(a.R + rowR[r] + ncol);
                     rres[(tm * PASSES + ps) * (SROWS / RPP) + q] = t;
                 }
-    }
+    };
+    if constexpr (HASR && RES_EARLY) fetch_residual();
 
     store_lds();
     __syncthreads();
@@ -278,6 +281,8 @@ __global__ __launch_bounds__(NT, (BK == 32 && WMT * WNT == 2 && !CONV) ? (HASR ?
             __syncthreads();
         }
     }
+
+    if constexpr (HASR && !RES_EARLY) fetch_residual();
 
     // ---- epilogue through LDS: each lane finishes 4 consecutive channels of one row -----
     // The staging rows belong to one wavefront (written and read back by its own lanes, and the main loop's last
