@@ -135,7 +135,7 @@ def run_linear(args):
     t0 = time.perf_counter()
     e0.record()
     for i in range(args.steps):
-        on = (not args.no_kernel_events) and i % every == every // 2
+        on = (not args.no_kernel_events) and i % every == min(every // 2, args.steps - 1)
         if on:
             ds.ds_profile_enable(True)
             sampled += 1
@@ -264,7 +264,7 @@ def main():
     t0 = time.perf_counter()
     e0.record()
     for i in range(args.steps):
-        on = (not args.no_kernel_events) and i % every == every // 2
+        on = (not args.no_kernel_events) and i % every == min(every // 2, args.steps - 1)
         if on:
             ds.ds_profile_enable(True)
             sampled += 1
