@@ -27,13 +27,16 @@ def _osz(n, k, s, p):
     return (n + 2 * p - k) // s + 1
 
 
-def _gemm(cost, kind, rows_in, rows_out, kk, k_in, k_out, residual=False, out_bytes=2):
-    """k_in, k_out: per-sample arrays of valid widths."""
+def _gemm(cost, kind, rows_in, rows_out, kk, k_in, k_out, residual=False, out_bytes=2, chained=False):
+    """k_in, k_out: per-sample arrays of valid widths.  chained: the layer runs inside the launch that
+    produced its input rows, so it adds flops, its output and its weights, but no input read and no launch."""
     k_in, k_out = np.asarray(k_in, np.float64), np.asarray(k_out, np.float64)
     flops = 2.0 * rows_out * kk * np.sum(k_in * k_out)
-    nbytes = 2.0 * rows_in * np.sum(k_in) + out_bytes * rows_out * np.sum(k_out) * (2 if residual else 1)
+    nbytes = (0.0 if chained else 2.0 * rows_in * np.sum(k_in)) + out_bytes * rows_out * np.sum(k_out) * (2 if residual else 1)
     nbytes += 2.0 * kk * float(np.max(k_in)) * float(np.max(k_out))
     cost.add(kind, flops, nbytes)
+    if chained:
+        cost[kind]["launches"] -= 1
 
 
 def mbnet_cost(arch, routes) -> Cost:
@@ -80,6 +83,10 @@ def resnet_cost(arch, routes) -> Cost:
         out = arch["out"][s][routes[s]].astype(np.float64)
         if s == 0 or not arch.get("single_gate"):
             c.add("gate", 2.0 * r * r * cprev.sum(), 2.0 * r * r * cprev.sum())
+        # stages with slices of at most 64 channels run a block's last convolution and the next block's first one
+        # as one launch (the wide map is written once and not read back)
+        mids, outs = arch["mid"][s], arch["out"][s]
+        chain = bool(mids.max() <= 64 and outs.max() >= 128 and not (mids % 8).any() and not (outs % 8).any())
         for b in range(nb):
             # dynamic depth: samples whose route has run its blocks of this stage contribute nothing
             on = (arch["nblk"][s][routes[s]] > b).astype(np.float64) if arch.get("nblk") is not None else np.ones(B)
@@ -91,7 +98,7 @@ def resnet_cost(arch, routes) -> Cost:
             m, o = mid * on, out * on
             if b == 0:
                 _gemm(c, "gemm", ro * ro, ro * ro, 1, cin, o)      # 1x1 projection reads only the strided pixels
-            _gemm(c, "gemm", r * r, r * r, 1, cin, m)
+            _gemm(c, "gemm", r * r, r * r, 1, cin, m, chained=chain and b > 0)
             _gemm(c, "gemm_taps", r * r, ro * ro, 9, m, m)
             _gemm(c, "gemm", ro * ro, ro * ro, 1, m, o, residual=True)
             r = ro

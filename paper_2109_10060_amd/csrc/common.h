@@ -102,6 +102,17 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
 // 1x1 / linear layers with input slices of at most 64 channels and several 64-column passes: one workgroup per 128 rows
 // and all their columns; DS_EUNSUPPORTED otherwise
 int32_t ds_launch_thin(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
+// a second 1x1 layer applied to the rows of a thin layer before they leave the workgroup (Section 3.2: the next
+// bottleneck's first convolution reads exactly the rows the previous bottleneck's last convolution wrote)
+struct ThinChain {
+    const bf16_t* Wt;              // [N2_full][w_ld]; its input slice is the first layer's output slice
+    const float *scale, *shift;    // [rows][tab_ld], row = the group's row of the first layer; nullable (1 / 0)
+    bf16_t* C;                     // second output: c_index[slot] * c_sample_stride + p * c_ld + col
+    int64_t w_ld, c_sample_stride;
+    int32_t c_ld, tab_ld, act;     // c_ld <= 0: the group's own width
+    int32_t k_out[DS_MAX_GROUPS];  // per group; <= 0: the group ends with the first layer
+};
+int32_t ds_launch_thin_chain(const GemmArgs& a, const ThinChain& ch, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
 // 3x3 stride-1 padding-1 layers on maps up to 59 pixels wide; DS_EUNSUPPORTED for any other shape
 int32_t ds_launch_conv3(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s);
 

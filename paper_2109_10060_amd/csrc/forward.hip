@@ -63,7 +63,7 @@ struct MList {  // m-tile list of one (bucketing, rows-per-sample) pair
 int32_t conv_gemm(const bf16_t* A, const int32_t* a_index, int64_t a_sstride, int a_ld, const bf16_t* Wt, int C_I_full,
                   int K, int stride, int pad, int H, int W, const float* scale, const float* shift, int tab_ld,
                   const bf16_t* R, bf16_t* C, int64_t c_sstride, int c_ld, const int32_t* offsets, const MList& ml,
-                  const GroupTable& gt, int act, hipStream_t s) {
+                  const GroupTable& gt, int act, hipStream_t s, const ThinChain* chain = nullptr, bool* chained = nullptr) {
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     const int Ho = (H + 2 * pad - K) / stride + 1, Wo = (W + 2 * pad - K) / stride + 1;
@@ -76,6 +76,12 @@ int32_t conv_gemm(const bf16_t* A, const int32_t* a_index, int64_t a_sstride, in
     a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.K = K; a.stride = stride; a.pad = pad; a.rows = Ho * Wo;
     a.offsets = offsets; a.mtiles = ds_mtile_entries(ml.list); a.n_mtiles = ds_mtile_count(ml.list);
     a.act = act; a.out_f32 = 0; a.gt = gt;
+    if (chain) {
+        // the layer that reads exactly these output rows rides along where the shapes allow
+        const int32_t rc = ds_launch_thin_chain(a, *chain, ml.cap, max_out(gt), s);
+        *chained = rc == DS_OK;
+        if (rc != DS_EUNSUPPORTED) return rc;
+    }
     {
         // short reductions with several column passes stream best with one workgroup per row tile
         const int32_t rc = ds_launch_thin(a, ml.cap, max_out(gt), s);
@@ -452,6 +458,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
             if (i != xi) free4[k++] = p.buf[i];
         bf16_t *Y1 = free4[0], *Y2 = free4[1], *Pj = free4[2], *Z = free4[3];
         const int64_t x_ss = (int64_t)rin * rin * c_prev_full;
+        bool y1_ready = false;         // the previous block's last launch has already run this block's first convolution
         for (int b = 0; b < nb; ++b) {
             const bool first = b == 0;
             const int bs = first ? stride : 1;
@@ -483,16 +490,34 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
             } else {
                 shortcut = Z;
             }
-            RC(conv_gemm(in, in_idx, in_ss, 0, (const bf16_t*)L[0], in_full, 1, 1, 0, rb, rb, (const float*)L[1],
-                         (const float*)L[2], w, nullptr, Y1, (int64_t)rb * rb * w, 0, p.offs[st], first ? ml_in : ml_out,
-                         first ? g1f : g1, DS_ACT_RELU, s));
+            if (!y1_ready)
+                RC(conv_gemm(in, in_idx, in_ss, 0, (const bf16_t*)L[0], in_full, 1, 1, 0, rb, rb, (const float*)L[1],
+                             (const float*)L[2], w, nullptr, Y1, (int64_t)rb * rb * w, 0, p.offs[st], first ? ml_in : ml_out,
+                             first ? g1f : g1, DS_ACT_RELU, s));
+            y1_ready = false;
             RC(conv_gemm(Y1, nullptr, (int64_t)rb * rb * w, 0, (const bf16_t*)L[3], w, 3, bs, 1, rb, rb, (const float*)L[4],
                          (const float*)L[5], w, nullptr, Y2, (int64_t)rout * rout * w, 0, p.offs[st], ml_out, g2,
                          DS_ACT_RELU, s));
+            // the next block's first convolution reads the rows this block's last one writes: where the slices are
+            // narrow enough the two run as one launch and Y1 is ready when the next block starts
+            ThinChain ch;
+            memset(&ch, 0, sizeof(ch));
+            bool next_any = false;
+            if (b + 1 < nb) {
+                const void* const* Ln = Q;
+                ch.Wt = (const bf16_t*)Ln[0]; ch.scale = (const float*)Ln[1]; ch.shift = (const float*)Ln[2];
+                ch.C = Y1; ch.w_ld = 4 * w; ch.c_sample_stride = (int64_t)rout * rout * w; ch.c_ld = 0; ch.tab_ld = w;
+                ch.act = DS_ACT_RELU;
+                for (int id = 0; id < G; ++id) {
+                    const bool on = g1.k_out[id] > 0 && (!d.nblk || d.nblk[st * T + (pairs ? id / T : id)] > b + 1);
+                    ch.k_out[id] = on ? g1.k_out[id] : 0;
+                    next_any = next_any || on;
+                }
+            }
             // c3 adds the shortcut; later blocks update Z in place (each element is read and written by one thread)
             RC(conv_gemm(Y2, nullptr, (int64_t)rout * rout * w, 0, (const bf16_t*)L[6], w, 1, 1, 0, rout, rout,
                          (const float*)L[7], (const float*)L[8], 4 * w, shortcut, Z, (int64_t)rout * rout * 4 * w, 0,
-                         p.offs[st], ml_out, g3, DS_ACT_RELU, s));
+                         p.offs[st], ml_out, g3, DS_ACT_RELU, s, next_any ? &ch : nullptr, &y1_ready));
         }
         X = Z;
         for (int i = 0; i < 5; ++i)

@@ -10,6 +10,7 @@
 // whole pass earlier.  The residual tile is parked in LDS, each lane adds its own 8-byte runs in place, and the tile
 // leaves as 16-byte pieces.  Same m-tile list, row addressing and results as gemm_kernel.
 #include "common.h"
+#include <cstring>
 
 namespace {
 
@@ -17,22 +18,31 @@ constexpr int BM = DS_GEMM_BM, NT = 256, T_LD = 64 + 8;
 constexpr uint32_t OOB = 0x80000000u;
 constexpr int TILE_BYTES = BM * T_LD * 2;
 constexpr int smem_bytes(int kch) { return kch * BM * 64 + kch * 64 * 64 + TILE_BYTES + BM * (8 + 8 + 4) + 2 * 64 * 4; }
+// chained variant (2 chunks): plus the second layer's 64 x 64 slab; the pass constants take the place of the activation
+// row table, which is spent by then (42 allocation units of 1280 bytes: three workgroups per compute unit still fit)
+constexpr int W2_BYTES = 64 * 64 * 2;
+constexpr int smem_bytes_chain() { return smem_bytes(2) + W2_BYTES - 2 * 64 * 4; }
 
 __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ (r >> 2)) & 3; }
 
 // KCH: 32-channel chunks of the widest input slice (2: up to 64 channels, 4: up to 128)
-template <bool HASR, int KCH>
-__global__ __launch_bounds__(NT) void thin_kernel(const GemmArgs a, const int max_mtiles) {
+// CHAIN: the rows' results feed a second 1x1 layer of at most 64 output channels before they leave the workgroup
+// (the next bottleneck's first convolution): each pass's 64 result columns are one reduction slab of that layer, whose
+// accumulators stay in registers over the passes, so the wide map is written once and not read back.
+template <bool HASR, int KCH, bool CHAIN>
+__global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs a, const int max_mtiles, const ThinChain ch) {
     constexpr int A_BYTES = KCH * BM * 64, B_BYTES = KCH * 64 * 64, CP = KCH * 4;   // CP 16-byte pieces per operand row
     constexpr int NAP = BM * CP / NT, NWP = 64 * CP / NT;                            // pieces per lane: activations, weights
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* As = smem;                                   // [KCH][128][32] bf16
     char* Bs = smem + A_BYTES;                         // [KCH][64][32] bf16
-    bf16_t* tile = (bf16_t*)(smem + A_BYTES + B_BYTES);   // [128][T_LD]: residual in, result out
-    long long* rowC = (long long*)(smem + A_BYTES + B_BYTES + TILE_BYTES);
-    long long* rowR = rowC + BM;
+    char* W2s = smem + A_BYTES + B_BYTES;              // CHAIN only: [2][64][32] bf16, the second layer's slab of the pass
+    constexpr int T_OFF = A_BYTES + B_BYTES + (CHAIN ? W2_BYTES : 0);
+    bf16_t* tile = (bf16_t*)(smem + T_OFF);            // [128][T_LD]: residual in, result out
+    long long* rowC = (long long*)(smem + T_OFF + TILE_BYTES);
+    long long* rowR = rowC + BM;                       // CHAIN: rows of the second output (the residual is addressed like C)
     uint32_t* rowA = (uint32_t*)(rowR + BM);
-    float* cst = (float*)(rowA + BM);                  // [64] scale, [64] shift of the pass
+    float* cst = (float*)(CHAIN ? rowA : rowA + BM);   // [64] scale, [64] shift of the pass (CHAIN: over the spent rowA)
     const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0x7fffffff, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.Wt, 0, 0x7fffffff, 0x00020000);
 
@@ -47,6 +57,8 @@ __global__ __launch_bounds__(NT) void thin_kernel(const GemmArgs a, const int ma
     const int a_ld = a.a_ld > 0 ? a.a_ld : k_in;
     const int c_ld = a.c_ld > 0 ? a.c_ld : k_out;
     const int r_ld = a.r_ld > 0 ? a.r_ld : k_out;
+    const int k_out2 = CHAIN ? ch.k_out[g] : 0;        // <= 0: this group ends with the first layer
+    const int c2_ld = ch.c_ld > 0 ? ch.c_ld : k_out2;
 
     if (tid < BM) {
         const int m = grow0 + tid;
@@ -61,7 +73,8 @@ __global__ __launch_bounds__(NT) void thin_kernel(const GemmArgs a, const int ma
             ra = (uint32_t)(((long long)sa * a.a_sample_stride + (long long)p * a_ld) * 2);
             const long long pc = p + a.c_row0;
             rc = (long long)cs * a.c_sample_stride + pc * c_ld;
-            rr = (long long)(a.r_use_index ? cs : 0) * a.r_sample_stride + pc * r_ld;
+            rr = CHAIN ? (long long)cs * ch.c_sample_stride + (long long)p * c2_ld
+                       : (long long)(a.r_use_index ? cs : 0) * a.r_sample_stride + pc * r_ld;
         }
         rowA[tid] = ra;
         rowC[tid] = rc;
@@ -95,7 +108,7 @@ __global__ __launch_bounds__(NT) void thin_kernel(const GemmArgs a, const int ma
             for (int i = 0; i < 4; ++i) {
                 const int row = prow8 + 32 * i;
                 uint4 t = make_uint4(0, 0, 0, 0);
-                if (rowC[row] >= 0 && n0 + pc8 < k_out) t = *(const uint4*)(a.R + rowR[row] + n0 + pc8);
+                if (rowC[row] >= 0 && n0 + pc8 < k_out) t = *(const uint4*)(a.R + (CHAIN ? rowC[row] : rowR[row]) + n0 + pc8);
                 rreg[i] = t;
             }
         }
@@ -122,6 +135,26 @@ __global__ __launch_bounds__(NT) void thin_kernel(const GemmArgs a, const int ma
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     const int prow = wave * 32 + l32;
     const int kch = (k_in + 31) >> 5;                  // chunks of this group's reduction, at most KCH
+    // second layer: its weights for the 64 channels of a pass, 2 pieces per lane (row tid / 8 + 32 i, channels 8 (tid % 8) ..)
+    const __amdgpu_buffer_rsrc_t rsrc_w2 = __builtin_amdgcn_make_buffer_rsrc((void*)(CHAIN ? ch.Wt : a.Wt), 0, 0x7fffffff, 0x00020000);
+    uint4 w2reg[2];
+    f32x16_t acc2[2];
+    auto fetch_w2 = [&](int n0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int nl = (tid >> 3) + 32 * i, c0 = n0 + (tid & 7) * 8;
+            const bool ok = nl < k_out2 && c0 < k_out;
+            const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w2, (int)(ok ? (uint32_t)(((long long)nl * ch.w_ld + c0) * 2) : OOB), 0, 0);
+            w2reg[i] = make_uint4(t[0], t[1], t[2], t[3]);
+        }
+    };
+    if constexpr (CHAIN) {
+        if (k_out2 > 0) fetch_w2(0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc2[t][e] = 0.f;
+    }
     for (int n0 = 0; n0 < k_out; n0 += 64) {
         __syncthreads();                               // activation rows staged / last pass's tile copied out
 #pragma unroll
@@ -130,12 +163,26 @@ __global__ __launch_bounds__(NT) void thin_kernel(const GemmArgs a, const int ma
             *(uint4*)(Bs + ((oc8 >> 2) * 64 + nl) * 64 + (((oc8 & 3) ^ swz(nl)) * 16)) = wreg[i];
         }
         if (tid < 128) cst[tid] = creg;
+        if constexpr (CHAIN) {
+            if (k_out2 > 0) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int nl = (tid >> 3) + 32 * i, pc = tid & 7;
+                    *(uint4*)(W2s + ((pc >> 2) * 64 + nl) * 64 + (((pc & 3) ^ swz(nl)) * 16)) = w2reg[i];
+                }
+            }
+        }
         if constexpr (HASR) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) *(uint4*)(tile + (prow8 + 32 * i) * T_LD + pc8) = rreg[i];
         }
         __syncthreads();
-        if (n0 + 64 < k_out) fetch_pass(n0 + 64);      // in flight during this pass
+        if (n0 + 64 < k_out) {                         // in flight during this pass
+            fetch_pass(n0 + 64);
+            if constexpr (CHAIN) {
+                if (k_out2 > 0) fetch_w2(n0 + 64);
+            }
+        }
         f32x16_t acc[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -188,15 +235,62 @@ __global__ __launch_bounds__(NT) void thin_kernel(const GemmArgs a, const int ma
             const long long rc = rowC[row];
             if (rc >= 0 && n0 + pc8 < k_out) *(uint4*)((bf16_t*)a.C + rc + n0 + pc8) = *(const uint4*)(tile + row * T_LD + pc8);
         }
+        if constexpr (CHAIN) {
+            if (k_out2 > 0) {
+                // the pass's 64 result columns (bf16, as stored) are one reduction slab of the second layer
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const bf16x8_t pf = *(const bf16x8_t*)(tile + prow * T_LD + kk * 16 + lhi * 8);
+                    const int c = (kk & 1) * 2 + lhi;
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const int nr = t * 32 + l32;
+                        const bf16x8_t wf = *(const bf16x8_t*)(W2s + ((kk >> 1) * 64 + nr) * 64 + ((c ^ swz(nr)) * 16));
+                        acc2[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, acc2[t], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (CHAIN) {
+        if (k_out2 <= 0) return;
+        __syncthreads();                               // the last pass's tile has been read
+        const long long trow2 = (long long)a.gt.row[g] * ch.tab_ld;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = t * 32 + q * 8 + lhi * 4;
+                float4 s4 = make_float4(1.f, 1.f, 1.f, 1.f), h4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (col < k_out2) {
+                    if (ch.scale) s4 = *(const float4*)(ch.scale + trow2 + col);
+                    if (ch.shift) h4 = *(const float4*)(ch.shift + trow2 + col);
+                }
+                float v[4] = {acc2[t][4 * q] * s4.x + h4.x, acc2[t][4 * q + 1] * s4.y + h4.y, acc2[t][4 * q + 2] * s4.z + h4.z,
+                              acc2[t][4 * q + 3] * s4.w + h4.w};
+                if (ch.act == DS_ACT_RELU) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                }
+                uint2 o;
+                o.x = f2bf2(v[0], v[1]);
+                o.y = f2bf2(v[2], v[3]);
+                *(uint2*)(tile + prow * T_LD + col) = o;
+            }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = prow8 + 32 * i;
+            if (rowC[row] >= 0 && pc8 < k_out2) *(uint4*)(ch.C + rowR[row] + pc8) = *(const uint4*)(tile + row * T_LD + pc8);
+        }
     }
 }
 
 }  // namespace
 
-// 1x1 / linear layers whose widest input slice is at most 64 channels, bf16 output, no activation or ReLU, one
-// segment; DS_EUNSUPPORTED otherwise (the caller then uses the general kernel)
-int32_t ds_launch_thin(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
-    if (max_mtiles <= 0 || max_kout <= 0) return DS_OK;
+namespace {
+
+int32_t thin_supported(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, int* kmax_out) {
     if (a.K > 1 || a.stride > 1 || a.pad > 0 || a.n_seg != 1 || a.out_f32 || (a.act != DS_ACT_NONE && a.act != DS_ACT_RELU))
         return DS_EUNSUPPORTED;
     int kmax = 0;
@@ -209,24 +303,68 @@ int32_t ds_launch_thin(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     if (kmax > 128 || (kmax > 64 && !a.R) || max_kout < 128) return DS_EUNSUPPORTED;
     const long long slots = (long long)max_mtiles * BM / (a.rows > 0 ? a.rows : 1) + 1;
     if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL) return DS_EUNSUPPORTED;
+    *kmax_out = kmax;
+    return DS_OK;
+}
+
+int32_t thin_configure() {
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute((const void*)thin_kernel<true, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(2)) != hipSuccess ||
-            hipFuncSetAttribute((const void*)thin_kernel<false, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(2)) != hipSuccess ||
-            hipFuncSetAttribute((const void*)thin_kernel<true, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(4)) != hipSuccess ||
-            hipFuncSetAttribute((const void*)thin_kernel<false, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(4)) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)thin_kernel<true, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(2)) != hipSuccess ||
+            hipFuncSetAttribute((const void*)thin_kernel<false, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(2)) != hipSuccess ||
+            hipFuncSetAttribute((const void*)thin_kernel<true, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(4)) != hipSuccess ||
+            hipFuncSetAttribute((const void*)thin_kernel<false, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(4)) != hipSuccess ||
+            hipFuncSetAttribute((const void*)thin_kernel<true, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_chain()) != hipSuccess)
             DS_FAIL(DS_EHIP, "thin layer: cannot reserve %d bytes of LDS", smem_bytes(4));
         configured = true;
     }
+    return DS_OK;
+}
+
+}  // namespace
+
+// 1x1 / linear layers whose widest input slice is at most 64 channels, bf16 output, no activation or ReLU, one
+// segment; DS_EUNSUPPORTED otherwise (the caller then uses the general kernel)
+int32_t ds_launch_thin(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
+    if (max_mtiles <= 0 || max_kout <= 0) return DS_OK;
+    int kmax = 0;
+    if (thin_supported(a, max_mtiles, max_kout, &kmax) != DS_OK) return DS_EUNSUPPORTED;
+    const int32_t rc = thin_configure();
+    if (rc != DS_OK) return rc;
     ProfScope prof(DS_K_GEMM, s);
     const dim3 grid((unsigned)max_mtiles), block(NT);
+    ThinChain none;
+    memset(&none, 0, sizeof(none));
     if (kmax <= 64) {
-        if (a.R) hipLaunchKernelGGL((thin_kernel<true, 2>), grid, block, smem_bytes(2), s, a, max_mtiles);
-        else hipLaunchKernelGGL((thin_kernel<false, 2>), grid, block, smem_bytes(2), s, a, max_mtiles);
+        if (a.R) hipLaunchKernelGGL((thin_kernel<true, 2, false>), grid, block, smem_bytes(2), s, a, max_mtiles, none);
+        else hipLaunchKernelGGL((thin_kernel<false, 2, false>), grid, block, smem_bytes(2), s, a, max_mtiles, none);
     } else {
-        if (a.R) hipLaunchKernelGGL((thin_kernel<true, 4>), grid, block, smem_bytes(4), s, a, max_mtiles);
-        else hipLaunchKernelGGL((thin_kernel<false, 4>), grid, block, smem_bytes(4), s, a, max_mtiles);
+        if (a.R) hipLaunchKernelGGL((thin_kernel<true, 4, false>), grid, block, smem_bytes(4), s, a, max_mtiles, none);
+        else hipLaunchKernelGGL((thin_kernel<false, 4, false>), grid, block, smem_bytes(4), s, a, max_mtiles, none);
     }
     DS_CHECK_LAUNCH("thin layer");
+    return DS_OK;
+}
+
+// The same layer (input slices up to 64 channels, residual addressed like the output) followed, inside the workgroup, by a
+// second 1x1 layer over the result rows with at most 64 output channels per group; DS_EUNSUPPORTED otherwise (the
+// caller then launches the two layers one after the other)
+int32_t ds_launch_thin_chain(const GemmArgs& a, const ThinChain& ch, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
+    if (max_mtiles <= 0 || max_kout <= 0) return DS_EUNSUPPORTED;
+    int kmax = 0;
+    if (thin_supported(a, max_mtiles, max_kout, &kmax) != DS_OK || kmax > 64) return DS_EUNSUPPORTED;
+    if (!a.R || !a.r_use_index || a.r_sample_stride != a.c_sample_stride || a.r_ld != a.c_ld) return DS_EUNSUPPORTED;
+    if (!ch.Wt || !ch.C || (ch.act != DS_ACT_NONE && ch.act != DS_ACT_RELU) || (ch.tab_ld % 4)) return DS_EUNSUPPORTED;
+    // 16-byte pieces of the second output and of its weights, float4 reads of its batch-norm constants
+    if ((ch.c_sample_stride % 8) || (ch.c_ld > 0 && ch.c_ld % 8) || (ch.w_ld % 8) ||
+        (((uintptr_t)ch.scale | (uintptr_t)ch.shift | (uintptr_t)ch.C | (uintptr_t)ch.Wt) & 15))
+        return DS_EUNSUPPORTED;
+    for (int t = 0; t < a.gt.T; ++t)
+        if (ch.k_out[t] > 64 || (ch.k_out[t] > 0 && ch.k_out[t] % 8)) return DS_EUNSUPPORTED;
+    const int32_t rc = thin_configure();
+    if (rc != DS_OK) return rc;
+    ProfScope prof(DS_K_GEMM, s);
+    hipLaunchKernelGGL((thin_kernel<true, 2, true>), dim3((unsigned)max_mtiles), dim3(NT), smem_bytes_chain(), s, a, max_mtiles, ch);
+    DS_CHECK_LAUNCH("chained thin layers");
     return DS_OK;
 }

@@ -155,6 +155,17 @@ def test_resnet_small_all_samples(gpu_lib):
     assert relerr(l3[5].cpu().numpy(), want) < TOL
 
 
+def test_resnet_chained_blocks_ragged_rows_all_samples(gpu_lib):
+    # three blocks per early stage at 48 x 48 input: 144 and 36 rows per sample, so the row tiles of the launches that
+    # run a block's last convolution together with the next block's first one straddle samples and end in a partial tile
+    arch = WL.resnet_arch(image=48, width_div=2, blocks=(3, 3, 1, 1))
+    params = WL.resnet_params(arch, S + 140)
+    B = 21
+    imgs = WL.images(S + 141, B, 48)
+    lb = _rn_bias(S + 142, B, 4)
+    _rn_case(gpu_lib, arch, params, imgs, lb, range(B))
+
+
 def test_resnet_dynamic_depth_small_all_samples(gpu_lib):
     # 8 routes per stage: 4 widths x (all blocks | one block fewer); 64 groups per stage.  Samples on a
     # shallow route must come through the skipped blocks untouched while their neighbours are updated.
