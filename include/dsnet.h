@@ -150,6 +150,20 @@ int32_t ds_sliced_linear(const void* x, int64_t x_ld, const void* w, int64_t w_l
                          int32_t rows, int32_t act, const void* residual, int64_t r_ld, void* y,
                          int32_t y_dtype, int64_t y_ld, void* ws, size_t ws_bytes, void* stream);
 
+/* ds_sliced_linear for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, results and errors, without the
+ * workspace.  The row-tile list the kernels read is kept in a device array built into the library
+ * (DS_NOALLOC_MAX_TILES records of 16 bytes, 512 KiB + 256 bytes per GPU the library has run on, held
+ * until the process ends); the call allocates and frees nothing and switches the ds_profile_* recording
+ * off for its duration.  (B * rows + 127) / 128 + T must not exceed DS_NOALLOC_MAX_TILES
+ * (DS_EWORKSPACE otherwise, before any launch).  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams or threads) race and must be ordered by the caller. */
+#define DS_NOALLOC_MAX_TILES 32768
+int32_t ds_sliced_linear_noalloc(const void* x, int64_t x_ld, const void* w, int64_t w_ld, int32_t N_full,
+                                 int32_t K_full, const float* bias, const ds_groups* g, int32_t B,
+                                 int32_t rows, int32_t act, const void* residual, int64_t r_ld, void* y,
+                                 int32_t y_dtype, int64_t y_ld, void* stream);
+
 /* Sliced dense convolution with split batch-norm (Eq. 9 and Eq. 14):
  * y[b, :c_out] = act(scale[row, :c_out] * (W[:c_out, :c_in] * x[b, :c_in]) + shift[row, :c_out]
  *                    + residual[b, :c_out]),  row = table_row[t].

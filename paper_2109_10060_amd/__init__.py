@@ -31,9 +31,9 @@ DS_ARCH_MBNET, DS_ARCH_RESNET, DS_ARCH_VIT, DS_ARCH_VIT_STEM = 1, 2, 3, 4
 EXPORTS = [
     "ds_last_error", "ds_version", "ds_bn_fold", "ds_bn_stats_workspace", "ds_bn_stats_accumulate", "ds_bn_stats_finish", "ds_gate_workspace", "ds_gate", "ds_gate_double_workspace",
     "ds_gate_double", "ds_route_bucket",
-    "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_conv_workspace", "ds_sliced_conv",
+    "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_linear_noalloc", "ds_sliced_conv_workspace", "ds_sliced_conv",
     "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_dwconv_spatial", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
-    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_forward_parts_workspace", "ds_forward_parts", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
+    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_forward_taps", "ds_forward_parts_workspace", "ds_forward_parts", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
 ]
 
 
@@ -223,6 +223,19 @@ def ds_sliced_linear(x, w, bias, groups: ds_groups, act=DS_ACT_NONE, residual=No
                               act, _ptr(residual), ctypes.c_int64(residual.shape[-1] if residual is not None else 0),
                               _ptr(y), DS_BF16 if y.dtype == torch.bfloat16 else DS_F32, ctypes.c_int64(y.shape[-1]),
                               _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return y
+
+
+def ds_sliced_linear_noalloc(x, w, bias, groups: ds_groups, y, act=DS_ACT_NONE, residual=None):
+    """ds_sliced_linear without a workspace (the library's built-in scratch); y is required, nothing is allocated."""
+    B, rows, x_ld = x.shape
+    N_full, K_full = w.shape
+    _chk(load().ds_sliced_linear_noalloc(_ptr(x, torch.bfloat16), ctypes.c_int64(x_ld), _ptr(w, torch.bfloat16),
+                                         ctypes.c_int64(w.stride(0)), N_full, K_full, _ptr(bias), ctypes.byref(groups), B,
+                                         rows, act, _ptr(residual),
+                                         ctypes.c_int64(residual.shape[-1] if residual is not None else 0), _ptr(y),
+                                         DS_BF16 if y.dtype == torch.bfloat16 else DS_F32, ctypes.c_int64(y.shape[-1]),
+                                         _stream()))
     return y
 
 

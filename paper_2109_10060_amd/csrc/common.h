@@ -249,6 +249,12 @@ struct ProfScope {
     ~ProfScope();
 };
 
+struct ProfPause {   // no launch inside its scope is recorded (and no event is created)
+    bool was;
+    ProfPause();
+    ~ProfPause();
+};
+
 // ---- small dense layer on one vector per item --------------------------------------
 struct FcArgs {
     const float* v_partial;   // [items][splits][C] partial sums (scaled by v_scale), or

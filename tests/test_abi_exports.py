@@ -54,6 +54,11 @@ def test_host_validation_returns_codes_without_a_gpu():
     assert lib.ds_sliced_mhsa(None, 2, 300, 64, None, None, None, None, 2, 64, ctypes.byref(g), None, None, None,
                               ctypes.c_size_t(0), None) == ds.DS_EUNSUPPORTED
     assert lib.ds_sliced_linear_workspace(64, 197, 4) >= 16 + 8 * (64 * 197 // 128 + 4)
+    # the entry point without a workspace refuses what its built-in scratch cannot hold, before any device call
+    g.k_in[0], g.k_out[0] = 16, 8
+    rc = lib.ds_sliced_linear_noalloc(None, ctypes.c_int64(16), None, ctypes.c_int64(16), 8, 16, None, ctypes.byref(g), 1,
+                                      128 * 40000, 0, None, ctypes.c_int64(0), None, 1, ctypes.c_int64(8), None)
+    assert rc == ds.DS_EWORKSPACE and b"built-in scratch" in lib.ds_last_error()
 
 
 def test_host_validation_of_the_spatial_statistics_and_forward_entry_points():
