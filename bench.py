@@ -209,6 +209,8 @@ def main():
     ap.add_argument("--event-every", type=int, default=5,
                     help="bracket the kernels of every N-th timed step with HIP events (1 = every step)")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class table to stderr")
+    ap.add_argument("--layers-json", default="", metavar="PATH",
+                    help="write the per-launch algorithmic work list of one step (for `profiling layers`)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB mebibytes 5 times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -281,6 +283,8 @@ def main():
     rt = routes.cpu().numpy()
     cost = {"mbnet": C.mbnet_cost, "mbnet_pp": C.mbnet_cost, "resnet": C.resnet_cost, "resnet_pp": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost,
             "vit_pp": C.vit_cost}[args.workload](arch, rt)
+    if args.layers_json:
+        json.dump(cost.launches, open(args.layers_json, "w"))
     roofline = None
     kernels = {}
     if prof:

@@ -300,6 +300,16 @@ size_t ds_forward_workspace(const ds_net* net, int32_t B);
 int32_t ds_forward(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
                    const float* logit_bias, float* logits, int32_t* routes_out, void* ws,
                    size_t ws_bytes, void* stream);
+/* ds_forward that also hands out the outputs of chosen blocks, for checking a network layer by layer against a
+ * reference (Section 5.2 assemblies; a block is a depthwise-separable block of DS-MBNet, a bottleneck of DS-ResNet
+ * counted over all stages, a transformer layer of DS-ViT, each numbered from 0 in execution order).  tap_blocks:
+ * host int32 [n_taps] (n_taps <= 64); tap_out: host array of n_taps device buffers, bf16 [B, rows, C_stored] of that
+ * block's output resolution and stored width, original sample order, channels-last; of each sample only its valid
+ * slice [rows, :c_out] is written (a sample whose route skips the block is not written at all).  Everything else
+ * as ds_forward, same workspace. */
+int32_t ds_forward_taps(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
+                        const float* logit_bias, float* logits, int32_t* routes_out, int32_t n_taps,
+                        const int32_t* tap_blocks, void* const* tap_out, void* ws, size_t ws_bytes, void* stream);
 /* The same forward pass with the batch run as `parts` (1..4) concurrent pieces: samples are independent (Section 3.1,
  * Eq. 1: the route and the sliced computation are per input), so the batch is cut into equal shares (rounded up to
  * a multiple of 8 samples), each share is gated, bucketed and computed on its own — the first on `stream`, the others

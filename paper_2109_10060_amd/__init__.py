@@ -342,6 +342,24 @@ def ds_forward(net: "Net", images, route_override=None, logit_bias=None, logits=
     return logits, routes
 
 
+def ds_forward_taps(net: "Net", images, taps: dict, route_override=None, logit_bias=None, ws=None):
+    """ds_forward that also fills taps[block index] (bf16 [B, rows, C_stored] device tensors, original sample order)
+    with the outputs of those blocks.  Returns (logits, routes)."""
+    lib = load()
+    B = images.shape[0]
+    logits = torch.empty((B, net.num_classes), dtype=torch.float32, device=images.device)
+    routes = torch.empty((net.n_gates, B), dtype=torch.int32, device=images.device)
+    if ws is None:
+        ws = net.workspace(B)
+    ids = sorted(taps)
+    c_ids = (ctypes.c_int32 * max(len(ids), 1))(*ids)
+    c_out = (ctypes.c_void_p * max(len(ids), 1))(*[_ptr(taps[i], torch.bfloat16).value for i in ids])
+    _chk(lib.ds_forward_taps(ctypes.byref(net.c_struct), _ptr(images, torch.bfloat16), B, _ptr(route_override),
+                             _ptr(logit_bias), _ptr(logits), _ptr(routes), len(ids), c_ids, c_out, _ptr(ws),
+                             ctypes.c_size_t(ws.numel()), _stream()))
+    return logits, routes
+
+
 def ds_forward_parts(net: "Net", images, parts: int, route_override=None, logit_bias=None, logits=None, routes=None, ws=None):
     """ds_forward with the batch run as `parts` concurrent pieces (the first on the current stream, the others on
     streams of the library).  Same results; ws needs net.workspace(B, parts)."""

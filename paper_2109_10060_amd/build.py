@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdsnet.so")
-SOURCES = ["api.hip", "gemm.hip", "route.hip", "elementwise.hip", "attention.hip", "forward.hip", "profile.hip", "stem.hip", "fc.hip", "conv3.hip", "dwpw.hip", "thin.hip"]
+SOURCES = ["api.hip", "gemm.hip", "route.hip", "elementwise.hip", "attention.hip", "forward.hip", "profile.hip", "stem.hip", "fc.hip", "conv3.hip", "dwpw.hip", "thin.hip", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-I", INCLUDE, "-I", CSRC]
 

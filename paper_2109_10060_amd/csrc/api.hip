@@ -5,6 +5,10 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 #include "common.h"
 
 static thread_local char g_err[512] = "";
@@ -14,6 +18,20 @@ void ds_set_error(const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+}
+
+int32_t ds_reserve_lds(const void* kernel, int bytes, const char* what) {
+    static std::mutex mu;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) DS_FAIL(DS_EHIP, "%s: no current device", what);
+    std::lock_guard<std::mutex> lock(mu);
+    const auto key = std::make_pair(dev, kernel);
+    if (done.count(key)) return DS_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        DS_FAIL(DS_EHIP, "%s: cannot reserve %d bytes of LDS", what, bytes);
+    done.insert(key);
+    return DS_OK;
 }
 
 extern "C" const char* ds_last_error(void) { return g_err; }

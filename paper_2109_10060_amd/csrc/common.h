@@ -42,6 +42,9 @@ void ds_set_error(const char* fmt, ...);
         if (e__ != hipSuccess) DS_FAIL(DS_EHIP, "%s: %s", what, hipGetErrorString(e__)); \
     } while (0)
 
+// reserves `bytes` of dynamic LDS for a kernel: once per (device, kernel), safe to call from any thread
+int32_t ds_reserve_lds(const void* kernel, int bytes, const char* what);
+
 static inline bool ds_aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 static inline size_t ds_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -288,12 +288,10 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
 
 template <bool HASR>
 int32_t launch(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
-    static bool configured = false;
     auto kern = conv3_kernel<HASR>;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess)
-            DS_FAIL(DS_EHIP, "sliced 3x3 conv: cannot reserve %d bytes of LDS", SMEM);
-        configured = true;
+    {
+        const int32_t rc = ds_reserve_lds((const void*)kern, SMEM, "sliced 3x3 conv");
+        if (rc) return rc;
     }
     const int ny = (max_kout + BN - 1) / BN;
     const unsigned grid = (unsigned)(((max_mtiles + 7) / 8) * ny * 8);
@@ -310,5 +308,6 @@ int32_t ds_launch_conv3(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout,
     if (a.K != 3 || a.stride != 1 || a.pad != 1 || a.n_seg != 1 || a.Ho != a.H || a.Wo != a.W || a.rows != a.H * a.W ||
         BM + 2 * (a.W + 1) > RMAX)
         return DS_EUNSUPPORTED;
+    if (((long long)max_kout * a.w_ld + 9 * a.w_tap_stride) * 2 >= 0x7fffffffLL) return DS_EUNSUPPORTED;   // 32-bit weight offsets
     return a.R ? launch<true>(a, max_mtiles, max_kout, s) : launch<false>(a, max_mtiles, max_kout, s);
 }

@@ -430,18 +430,14 @@ int32_t ds_launch_fc(const FcArgs& a, int32_t w_bf16, int32_t acc_f64, int32_t k
     const unsigned gy = (unsigned)((a.items + TI - 1) / TI);
     ProfScope prof(kind, s);
     const bool vec = (a.C % 8) == 0 && (a.w_ld % 8) == 0 && (a.v_rows == nullptr || (a.v_row_stride % 4) == 0);
-    static const int use_mfma = [] {
-        const char* e = getenv("DSNET_FC_MFMA");        // tuning knob: 0 keeps the classifier on the vector kernel
-        return e ? atoi(e) : 1;
-    }();
-    if (use_mfma && vec && w_bf16 && !acc_f64 && a.relu == 0 && (a.v_rows ? (a.v_row_stride % 8) == 0 : a.splits == 1) &&
+    if (vec && w_bf16 && !acc_f64 && a.relu == 0 && (a.v_rows ? (a.v_row_stride % 8) == 0 : a.splits == 1) &&
         a.items >= 32) {
         const dim3 grid((unsigned)((a.n_out + 31) / 32), (unsigned)((a.items + 31) / 32));
         hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(64 * FC_NW), 0, s, a);
         DS_CHECK_LAUNCH("fc (matrix cores)");
         return DS_OK;
     }
-    if (use_mfma && vec && !w_bf16 && acc_f64 && !a.v_rows && a.items >= 16) {
+    if (vec && !w_bf16 && acc_f64 && !a.v_rows && a.items >= 16) {
         const dim3 grid((unsigned)((a.n_out + 15) / 16), (unsigned)((a.items + 15) / 16));
         hipLaunchKernelGGL(fc_mfma64_kernel, grid, dim3(256), 0, s, a);
         DS_CHECK_LAUNCH("fc (fp64 matrix cores)");

@@ -59,6 +59,45 @@ struct MList {  // m-tile list of one (bucketing, rows-per-sample) pair
         if (rc__) return rc__; \
     } while (0)
 
+// ---- intermediate activations for inspection (ds_forward_taps) ---------------------------------
+// A tap copies one block's output from the slot-major packed layout to [sample][row][C_full] in the original sample
+// order; only the valid slice of each sample is written.
+struct Taps {
+    int n;
+    const int32_t* ids;      // host: block indices in execution order
+    void* const* out;        // host array of device buffers
+};
+
+__global__ void unpack_slots_kernel(const bf16_t* x, int64_t x_sstride, int x_ld, const int32_t* perm, const int32_t* slot_group,
+                                    const GroupTable gt, int rows, int c_full, bf16_t* out) {
+    const int slot = blockIdx.y;
+    const int w = gt.k_out[slot_group ? slot_group[slot] : 0];
+    if (w <= 0) return;
+    const int ld = x_ld > 0 ? x_ld : w, w8 = w >> 3;
+    const int64_t n = (int64_t)rows * w8;
+    const bf16_t* src = x + (int64_t)slot * x_sstride;
+    bf16_t* dst = out + (int64_t)(perm ? perm[slot] : slot) * rows * c_full;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / w8;
+        const int c = (int)(i - r * w8) * 8;
+        *(uint4*)(dst + r * c_full + c) = *(const uint4*)(src + r * ld + c);
+    }
+}
+
+// copies block `id`'s output when it is among the requested taps
+int32_t tap_block(const Taps* taps, int id, const bf16_t* x, int64_t x_sstride, int x_ld, const int32_t* perm,
+                  const int32_t* slot_group, const GroupTable& gt, int B, int rows, int c_full, hipStream_t s) {
+    if (!taps) return DS_OK;
+    for (int i = 0; i < taps->n; ++i) {
+        if (taps->ids[i] != id) continue;
+        ProfScope prof(DS_K_MISC, s);
+        hipLaunchKernelGGL(unpack_slots_kernel, dim3(8, B), dim3(256), 0, s, x, x_sstride, x_ld, perm, slot_group, gt, rows,
+                           c_full, (bf16_t*)taps->out[i]);
+        DS_CHECK_LAUNCH("tap copy");
+    }
+    return DS_OK;
+}
+
 // pointwise / KxK convolution through the grouped GEMM
 int32_t conv_gemm(const bf16_t* A, const int32_t* a_index, int64_t a_sstride, int a_ld, const bf16_t* Wt, int C_I_full,
                   int K, int stride, int pad, int H, int W, const float* scale, const float* shift, int tab_ld,
@@ -174,7 +213,8 @@ void plan_mb(const MbDesc& d, int B, Bump& bp, MbPlan* p) {
 }
 
 int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int B, const int32_t* route_override,
-                   const float* logit_bias, float* logits, int32_t* routes_out, const MbPlan& p, hipStream_t s) {
+                   const float* logit_bias, float* logits, int32_t* routes_out, const MbPlan& p, hipStream_t s,
+                   const Taps* taps) {
     const void* const* P = net->params;
     int r = (d.image + 2 - 3) / 2 + 1;
     RC(ds_launch_set_offsets(p.off1, B, s));
@@ -240,6 +280,7 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
                                               (const float*)Q[5], oth, s);
             if (rc == DS_OK) {
                 bf16_t* t = cur; cur = oth; oth = t;
+                RC(tap_block(taps, i, cur, (int64_t)r * r * co, co, nullptr, nullptr, gpw, B, r * r, co, s));
                 continue;
             }
             if (rc != DS_EUNSUPPORTED) return rc;
@@ -277,6 +318,8 @@ int32_t forward_mb(const ds_net* net, const MbDesc& d, const bf16_t* images, int
         RC(conv_gemm(oth, nullptr, (int64_t)r * r * ci, phase ? 0 : ci, (const bf16_t*)Q[3], ci, 1, 1, 0, r, r,
                      (const float*)Q[4], (const float*)Q[5], co, nullptr, cur, (int64_t)r * r * co, phase ? 0 : co,
                      offsets, ml, gpw, DS_ACT_RELU, s));
+        RC(tap_block(taps, i, cur, (int64_t)r * r * co, phase ? 0 : co, phase ? p.perm : nullptr,
+                     phase ? p.slot_group : nullptr, gpw, B, r * r, co, s));
     }
     const void* const* F = P + 3 + 6 * d.nb + 4;
     const int cl = d.blk[3 * (d.nb - 1) + 1];
@@ -371,7 +414,8 @@ void plan_rn(const RnDesc& d, int B, Bump& bp, RnPlan* p) {
 // Bs: batch stride of the caller's gate-major arrays (route_override, logit_bias, routes_out); B when the whole batch
 // is run as one part
 int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int B, int Bs, const int32_t* route_override,
-                   const float* logit_bias, float* logits, int32_t* routes_out, const RnPlan& p, hipStream_t s) {
+                   const float* logit_bias, float* logits, int32_t* routes_out, const RnPlan& p, hipStream_t s,
+                   const Taps* taps) {
     const void* const* P = net->params;
     const int T = d.T, G = rn_groups(d);
     const bool pairs = !d.single_gate;      // group id = q * T + q_prev, or q alone (then q_prev = q)
@@ -391,6 +435,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
     int xi = 1;                    // index of X in buf[]
     int c_prev_full = d.stem_out;
     const void* const* Q = P + 3;
+    int block_id = 0;              // blocks counted over all stages, in execution order
     for (int st = 0; st < 4; ++st) {
         const int w = d.widths[st], nb = d.blocks[st];
         const int rin = r;
@@ -459,7 +504,7 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
         bf16_t *Y1 = free4[0], *Y2 = free4[1], *Pj = free4[2], *Z = free4[3];
         const int64_t x_ss = (int64_t)rin * rin * c_prev_full;
         bool y1_ready = false;         // the previous block's last launch has already run this block's first convolution
-        for (int b = 0; b < nb; ++b) {
+        for (int b = 0; b < nb; ++b, ++block_id) {
             const bool first = b == 0;
             const int bs = first ? stride : 1;
             const int rb = first ? rin : rout;  // resolution of the block input
@@ -479,8 +524,6 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
             const int32_t* in_idx = first ? src : nullptr;
             const int64_t in_ss = first ? x_ss : (int64_t)rout * rout * 4 * w;
             const int in_full = first ? c_prev_full : 4 * w;
-            bf16_t* outbuf = first ? Z : (Z == free4[3] ? (bf16_t*)X : free4[3]);
-            (void)outbuf;
             const bf16_t* shortcut;
             if (first) {
                 RC(conv_gemm(in, in_idx, in_ss, 0, (const bf16_t*)L[9], in_full, 1, bs, 0, rb, rb, (const float*)L[10],
@@ -518,6 +561,8 @@ int32_t forward_rn(const ds_net* net, const RnDesc& d, const bf16_t* images, int
             RC(conv_gemm(Y2, nullptr, (int64_t)rout * rout * w, 0, (const bf16_t*)L[6], w, 1, 1, 0, rout, rout,
                          (const float*)L[7], (const float*)L[8], 4 * w, shortcut, Z, (int64_t)rout * rout * 4 * w, 0,
                          p.offs[st], ml_out, g3, DS_ACT_RELU, s, next_any ? &ch : nullptr, &y1_ready));
+            RC(tap_block(taps, block_id, Z, (int64_t)rout * rout * 4 * w, 0, p.perm[st], p.slot_group[st], gpj, B, rout * rout,
+                         4 * w, s));
         }
         X = Z;
         for (int i = 0; i < 5; ++i)
@@ -638,7 +683,8 @@ int32_t linear_gemm(const bf16_t* A, int64_t a_ss, int a_ld, const bf16_t* Wt, i
 }
 
 int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, int B, const int32_t* route_override,
-                    const float* logit_bias, float* logits, int32_t* routes_out, const VitPlan& p, hipStream_t s) {
+                    const float* logit_bias, float* logits, int32_t* routes_out, const VitPlan& p, hipStream_t s,
+                    const Taps* taps) {
     const void* const* P = net->params + d.pbase;
     const int np = d.N - 1, Hd = d.H * d.dh, T = d.T;
     const int kp = d.stem_dim ? d.stem_dim : 3 * d.patch * d.patch;   // reduction length of one embedding tap
@@ -776,6 +822,7 @@ int32_t forward_vit(const ds_net* net, const VitDesc& d, const bf16_t* images, i
                        (int64_t)d.N * d.M, 0, 0, d.N, 1, 0, 0, 0, p.offs, ml_t, g1, DS_ACT_GELU, s));
         RC(linear_gemm(p.h, (int64_t)d.N * d.M, 0, (const bf16_t*)L[10], d.M, (const float*)L[11], p.x, x_ss, 0, 1, p.x,
                        x_ss, 0, 0, d.N, 1, 0, 0, 0, p.offs, ml_t, g2, DS_ACT_NONE, s));
+        RC(tap_block(taps, l, p.x, x_ss, 0, p.perm, p.slot_group, g2, B, d.N, d.D, s));
     }
     const void* const* F = P + 4 + 12 * d.depth;
     RC(ds_launch_layernorm(xv, av, (const float*)F[0], (const float*)F[1], eps, p.slot_group, fq, B, d.N, 0, 1, s));
@@ -872,7 +919,8 @@ int32_t check_forward(const char* who, const ds_net* net, const void* images, in
 // Samples b0 .. b0 + Bp - 1 of a batch of Bs (a checked description): the caller's arrays are addressed at the
 // part's offset, the gate-major ones with the whole batch as their stride; ws holds ds_forward_workspace(net, Bp).
 int32_t run_part(const ds_net* net, const bf16_t* images, int b0, int Bp, int Bs, const int32_t* route_override,
-                 const float* logit_bias, float* logits, int32_t* routes_out, void* ws, hipStream_t s) {
+                 const float* logit_bias, float* logits, int32_t* routes_out, void* ws, hipStream_t s,
+                 const Taps* taps = nullptr) {
     Bump bp = {(char*)ws, 0};
     if (net->arch == DS_ARCH_MBNET) {
         MbDesc d;
@@ -881,7 +929,7 @@ int32_t run_part(const ds_net* net, const bf16_t* images, int b0, int Bp, int Bs
         plan_mb(d, Bp, bp, &p);
         return forward_mb(net, d, images + (size_t)b0 * 3 * d.image * d.image, Bp, route_override ? route_override + b0 : nullptr,
                           logit_bias ? logit_bias + (size_t)b0 * d.T : nullptr, logits + (size_t)b0 * d.classes,
-                          routes_out ? routes_out + b0 : nullptr, p, s);
+                          routes_out ? routes_out + b0 : nullptr, p, s, taps);
     }
     if (net->arch == DS_ARCH_RESNET) {
         RnDesc d;
@@ -890,7 +938,7 @@ int32_t run_part(const ds_net* net, const bf16_t* images, int b0, int Bp, int Bs
         plan_rn(d, Bp, bp, &p);
         return forward_rn(net, d, images + (size_t)b0 * 3 * d.image * d.image, Bp, Bs, route_override ? route_override + b0 : nullptr,
                           logit_bias ? logit_bias + (size_t)b0 * d.T : nullptr, logits + (size_t)b0 * d.classes,
-                          routes_out ? routes_out + b0 : nullptr, p, s);
+                          routes_out ? routes_out + b0 : nullptr, p, s, taps);
     }
     VitDesc d;
     VitPlan p;
@@ -898,7 +946,7 @@ int32_t run_part(const ds_net* net, const bf16_t* images, int b0, int Bp, int Bs
     plan_vit(d, Bp, bp, &p);
     return forward_vit(net, d, images + (size_t)b0 * 3 * d.image * d.image, Bp, route_override ? route_override + b0 : nullptr,
                        logit_bias ? logit_bias + (size_t)b0 * d.T : nullptr, logits + (size_t)b0 * d.classes,
-                       routes_out ? routes_out + b0 : nullptr, p, s);
+                       routes_out ? routes_out + b0 : nullptr, p, s, taps);
 }
 
 // side streams and fork / join events of ds_forward_parts, made on first use, one set per device, kept until the
@@ -942,6 +990,22 @@ extern "C" int32_t ds_forward(const ds_net* net, const void* images, int32_t B, 
     const size_t need = ds_forward_workspace(net, B);
     if (!ws || ws_bytes < need || (((uintptr_t)ws) & 255u)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
     return run_part(net, (const bf16_t*)images, 0, B, B, route_override, logit_bias, logits, routes_out, ws, (hipStream_t)stream);
+}
+
+extern "C" int32_t ds_forward_taps(const ds_net* net, const void* images, int32_t B, const int32_t* route_override,
+                                   const float* logit_bias, float* logits, int32_t* routes_out, int32_t n_taps,
+                                   const int32_t* tap_blocks, void* const* tap_out, void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "ds_forward_taps";
+    if (n_taps < 0 || n_taps > 64 || (n_taps > 0 && (!tap_blocks || !tap_out))) DS_FAIL(DS_EINVAL, "%s: bad tap list", who);
+    for (int i = 0; i < n_taps; ++i)
+        if (tap_blocks[i] < 0 || !tap_out[i] || !ds_aligned16(tap_out[i])) DS_FAIL(DS_EINVAL, "%s: tap %d: negative block or bad buffer", who, i);
+    const int32_t rc = check_forward(who, net, images, B, logits);
+    if (rc || B == 0) return rc;
+    const size_t need = ds_forward_workspace(net, B);
+    if (!ws || ws_bytes < need || (((uintptr_t)ws) & 255u)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes, 256-byte aligned", who, need);
+    const Taps taps = {n_taps, tap_blocks, tap_out};
+    return run_part(net, (const bf16_t*)images, 0, B, B, route_override, logit_bias, logits, routes_out, ws, (hipStream_t)stream,
+                    n_taps ? &taps : nullptr);
 }
 
 extern "C" size_t ds_forward_parts_workspace(const ds_net* net, int32_t B, int32_t parts) {

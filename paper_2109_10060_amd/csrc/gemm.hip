@@ -9,22 +9,21 @@
 // case the K*K taps are walked inside the reduction loop and the A operand is
 // gathered from the shifted input pixels (zero outside the image).
 //
-// Tiling: 128 x BN output tile per 256-thread workgroup (BN = 64, 128 or 256,
-// chosen from the widest slice of the layer), 4 wavefronts, each holding a grid
-// of v_mfma_f32_32x32x16_bf16 accumulators.  Operands go through LDS in 64-deep
-// slabs (128-byte rows, 16-byte chunks XOR-swizzled by row so stores and reads are
-// bank-conflict free); the next slab's global loads are issued into registers
-// before the current slab's 32 matrix instructions per wavefront and stored to
-// LDS after them.  The epilogue (split batch-norm scale and
-// shift or bias, residual, ReLU/GELU, bf16 rounding) re-reads the accumulators
-// through LDS so that every lane stores 4 consecutive channels of one row.
+// Tiling: 128 x 64 output tile per 256-thread workgroup, 4 wavefronts, each holding a 32 x 64 grid of
+// v_mfma_f32_32x32x16_bf16 accumulators (the dispatcher uses this shape for every layer: with ragged route
+// groups and slices as narrow as 64 channels the wider 128 x 128 / 128 x 256 instantiations lose more to
+// quantisation and residency than their lower operand traffic gains).  Operands go through one LDS tile in
+// 32-deep slabs, or 64-deep ones for reductions of 256 steps and more (64- or 128-byte rows, 16-byte chunks
+// XOR-swizzled by row so stores and reads are bank-conflict free); the next slab's global loads are issued into
+// registers before the current slab's matrix instructions and stored to LDS after them, and 5-6 resident
+// workgroups per compute unit hide each other's round trips.  The epilogue (split batch-norm scale and
+// shift or bias, residual, ReLU/GELU, bf16 rounding) re-reads the accumulators through LDS so that every lane
+// stores 4 consecutive channels of one row.
 //
 // Work items are (m-tile, n-tile) pairs with the n-tile fastest; the linear block
 // index is dealt round-robin to the 8 XCDs by the hardware, so each XCD is given
 // a contiguous run of work items and the blocks that share an activation tile hit
 // the same L2.
-#include <stdlib.h>
-
 #include "common.h"
 
 namespace {
@@ -373,12 +372,10 @@ __global__ void build_mtiles_kernel(const int32_t* offsets, int T, int rows, int
 template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV, bool HASR>
 int32_t launch(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
-    static bool configured = false;
     auto kern = gemm_kernel<WROWS, WCOLS, WMT, WNT, BK, CONV, HASR>;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::SMEM) != hipSuccess)
-            DS_FAIL(DS_EHIP, "sliced gemm: cannot reserve %d bytes of LDS", TL::SMEM);
-        configured = true;
+    {
+        const int32_t rc = ds_reserve_lds((const void*)kern, TL::SMEM, "sliced gemm");
+        if (rc) return rc;
     }
     const int ny = a.n_seg * ((max_kout + TL::BN - 1) / TL::BN);
     const unsigned grid = (unsigned)(((max_mtiles + 7) / 8) * ny * 8);
@@ -404,10 +401,6 @@ int32_t ds_build_mtiles(const int32_t* offsets, int32_t T, int32_t rows, void* l
 
 int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
     if (max_mtiles <= 0 || max_kout <= 0) return DS_OK;
-    static const int forced = [] {
-        const char* e = getenv("DSNET_GEMM_TILE");   // tuning knob: force the n-tile width (64, 128, 256)
-        return e ? atoi(e) : 0;
-    }();
     // ragged route slices favour the narrow 128x64 tile at high occupancy in every layer of the batch-256 networks.
     // Its slabs are 32 deep for short reductions and 64 deep from 256 reduction steps on: half the barriers and
     // twice the bytes in flight per workgroup outweigh the lower residency there (measured per layer: ViT MLP
@@ -416,17 +409,16 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     // the 8x8 patch embedding over 24 channels ran 144 -> 226 us with it)
     int kmax = 0;
     for (int t = 0; t < a.gt.T; ++t) kmax = a.gt.k_in[t] > kmax ? a.gt.k_in[t] : kmax;
-    const int bn = forced ? forced : ((kmax >= 64 && kmax * a.K * (a.Kw > 0 ? a.Kw : a.K) >= 256) ? 64 : 32);
-    // 32-bit byte offsets inside the kernel: the operands must span less than 2 GiB
+    const long long taps = (long long)a.K * (a.Kw > 0 ? a.Kw : a.K);
+    const bool deep = kmax >= 64 && kmax * taps >= 256;
+    // 32-bit byte offsets inside the kernel: activations and weights must each span less than 2 GiB
     const long long slots = (long long)max_mtiles * BM / (a.rows > 0 ? a.rows : 1) + 1;
     if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL)
         DS_FAIL(DS_EUNSUPPORTED, "sliced gemm: activation tensor spans 2 GiB or more");
+    if (((long long)a.n_seg * a.w_seg_stride + (long long)max_kout * a.w_ld + taps * a.w_tap_stride + kmax) * 2 >= 0x7fffffffLL)
+        DS_FAIL(DS_EUNSUPPORTED, "sliced gemm: weight tensor spans 2 GiB or more");
     const bool conv = a.K > 1 || a.stride > 1 || a.pad > 0;
-    static const int conv3 = [] {
-        const char* e = getenv("DSNET_CONV3");       // tuning knob: 0 sends 3x3 layers through the tap-walking kernel
-        return e ? atoi(e) : 1;
-    }();
-    if (conv && conv3 && !forced) {
+    if (conv) {
         const int32_t rc = ds_launch_conv3(a, max_mtiles, max_kout, s);
         if (rc != DS_EUNSUPPORTED) return rc;
     }
@@ -435,9 +427,7 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
                  : launch<__VA_ARGS__, true, false>(a, max_mtiles, max_kout, s))                       \
           : (a.R ? launch<__VA_ARGS__, false, true>(a, max_mtiles, max_kout, s)                        \
                  : launch<__VA_ARGS__, false, false>(a, max_mtiles, max_kout, s)))
-    if (bn == 32) return DS_GEMM_DISPATCH(4, 1, 1, 2, 32);   // 64-wide tile, 32-deep slabs
-    if (bn == 64) return DS_GEMM_DISPATCH(4, 1, 1, 2, 64);
-    if (bn == 128) return DS_GEMM_DISPATCH(2, 2, 2, 2, 64);
-    return DS_GEMM_DISPATCH(2, 2, 2, 4, 64);
+    if (!deep) return DS_GEMM_DISPATCH(4, 1, 1, 2, 32);   // 64-wide tile, 32-deep slabs
+    return DS_GEMM_DISPATCH(4, 1, 1, 2, 64);
 #undef DS_GEMM_DISPATCH
 }

@@ -33,6 +33,10 @@ ProfScope::~ProfScope() {
     if (rec >= 0) (void)hipEventRecord(g_pool[rec].b, s);
 }
 
+// recording creates HIP events on first use; entry points that must not allocate switch it off for their duration
+ProfPause::ProfPause() : was(g_on) { g_on = false; }
+ProfPause::~ProfPause() { g_on = was; }
+
 extern "C" int32_t ds_profile_enable(int32_t on) {
     g_on = on != 0;
     return DS_OK;

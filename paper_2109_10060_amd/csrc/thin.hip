@@ -303,21 +303,19 @@ int32_t thin_supported(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     if (kmax > 128 || (kmax > 64 && !a.R) || max_kout < 128) return DS_EUNSUPPORTED;
     const long long slots = (long long)max_mtiles * BM / (a.rows > 0 ? a.rows : 1) + 1;
     if (slots * a.a_sample_stride * 2 >= 0x7fffffffLL) return DS_EUNSUPPORTED;
+    if (((long long)max_kout * a.w_ld + kmax) * 2 >= 0x7fffffffLL) return DS_EUNSUPPORTED;   // 32-bit weight offsets
     *kmax_out = kmax;
     return DS_OK;
 }
 
 int32_t thin_configure() {
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)thin_kernel<true, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(2)) != hipSuccess ||
-            hipFuncSetAttribute((const void*)thin_kernel<false, 2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(2)) != hipSuccess ||
-            hipFuncSetAttribute((const void*)thin_kernel<true, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(4)) != hipSuccess ||
-            hipFuncSetAttribute((const void*)thin_kernel<false, 4, false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(4)) != hipSuccess ||
-            hipFuncSetAttribute((const void*)thin_kernel<true, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes_chain()) != hipSuccess)
-            DS_FAIL(DS_EHIP, "thin layer: cannot reserve %d bytes of LDS", smem_bytes(4));
-        configured = true;
-    }
+    const int32_t rc[5] = {ds_reserve_lds((const void*)thin_kernel<true, 2, false>, smem_bytes(2), "thin layer"),
+                           ds_reserve_lds((const void*)thin_kernel<false, 2, false>, smem_bytes(2), "thin layer"),
+                           ds_reserve_lds((const void*)thin_kernel<true, 4, false>, smem_bytes(4), "thin layer"),
+                           ds_reserve_lds((const void*)thin_kernel<false, 4, false>, smem_bytes(4), "thin layer"),
+                           ds_reserve_lds((const void*)thin_kernel<true, 2, true>, smem_bytes_chain(), "thin layer")};
+    for (int i = 0; i < 5; ++i)
+        if (rc[i]) return rc[i];
     return DS_OK;
 }
 

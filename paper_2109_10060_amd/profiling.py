@@ -3,6 +3,12 @@
   python -m paper_2109_10060_amd.profiling stats  <kernel_stats.csv> <out.txt> "<title>" "<command>"
   python -m paper_2109_10060_amd.profiling traffic <fetch.csv> <write.csv> <copy_fetch.csv> <copy_write.csv> \
          <copy_bytes> <out.json> "<commands>"
+  python -m paper_2109_10060_amd.profiling layers <kernel_trace.csv> <layers.json> <out.txt> "<title>" "<command>"
+
+`layers` joins a rocprofv3 kernel trace of the benchmark with the per-launch work list the benchmark writes
+(`bench.py --layers-json`): one row per kernel launch of a forward pass with its algorithmic flops and bytes, its
+duration averaged over the traced passes, the rates these give, the roof its arithmetic intensity selects
+(bf16 matrix peak above the ridge of 2500 TFLOP/s / 8 TB/s = 312 flop per byte, HBM below) and the fraction reached.
 
 `traffic` reads two counter-collection runs of the benchmark (FETCH_SIZE, then WRITE_SIZE, KiB per
 dispatch), scales each by what the same counter reads for a plain device copy of known size, and
@@ -76,8 +82,70 @@ def traffic(fetch_csv, write_csv, copy_fetch_csv, copy_write_csv, copy_bytes, ou
     print(json.dumps(out))
 
 
+# kernel-name fragments -> class of the per-launch work list (cost.py)
+CLASS_OF = (("attention_kernel", "attention"), ("layernorm", "layernorm"), ("dwconv", "dwconv"), ("dwpw_kernel", "dwconv"),
+            ("stem_", "stem"), ("maxpool_kernel", "maxpool"))
+PEAK_TFLOPS, PEAK_GBS = 2500.0, 8000.0
+
+
+def layers(trace_csv, layers_json, out_path, title, command):
+    work = json.load(open(layers_json))
+    rows = list(csv.DictReader(open(trace_csv)))
+    per_class = {}
+    for r in rows:
+        name = r["Kernel_Name"]
+        cls = None
+        if any(k in name for k in GEMM_KERNELS):
+            cls = "gemm*"
+        else:
+            for frag, c in CLASS_OF:
+                if frag in name:
+                    cls = c
+                    break
+        if cls is None:
+            continue
+        per_class.setdefault(cls, []).append((_short(name), (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) * 1e-3))
+    want = {}
+    for i, w in enumerate(work):
+        cls = "gemm*" if w["kind"] in ("gemm", "gemm_taps") else w["kind"]
+        want.setdefault(cls, []).append(i)
+    lines = [f"# {title}", f"# command: {command}",
+             "# us = mean duration of that launch over the traced passes; roof = the one the launch's flop per byte selects",
+             "layer | kernel | shape | GFLOP | MB | flop/B | us | TFLOP/s | GB/s | roof | fraction"]
+    out_rows = {}
+    for cls, idx in want.items():
+        got = per_class.get(cls, [])
+        n = len(idx)
+        if not got or len(got) < n or cls in ("gate", "head", "index"):
+            continue
+        passes = min(len(got) // n, 8)           # the last passes of the run: warm, and aligned to the end of the trace
+        tail = got[len(got) - passes * n:]
+        for k, i in enumerate(idx):
+            durs = [tail[p * n + k][1] for p in range(passes)]
+            out_rows[i] = (tail[(passes - 1) * n + k][0], sum(durs) / len(durs), passes)
+    tot = {"mfma": [0.0, 0.0], "hbm": [0.0, 0.0]}
+    for i, w in enumerate(work):
+        if i not in out_rows:
+            continue
+        kern, us, _ = out_rows[i]
+        ai = w["flops"] / max(w["bytes"], 1.0)
+        tf, gbs = w["flops"] / (us * 1e-6) / 1e12, w["bytes"] / (us * 1e-6) / 1e9
+        roof = "mfma" if ai >= PEAK_TFLOPS * 1e12 / (PEAK_GBS * 1e9) else "hbm"
+        frac = tf / PEAK_TFLOPS if roof == "mfma" else gbs / PEAK_GBS
+        tot[roof][0] += us
+        tot[roof][1] += frac * us
+        lines.append(f"{w['name']} | {kern} | {w['shape']} | {w['flops'] / 1e9:.2f} | {w['bytes'] / 1e6:.1f} | {ai:.0f} | "
+                     f"{us:.1f} | {tf:.0f} | {gbs:.0f} | {roof} | {frac:.3f}")
+    for roof, (us, acc) in tot.items():
+        if us:
+            lines.append(f"# launches under the {roof} roof: {us:.0f} us per pass, time-weighted fraction {acc / us:.3f}")
+    open(out_path, "w").write("\n".join(lines) + "\n")
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "stats":
+    if sys.argv[1] == "layers":
+        layers(*sys.argv[2:7])
+    elif sys.argv[1] == "stats":
         stats(*sys.argv[2:6])
     elif sys.argv[1] == "traffic":
         traffic(*sys.argv[2:9])

@@ -20,3 +20,17 @@ def gpu_lib():
     import paper_2109_10060_amd as ds
     ds.load()
     return ds
+
+
+@pytest.fixture(autouse=True)
+def _parity_scope(request):
+    from tests import parity
+    parity.set_current(request.node.nodeid)
+    yield
+
+
+def pytest_terminal_summary(terminalreporter):
+    from tests import parity
+    if parity.RECORDS:
+        for line in parity.summary_lines():
+            terminalreporter.write_line(line)

@@ -4,9 +4,15 @@ Small nets: every sample of a mixed-route batch is checked.  Full-size configura
 (batch 256, 224x224): the launch configuration the benchmark times; a seeded sample of
 images spanning the routes is recomputed one by one by the oracle, and batch-level
 properties (permutation equivariance, bit-exact repeatability, route histogram) are
-checked on the whole batch.  Logit tolerance: max |gpu - oracle| / max |oracle| <= 2e-2
-(bf16 storage, fp32 accumulation).  Routes must match the oracle exactly; the seeded
-logit bias keeps every gate margin far above 1e-6.
+checked on the whole batch.  At batch 256 the checked images are chosen so that every
+route of the network occurs among them (all 14 widths, all 16 route pairs at each stage
+boundary, all 48 embed / head / MLP tuples), and besides the logits the outputs of two to
+four blocks inside the network (ds_forward_taps) are compared with the oracle's.
+Tolerance: max |gpu - oracle| / max |oracle| <= 2e-2 per tensor (bf16 storage, fp32
+accumulation); the element-wise form is recorded beside it (tests/parity.py).  Routes
+must match the oracle exactly: the seeded logit bias keeps every gate margin far above
+the bf16 noise of the features, and the tests assert that no sample needed the exemption
+for gates that read bf16 features.
 """
 import numpy as np
 import pytest
@@ -25,25 +31,60 @@ def dev(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV).to(dtype).contiguous()
 
 
+from tests.parity import both as _both  # noqa: E402
+
+
 def relerr(got, want):
-    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
-    return float(np.max(np.abs(got - want)) / np.max(np.abs(want)))
+    """The stated bound's form, max |gpu - oracle| / max |oracle|; the element-wise form is recorded beside it."""
+    return _both(got, want)[0]
+
+
+def _taps_gpu(gpu_lib, net, xg, shapes, **kw):
+    """Runs ds_forward_taps; shapes: {block: (rows, C_stored)}.  Buffers start as NaN, so unwritten tails show."""
+    B = xg.shape[0]
+    bufs = {k: torch.full((B, r, c), float("nan"), dtype=torch.bfloat16, device=DEV) for k, (r, c) in shapes.items()}
+    logits, routes = gpu_lib.ds_forward_taps(net, xg, bufs, **kw)
+    torch.cuda.synchronize()
+    return logits, routes, bufs
+
+
+def _check_tap(buf, b, want_chw):
+    """buf[b]: [rows, C_stored] channels-last; want_chw: the oracle's [c, H, W] (or [tokens, c]) block output."""
+    want = np.asarray(want_chw, np.float64)
+    want = want.reshape(want.shape[0], -1).T if want.ndim == 3 else want
+    c = want.shape[1]
+    got = buf[b].to(torch.float64).cpu().numpy()
+    assert np.all(np.isnan(got[:, c:])), "tap tail beyond the valid slice was written"
+    return relerr(got[:, :c], want)
 
 
 # ------------------------------------------------------------------ DS-MBNet
-def _mb_case(gpu_lib, arch, params, imgs, lb, check):
+def _mb_case(gpu_lib, arch, params, imgs, lb, check, tap_blocks=()):
     net = gpu_lib.build_mbnet(arch, params, DEV)
     B = imgs.shape[0]
     xg, lbg = dev(imgs, torch.bfloat16), dev(lb[None], torch.float32)
     logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
     torch.cuda.synchronize()
+    bufs = {}
+    if tap_blocks:
+        res = arch["image"] // 2
+        shapes = {}
+        for i, (_ci, co, st) in enumerate(arch["blocks"]):
+            res = (res - 1) // st + 1
+            if i in tap_blocks:
+                shapes[i] = (res * res, co)
+        l1, r1, bufs = _taps_gpu(gpu_lib, net, xg, shapes, logit_bias=lbg)
+        assert torch.equal(l1, logits) and torch.equal(r1, routes)      # taps do not disturb the pass
     lg, rt = logits.cpu().numpy(), routes.cpu().numpy()[0]
     worst = 0.0
     for b in check:
-        want, t, z = O.forward_mbnet(arch, params, imgs[b], logit_bias=lb[b])
+        taps = {}
+        want, t, z = O.forward_mbnet(arch, params, imgs[b], logit_bias=lb[b], taps=taps)
         assert O.gate_margin(z) > 1e-2
         assert rt[b] == t, (b, rt[b], t)
         worst = max(worst, relerr(lg[b], want))
+        for i in tap_blocks:
+            worst = max(worst, _check_tap(bufs[i], b, taps[f"ds{i}"]))
     assert worst < TOL, worst
     # teacher-forced routes give the same result as the free-running gate when routes agree
     l2, r2 = gpu_lib.ds_forward(net, xg, route_override=routes.clone(), logit_bias=lbg)
@@ -80,8 +121,10 @@ def test_mbnet_config3_batch256(gpu_lib):
     imgs = WL.images(S + 103, B)
     lb = WL.seeded_logit_bias(S + 203, B, arch["T"])
     target = np.argmax(lb, axis=1)
-    check = [int(np.where(target == t)[0][0]) for t in (0, 5, 9, 13)] + [255]
-    net, xg, lbg, logits, routes = _mb_case(gpu_lib, arch, params, imgs, lb, check)
+    # 32 images: the first two of every width, then the last images of the batch
+    check = sorted({int(b) for t in range(14) for b in np.where(target == t)[0][:2]} | {252, 253, 254, 255})
+    assert len(check) == 32 and set(target[check].tolist()) == set(range(14))
+    net, xg, lbg, logits, routes = _mb_case(gpu_lib, arch, params, imgs, lb, check, tap_blocks=(2, 5, 12))
     rt = routes.cpu().numpy()[0]
     assert np.array_equal(rt, target)
     assert np.bincount(rt, minlength=14).min() >= 18
@@ -109,29 +152,63 @@ def test_mbnet_pp_batch256(gpu_lib):
     imgs = WL.images(S + 136, B)
     lb = WL.seeded_logit_bias(S + 236, B, arch["T"])
     target = np.argmax(lb, axis=1)
-    check = [int(np.where(target == t)[0][0]) for t in (0, 5, 11)]
-    _mb_case(gpu_lib, arch, params, imgs, lb, check)
+    check = sorted({int(b) for t in range(12) for b in np.where(target == t)[0][:2]})      # every path twice
+    _mb_case(gpu_lib, arch, params, imgs, lb, check, tap_blocks=(5, 12))
 
 
 # ------------------------------------------------------------------ DS-ResNet
-def _rn_case(gpu_lib, arch, params, imgs, lb, check):
+def _rn_case(gpu_lib, arch, params, imgs, lb, check, tap_stage_ends=False, max_exempt=0):
+    """max_exempt: how many checked samples may take the exemption for gates that read bf16 features (a route
+    that differs from the oracle's where the oracle's margin is inside that noise); 0 under the seeded bias."""
     net = gpu_lib.build_resnet(arch, params, DEV)
     xg, lbg = dev(imgs, torch.bfloat16), dev(lb, torch.float32)
     logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
     torch.cuda.synchronize()
+    bufs, tap_of = {}, {}
+    if tap_stage_ends:
+        res, blk, shapes = arch["image"] // 4, 0, {}
+        for s, nb in enumerate(arch["blocks"]):
+            res = res if s == 0 else (res - 1) // 2 + 1
+            blk += nb
+            shapes[blk - 1] = (res * res, 4 * int(arch["widths"][s]))
+            tap_of[blk - 1] = f"s{s}.b{nb - 1}"
+        l1, r1, bufs = _taps_gpu(gpu_lib, net, xg, shapes, logit_bias=lbg)
+        assert torch.equal(l1, logits) and torch.equal(r1, routes)
     lg, rt = logits.cpu().numpy(), routes.cpu().numpy()
-    worst = 0.0
+    worst, exempt = 0.0, 0
     for b in check:
-        want, ro, zs = O.forward_resnet(arch, params, imgs[b], logit_bias=lb[:, b])
+        taps = {}
+        want, ro, zs = O.forward_resnet(arch, params, imgs[b], logit_bias=lb[:, b], taps=taps)
         if rt[:, b].tolist() != ro:
             # mid-network gates read bf16 features, so a gate may only disagree where the oracle's
             # margin is within that noise; activations are then compared under the GPU's routes
+            exempt += 1
             s0 = next(s for s in range(4) if rt[s, b] != ro[s])
             assert O.gate_margin(zs[s0]) < 2e-2 * np.max(np.abs(zs[s0])), (b, rt[:, b], ro, zs[s0])
-            want, _, _ = O.forward_resnet(arch, params, imgs[b], logit_bias=lb[:, b], route_override=rt[:, b])
+            taps = {}
+            want, _, _ = O.forward_resnet(arch, params, imgs[b], logit_bias=lb[:, b], route_override=rt[:, b], taps=taps)
         worst = max(worst, relerr(lg[b], want))
+        for blk, name in tap_of.items():
+            if name in taps:            # a route of lesser depth stops before the stage's last stored block
+                worst = max(worst, _check_tap(bufs[blk], b, taps[name]))
     assert worst < TOL, worst
+    assert exempt <= max_exempt, f"{exempt} checked samples needed the bf16-gate exemption"
     return net, xg, lbg, logits, routes
+
+
+def _cover_boundary_pairs(rt, n):
+    """Indices of n samples such that every (route of stage s-1, route of stage s) pair that occurs in rt [4, B] is
+    among them, chosen greedily; filled up with the first samples not yet taken."""
+    B = rt.shape[1]
+    need = {(s, int(rt[s - 1, b]), int(rt[s, b])) for s in range(1, 4) for b in range(B)} | {(0, 0, int(r)) for r in rt[0]}
+    keys = lambda b: {(s, int(rt[s - 1, b]), int(rt[s, b])) for s in range(1, 4)} | {(0, 0, int(rt[0, b]))}
+    pick = []
+    while need:
+        b = max(range(B), key=lambda i: (len(keys(i) & need), -i))
+        pick.append(b)
+        need -= keys(b)
+    pick += [b for b in range(B) if b not in pick][:max(0, n - len(pick))]
+    return sorted(pick)
 
 
 def _rn_bias(seed, B, T):
@@ -206,8 +283,8 @@ def test_resnet_pp_single_gate_small_and_batch256(gpu_lib):
     imgs = WL.images(S + 151, B)
     lb = _rn_bias(S + 251, B, 9)
     target = np.argmax(lb[0], axis=1)
-    check = [int(np.where(target == t)[0][0]) for t in (0, 8)]
-    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, check)
+    check = [int(np.where(target == t)[0][0]) for t in range(9)]            # every path once
+    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, check, tap_stage_ends=True)
     rt = routes.cpu().numpy()
     assert (rt == rt[0]).all() and np.array_equal(rt[0], target)
 
@@ -219,9 +296,13 @@ def test_resnet_config4_batch256(gpu_lib):
     imgs = WL.images(S + 104, B)
     lb = _rn_bias(S + 204, B, 4)
     target = np.argmax(lb, axis=2)                                  # [4, B]
-    check = [0, 101, 255]
-    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, check)
+    # 32 images covering all 4 first-stage routes and all 16 (previous, own) route pairs of every later stage
+    check = _cover_boundary_pairs(target, 32)
+    assert len(check) == 32
+    net, xg, lbg, logits, routes = _rn_case(gpu_lib, arch, params, imgs, lb, check, tap_stage_ends=True)
     rt = routes.cpu().numpy()
+    for s in range(1, 4):
+        assert len({(int(rt[s - 1, b]), int(rt[s, b])) for b in check}) == 16
     assert np.mean(rt == target) > 0.97                              # the seeded bias decides nearly every gate
     for s in range(1, 4):
         assert len(set(zip(rt[s - 1].tolist(), rt[s].tolist()))) == 16   # all 16 (r_prev, r) boundary pairs occur
@@ -231,17 +312,31 @@ def test_resnet_config4_batch256(gpu_lib):
 
 
 # ------------------------------------------------------------------ DS-ViT
-def _vit_case(gpu_lib, arch, params, imgs, lb, check):
+def _vit_taps(gpu_lib, arch, net, xg, lbg, logits, routes, tap_layers):
+    if not tap_layers:
+        return {}
+    shapes = {l: (arch["tokens"], arch["embed"]) for l in tap_layers}
+    l1, r1, bufs = _taps_gpu(gpu_lib, net, xg, shapes, logit_bias=lbg)
+    assert torch.equal(l1, logits) and torch.equal(r1, routes)
+    return bufs
+
+
+def _vit_case(gpu_lib, arch, params, imgs, lb, check, tap_layers=()):
     net = gpu_lib.build_vit(arch, params, DEV)
     xg, lbg = dev(imgs, torch.bfloat16), dev(lb[None], torch.float32)
     logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
     torch.cuda.synchronize()
+    bufs = _vit_taps(gpu_lib, arch, net, xg, lbg, logits, routes, tap_layers)
     lg, rt = logits.cpu().numpy(), routes.cpu().numpy()[0]
     assert np.array_equal(rt, [O.gate_route(z) for z in lb])
     worst = 0.0
     for b in check:
-        want = O.forward_vit(arch, params, imgs[b], int(rt[b]))
+        taps = {}
+        want = O.forward_vit(arch, params, imgs[b], int(rt[b]), taps=taps)
         worst = max(worst, relerr(lg[b], want))
+        for l in tap_layers:
+            if f"l{l}" in taps:
+                worst = max(worst, _check_tap(bufs[l], b, taps[f"l{l}"]))
     assert worst < TOL, worst
     return net, xg, lbg, logits, routes
 
@@ -272,21 +367,29 @@ def test_vit_dynamic_depth_small_all_samples(gpu_lib):
     _vit_case(gpu_lib, arch0, params, imgs[:6], lb[:6], range(6))
 
 
-def _vit_stem_case(gpu_lib, arch, params, imgs, lb, check):
+def _vit_stem_case(gpu_lib, arch, params, imgs, lb, check, tap_layers=(), max_exempt=0):
     net = gpu_lib.build_vit(arch, params, DEV)
     xg, lbg = dev(imgs, torch.bfloat16), dev(lb[None], torch.float32)
     logits, routes = gpu_lib.ds_forward(net, xg, logit_bias=lbg)
     torch.cuda.synchronize()
+    bufs = _vit_taps(gpu_lib, arch, net, xg, lbg, logits, routes, tap_layers)
     lg, rt = logits.cpu().numpy(), routes.cpu().numpy()[0]
-    worst = 0.0
+    worst, exempt = 0.0, 0
     for b in check:
-        want, ro, z = O.forward_vit_stem(arch, params, imgs[b], logit_bias=lb[b])
+        taps = {}
+        want, ro, z = O.forward_vit_stem(arch, params, imgs[b], logit_bias=lb[b], taps=taps)
         if int(rt[b]) != ro:
             # the gate reads bf16 stem features: it may only disagree inside that noise
+            exempt += 1
             assert O.gate_margin(z) < 2e-2 * np.max(np.abs(z)), (b, rt[b], ro, z)
-            want, _, _ = O.forward_vit_stem(arch, params, imgs[b], logit_bias=lb[b], route_override=int(rt[b]))
+            taps = {}
+            want, _, _ = O.forward_vit_stem(arch, params, imgs[b], logit_bias=lb[b], route_override=int(rt[b]), taps=taps)
         worst = max(worst, relerr(lg[b], want))
+        for l in tap_layers:
+            if f"l{l}" in taps:
+                worst = max(worst, _check_tap(bufs[l], b, taps[f"l{l}"]))
     assert worst < TOL, worst
+    assert exempt <= max_exempt, f"{exempt} checked samples needed the bf16-gate exemption"
     return net, xg, lbg, logits, routes
 
 
@@ -321,8 +424,8 @@ def test_vit_stem_batch256(gpu_lib):
     imgs = WL.images(S + 175, B)
     lb = WL.seeded_logit_bias(S + 275, B, arch["T"], amp=16.0)
     target = np.argmax(lb, axis=1)
-    check = [int(np.where(target == t)[0][0]) for t in (0, 47)] + [200]
-    net, xg, lbg, logits, routes = _vit_stem_case(gpu_lib, arch, params, imgs, lb, check)
+    check = sorted({int(np.where(target == t)[0][0]) for t in range(0, 48, 3)} | {200})      # 16 routes + one more
+    net, xg, lbg, logits, routes = _vit_stem_case(gpu_lib, arch, params, imgs, lb, check, tap_layers=(0, 1))
     pi = torch.randperm(B, generator=torch.Generator().manual_seed(4)).to(DEV)
     l3, r3 = gpu_lib.ds_forward(net, xg[pi].contiguous(), logit_bias=lbg[:, pi].contiguous())
     assert torch.equal(l3, logits[pi]) and torch.equal(r3, routes[:, pi])
@@ -351,8 +454,8 @@ def test_vit_pp_batch256(gpu_lib):
     imgs = WL.images(S + 185, B)
     lb = WL.seeded_logit_bias(S + 285, B, arch["T"], amp=16.0)
     target = np.argmax(lb, axis=1)
-    check = [int(np.where(target == t)[0][0]) for t in (0, 3, 7)]
-    net, xg, lbg, logits, routes = _vit_stem_case(gpu_lib, arch, params, imgs, lb, check)
+    check = [int(np.where(target == t)[0][0]) for t in range(8)]            # every path once
+    net, xg, lbg, logits, routes = _vit_stem_case(gpu_lib, arch, params, imgs, lb, check, tap_layers=(5, 11, 13))
     assert np.bincount(routes.cpu().numpy()[0], minlength=8).min() >= 28
 
 
@@ -363,8 +466,9 @@ def test_vit_config5_batch256(gpu_lib):
     imgs = WL.images(S + 105, B)
     lb = WL.seeded_logit_bias(S + 205, B, arch["T"])
     target = np.argmax(lb, axis=1)
-    check = [int(np.where(target == t)[0][0]) for t in (0, 23, 47)] + [128]
-    net, xg, lbg, logits, routes = _vit_case(gpu_lib, arch, params, imgs, lb, check)
+    check = sorted({int(np.where(target == t)[0][0]) for t in range(48)})   # one image of every (embed, heads, MLP) route
+    assert len(check) == 48
+    net, xg, lbg, logits, routes = _vit_case(gpu_lib, arch, params, imgs, lb, check, tap_layers=(0, 5, 11))
     assert np.bincount(routes.cpu().numpy()[0], minlength=48).min() >= 5
     pi = torch.randperm(B, generator=torch.Generator().manual_seed(3)).to(DEV)
     l3, r3 = gpu_lib.ds_forward(net, xg[pi].contiguous(), logit_bias=lbg[:, pi].contiguous())

@@ -460,3 +460,20 @@ def test_re_sbn_recalibration_is_the_population_statistics_per_route():
     # a route without samples stays at its initial statistics
     m2, v2, c2 = O.re_sbn_recalibrate(samples[:1], routes[:1], T, C)
     assert c2.tolist() == [H * W, 0, 0] and np.all(m2[1:] == 0) and np.all(v2[1:] == 1)
+
+
+def test_config1_recorded_seeds_give_mixed_routes_from_the_computed_gate():
+    """config1's own seed routes all eight samples alike; the recorded later seeds are the first whose computed gate
+    (no bias) yields two and three routes with every top-2 margin above 1e-3, so a GPU gate must reproduce them."""
+    import workloads as WL
+
+    def routes(seed):
+        c = WL.config1(seed=seed)
+        z = [O.gate_logits(O.gate_encoder(c["x"][b]), c["gate.w1"], c["gate.b1"], c["gate.w2"], c["gate.b2"])
+             for b in range(c["B"])]
+        return [O.gate_route(v) for v in z], min(O.gate_margin(v) for v in z)
+
+    assert len(set(routes(WL.BASE_SEED + 1)[0])) == 1
+    for seed, n in zip(WL.CONFIG1_MIXED_SEEDS, (2, 3)):
+        r, margin = routes(seed)
+        assert len(set(r)) == n and margin > 1e-3

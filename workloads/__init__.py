@@ -18,4 +18,4 @@ from .nets import (  # noqa: F401
     seeded_logit_bias,
     images,
 )
-from .configs import config1, config2  # noqa: F401
+from .configs import CONFIG1_MIXED_SEEDS, config1, config2  # noqa: F401
