@@ -4,9 +4,13 @@
 One step = one ds_forward pass (gate, bucketing, every sliced layer, classifier,
 un-permute) over a batch of 256 synthetic ImageNet-shaped images with mixed routes,
 inputs and weights resident in HBM.  Prints one JSON line:
-images/s, the roofline fraction of the dominant kernel (measured with HIP events
-around every launch of it inside the timed region) and the CPU oracle timed on a
-bounded sample of the same workload.
+images/s (mean over the timed steps, with the median and the 10th / 90th percentile
+of the single steps beside it), the roofline fraction of the dominant kernel class
+(measured with HIP events around every launch of it inside the timed region) and of
+each of its kernels against the roof its launches select, and the CPU oracle timed
+on a bounded sample of the same workload.  Without --workload the headline is
+config 4 (DS-ResNet) and configs 3 and 5 are measured after it (other_workloads).
+Defaults: 20 warm-up and 100 timed steps.
 """
 from __future__ import annotations
 
@@ -99,7 +103,8 @@ def cpu_baseline(name, arch, params, imgs, lb, budget_s=15.0):
         n += 1
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "images/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {n} images of the same batch, one by one, float64 numpy ({dt:.1f} s)"}
+            "sample": f"first {n} images of the same batch, one image at a time, float64 numpy ({dt:.1f} s); cores = the "
+                      f"threads of numpy's BLAS pool (its matmul calls are the only parallel part; no parallelism over samples)"}
 
 
 def run_linear(args):
@@ -191,55 +196,53 @@ def run_linear(args):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet", choices=["mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp", "resnet_pp", "linear"])
-    ap.add_argument("--batch", type=int, default=256)
-    ap.add_argument("--parts", type=int, default=1,
-                    help="run the batch as this many concurrent shares (ds_forward_parts, 1..4); 1 = ds_forward")
-    ap.add_argument("--mix", default="uniform", choices=["uniform", "skewed"],
-                    help="route mix: every route about equally often (default), or half of the batch on the smallest "
-                         "route at early gates / the largest route at late gates")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-events", action="store_true",
-                    help="do not bracket kernel launches with HIP events (roofline is then null)")
-    ap.add_argument("--event-every", type=int, default=5,
-                    help="bracket the kernels of every N-th timed step with HIP events (1 = every step)")
-    ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class table to stderr")
-    ap.add_argument("--layers-json", default="", metavar="PATH",
-                    help="write the per-launch algorithmic work list of one step (for `profiling layers`)")
-    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
-                    help="only run a plain device copy of MIB mebibytes 5 times (reference for the HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (--gpus must be 1)")
+GEMM_CLASSES = ("gemm", "gemm_taps", "conv3", "thin")          # kernel classes whose launches are the cost model's gemm / gemm_taps records
+KERNEL_OF = {"gemm": "gemm_kernel", "gemm_taps": "gemm_kernel", "conv3": "conv3_kernel", "thin": "thin_kernel"}
+RIDGE = PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)     # flop per byte above which the matrix peak is the roof
 
-    if args.workload == "linear" and not args.copy_calibration:
-        return run_linear(args)
 
+def rates(flops, nbytes, ms, contraction):
+    """Algorithmic rates of `flops` / `nbytes` done in `ms`, and the fraction of the roof that applies: a contraction whose
+    flop per byte lies above the ridge is held against the bf16 matrix peak, everything else against HBM bandwidth."""
+    t = ms * 1e-3
+    tf, gbs = flops / t / 1e12, nbytes / t / 1e9
+    ai = flops / max(nbytes, 1.0)
+    roof = "mfma" if contraction and ai >= RIDGE else "hbm"
+    return {"tflops": tf, "algorithmic_gbs": gbs, "flop_per_byte": ai, "roof": roof,
+            "frac": tf / PEAK_MFMA_BF16_TFLOPS if roof == "mfma" else gbs / PEAK_HBM_GBS,
+            "frac_mfma": tf / PEAK_MFMA_BF16_TFLOPS, "frac_hbm": gbs / PEAK_HBM_GBS}
+
+
+def match_launches(cost, launches, sampled):
+    """Joins the recorded launches (class, ms) of `sampled` identical steps with the cost model's per-launch records, class
+    by class in launch order.  Returns the cost records with 'kernel' and 'us' (mean over the sampled steps) filled in."""
+    per_step = len(launches) // sampled
+    rows = [dict(r) for r in cost.launches]
+    want = {}
+    for i, r in enumerate(rows):
+        want.setdefault("gemm*" if r["kind"] in ("gemm", "gemm_taps") else r["kind"], []).append(i)
+    for cls, idx in want.items():
+        got = [[(k, ms) for k, ms in launches[s0 * per_step:(s0 + 1) * per_step]
+                if (k in GEMM_CLASSES if cls == "gemm*" else k == cls)] for s0 in range(sampled)]
+        if any(len(g) != len(idx) for g in got):
+            continue                                   # this class is launched differently from the model (gate, head): totals only
+        for k, i in enumerate(idx):
+            rows[i]["kernel"] = KERNEL_OF.get(got[0][k][0], got[0][k][0])
+            rows[i]["us"] = 1e3 * sum(g[k][1] for g in got) / sampled
+    return rows
+
+
+def run_net(workload, args, steps, warmup, with_cpu_baseline):
     import numpy as np
     import torch
     import paper_2109_10060_amd as ds
     from paper_2109_10060_amd import cost as C
 
-    ds.load()
     dev = "cuda:0"
-    if args.copy_calibration:
-        n = args.copy_calibration << 20
-        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes": n, "repeats": 5}))
-        return
     B = args.batch
-    arch, params, imgs, lb, label = build_workload(args.workload, B, args.mix)
+    arch, params, imgs, lb, label = build_workload(workload, B, args.mix)
     net = {"mbnet": ds.build_mbnet, "mbnet_pp": ds.build_mbnet, "resnet": ds.build_resnet, "resnet_pp": ds.build_resnet, "vit": ds.build_vit,
-           "vit_stem": ds.build_vit, "vit_pp": ds.build_vit}[args.workload](arch, params, dev)
+           "vit_stem": ds.build_vit, "vit_pp": ds.build_vit}[workload](arch, params, dev)
     x = torch.from_numpy(imgs).to(dev).to(torch.bfloat16).contiguous()
     lbg = torch.from_numpy(lb).to(dev).contiguous()
     logits = torch.empty((B, net.num_classes), dtype=torch.float32, device=dev)
@@ -252,7 +255,7 @@ def main():
         else:
             ds.ds_forward_parts(net, x, args.parts, logit_bias=lbg, logits=logits, routes=routes, ws=ws)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     # per-kernel HIP events are recorded on a sample of the timed steps (every --event-every-th):
@@ -261,40 +264,48 @@ def main():
     ds.ds_profile_reset()
     every = max(1, args.event_every)
     sampled = 0
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    sampled_steps = set()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    e0.record()
-    for i in range(args.steps):
-        on = (not args.no_kernel_events) and i % every == min(every // 2, args.steps - 1)
+    marks[0].record()
+    for i in range(steps):
+        on = (not args.no_kernel_events) and i % every == min(every // 2, steps - 1)
         if on:
             ds.ds_profile_enable(True)
             sampled += 1
+            sampled_steps.add(i)
         step()
         if on:
             ds.ds_profile_enable(False)
-    e1.record()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    gpu_ms = e0.elapsed_time(e1)
-    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    gpu_ms = marks[0].elapsed_time(marks[steps])
+    ms_per_step = max(wall_ms, gpu_ms) / steps
+    # spread of the individual steps (those without kernel events, which cost 13-16 %)
+    per = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps) if i not in sampled_steps) or [ms_per_step]
+    pick = lambda q: per[min(len(per) - 1, int(q * len(per)))]
     prof = ds.ds_profile_read() if sampled else {}
+    launches = ds.ds_profile_launches() if sampled else []
 
     rt = routes.cpu().numpy()
     cost = {"mbnet": C.mbnet_cost, "mbnet_pp": C.mbnet_cost, "resnet": C.resnet_cost, "resnet_pp": C.resnet_cost, "vit": C.vit_cost, "vit_stem": C.vit_cost,
-            "vit_pp": C.vit_cost}[args.workload](arch, rt)
-    if args.layers_json:
-        json.dump(cost.launches, open(args.layers_json, "w"))
+            "vit_pp": C.vit_cost}[workload](arch, rt)
     roofline = None
     kernels = {}
     if prof:
-        # dominant kernel: the grouped GEMM (all its launches: linear/1x1, tap-walking and patch-staged 3x3)
-        ms = prof["gemm"][0] + prof["gemm_taps"][0]
-        n = prof["gemm"][1] + prof["gemm_taps"][1]
+        rows = match_launches(cost, launches, sampled) if args.parts == 1 else []
+        if args.layers_json:
+            json.dump(rows, open(args.layers_json, "w"))
+        # the grouped GEMM class (linear / 1x1 / KxK layers) as one figure, as the dominant kernel of every network, ...
+        gsel = [r for r in rows if r["kind"] in ("gemm", "gemm_taps") and "us" in r]
+        ms = sum(prof[k][0] for k in GEMM_CLASSES)
+        n = sum(prof[k][1] for k in GEMM_CLASSES)
         flops = (cost["gemm"]["flops"] + cost["gemm_taps"]["flops"]) * sampled
         nbytes = (cost["gemm"]["bytes"] + cost["gemm_taps"]["bytes"]) * sampled
         traffic = None
-        tfile = os.path.join(ROOT, "profiles", f"gemm_traffic_{args.workload}_b256.txt")
+        tfile = os.path.join(ROOT, "profiles", f"gemm_traffic_{workload}_b256.txt")
         if os.path.exists(tfile) and B == 256:
             from paper_2109_10060_amd.profiling import kernel_source_hash
             t = json.load(open(tfile))
@@ -309,35 +320,115 @@ def main():
                         "launches_per_step": n / sampled, "avg_launch_us": ms * 1e3 / n,
                         "steps_sampled": sampled, "share_of_step": ms / (ms_per_step * sampled),
                         "hbm_view": {"achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}}
+            # ... and each of its three kernels against the roof its own launches select: the launches whose flop per byte
+            # lies above the ridge against the matrix peak, the others against HBM bandwidth
+            per_kernel = {}
+            for kern in ("gemm_kernel", "conv3_kernel", "thin_kernel"):
+                mine = [r for r in gsel if r["kernel"] == kern]
+                if not mine:
+                    continue
+                entry = {"launches_per_step": len(mine), "ms_per_step": sum(r["us"] for r in mine) * 1e-3}
+                for roof in ("mfma", "hbm"):
+                    part = [r for r in mine if ("mfma" if r["flops"] / max(r["bytes"], 1.0) >= RIDGE else "hbm") == roof]
+                    if part:
+                        t_ms = sum(r["us"] for r in part) * 1e-3
+                        rr = rates(sum(r["flops"] for r in part), sum(r["bytes"] for r in part), t_ms, True)
+                        entry[roof + "_bound_launches"] = {"launches": len(part), "ms_per_step": t_ms, "tflops": rr["tflops"],
+                                                           "algorithmic_gbs": rr["algorithmic_gbs"],
+                                                           "frac": rr["frac_mfma"] if roof == "mfma" else rr["frac_hbm"]}
+                per_kernel[kern] = entry
+            roofline["per_kernel"] = per_kernel
         # every kernel class with its algorithmic rates (same events, same sampled steps)
-        for k, (t, cnt) in prof.items():
+        merged = dict(prof)
+        for k, (t, cnt) in merged.items():
             if not cnt:
                 continue
-            c = cost.get(k, {"flops": 0.0, "bytes": 0.0})
-            per_step_s = t / sampled * 1e-3
-            kernels[k] = {"ms_per_step": t / sampled, "launches_per_step": cnt / sampled,
-                          "tflops": c["flops"] / per_step_s / 1e12 if t else 0.0,
-                          "algorithmic_gbs": c["bytes"] / per_step_s / 1e9 if t else 0.0}
+            ck = {"conv3": "gemm_taps", "thin": "gemm"}.get(k, k)
+            c = cost.get(ck, {"flops": 0.0, "bytes": 0.0}) if k not in ("conv3", "thin", "gemm", "gemm_taps") else None
+            if c is None:
+                mine = [r for r in gsel if (r["kernel"], r["kind"]) == (KERNEL_OF[k], "gemm_taps" if k in ("gemm_taps", "conv3") else "gemm")
+                        or (k == "conv3" and r["kernel"] == "conv3_kernel") or (k == "thin" and r["kernel"] == "thin_kernel")]
+                c = {"flops": sum(r["flops"] for r in mine), "bytes": sum(r["bytes"] for r in mine)}
+            per_step_ms = t / sampled
+            kernels[k] = {"ms_per_step": per_step_ms, "launches_per_step": cnt / sampled,
+                          **{kk: vv for kk, vv in rates(c["flops"], c["bytes"], per_step_ms, k in GEMM_CLASSES or k == "attention").items()
+                             if kk in ("tflops", "algorithmic_gbs", "roof", "frac")}}
         if args.breakdown:
-            for k, (t, cnt) in prof.items():
-                if not cnt:
-                    continue
-                c = cost.get(k, {"flops": 0.0, "bytes": 0.0})
-                sys.stderr.write(f"{k:10s} {t / sampled:8.3f} ms/step {cnt // sampled:4d} launches  "
-                                 f"{c['flops'] / (t / sampled * 1e-3) / 1e12 if t else 0:8.1f} TFLOP/s "
-                                 f"{c['bytes'] / (t / sampled * 1e-3) / 1e9 if t else 0:8.0f} GB/s\n")
+            for k, v in kernels.items():
+                sys.stderr.write(f"{k:10s} {v['ms_per_step']:8.3f} ms/step {int(v['launches_per_step']):4d} launches  "
+                                 f"{v['tflops']:8.1f} TFLOP/s {v['algorithmic_gbs']:8.0f} GB/s  {v['roof']} {v['frac']:.3f}\n")
 
     out = {
         "metric": "images/sec at batch 256 (mixed gate widths)", "value": B / (ms_per_step * 1e-3), "unit": "images/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": pick(0.5), "ms_per_step_p10": pick(0.1), "ms_per_step_p90": pick(0.9),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": label, "batch": B, "image": arch["image"], "route_mix": args.mix, "parts": args.parts,
                    "route_histogram": [np.bincount(r, minlength=net.T).tolist() for r in rt]},
         "roofline": roofline,
         "kernels": kernels,
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.workload, arch, params, imgs, lb)
+    if with_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(workload, arch, params, imgs, lb)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="", choices=["", "mbnet", "resnet", "vit", "vit_stem", "vit_pp", "mbnet_pp", "resnet_pp", "linear"],
+                    help="default: config 4 (DS-ResNet) as the headline line, with configs 3 (DS-MBNet) and 5 (DS-ViT) measured "
+                         "after it and reported under other_workloads; naming a workload runs that one only")
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--parts", type=int, default=1,
+                    help="run the batch as this many concurrent shares (ds_forward_parts, 1..4); 1 = ds_forward")
+    ap.add_argument("--mix", default="uniform", choices=["uniform", "skewed"],
+                    help="route mix: every route about equally often (default), or half of the batch on the smallest "
+                         "route at early gates / the largest route at late gates")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernel launches with HIP events (roofline is then null)")
+    ap.add_argument("--event-every", type=int, default=5,
+                    help="bracket the kernels of every N-th timed step with HIP events (1 = every step)")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class table to stderr")
+    ap.add_argument("--layers-json", default="", metavar="PATH",
+                    help="write the per-launch work list of one step with the measured duration of each launch")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of MIB mebibytes 5 times (reference for the HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the library has no multi-GPU path (--gpus must be 1)")
+
+    if args.workload == "linear" and not args.copy_calibration:
+        return run_linear(args)
+
+    import torch
+    import paper_2109_10060_amd as ds
+
+    ds.load()
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": n, "repeats": 5}))
+        return
+    out = run_net(args.workload or "resnet", args, args.steps, args.warmup, not args.no_cpu_baseline)
+    if not args.workload:
+        # configs 3 and 5 ride along in the default line (same protocol, fewer steps, no CPU leg), so that the recorded run
+        # carries the depthwise / LayerNorm / attention kernels as well
+        others = {}
+        layers_json, args.layers_json = args.layers_json, ""
+        for w in ("mbnet", "vit"):
+            r = run_net(w, args, max(10, args.steps // 2), max(3, args.warmup // 2), False)
+            others[w] = {k: r[k] for k in ("value", "unit", "ms_per_step", "ms_per_step_median", "steps", "warmup", "config",
+                                           "roofline", "kernels")}
+        args.layers_json = layers_json
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 

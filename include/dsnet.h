@@ -332,10 +332,14 @@ int32_t ds_forward_parts(const ds_net* net, const void* images, int32_t B, const
  * ds_profile_reset().  ds_profile_read waits for the recorded events and returns the summed
  * milliseconds and launch count of one kernel class: 0 grouped GEMM on linear/1x1 layers,
  * 1 grouped GEMM walking KxK taps, 2 attention, 3 depthwise conv, 4 LayerNorm, 5 stem conv,
- * 6 max-pool, 7 pool+classifier, 8 gate, 9 bucket, 10 index helpers.  Not thread-safe; host pointers. */
+ * 6 max-pool, 7 pool+classifier, 8 gate, 9 bucket, 10 index helpers, 11 3x3 stride-1 convolution with the
+ * patch staged once, 12 short-reduction 1x1 layers (one workgroup per row tile).  ds_profile_launches gives the
+ * recorded launches one by one in launch order: kinds[i] and ms[i] for i < min(*count, capacity), *count = the number
+ * recorded.  Not thread-safe; host pointers. */
 int32_t ds_profile_enable(int32_t on);
 int32_t ds_profile_reset(void);
 int32_t ds_profile_read(int32_t kind, double* total_ms, int64_t* launches);
+int32_t ds_profile_launches(int32_t* kinds, float* ms, int64_t capacity, int64_t* count);
 
 #ifdef __cplusplus
 }

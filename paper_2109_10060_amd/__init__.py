@@ -33,7 +33,7 @@ EXPORTS = [
     "ds_gate_double", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_linear_noalloc", "ds_sliced_conv_workspace", "ds_sliced_conv",
     "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_dwconv_spatial", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
-    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_forward_taps", "ds_forward_parts_workspace", "ds_forward_parts", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
+    "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_forward_taps", "ds_forward_parts_workspace", "ds_forward_parts", "ds_profile_enable", "ds_profile_reset", "ds_profile_read", "ds_profile_launches",
 ]
 
 
@@ -378,7 +378,7 @@ def ds_forward_parts(net: "Net", images, parts: int, route_override=None, logit_
 
 
 KERNEL_CLASSES = ["gemm", "gemm_taps", "attention", "dwconv", "layernorm", "stem", "maxpool", "head", "gate",
-                  "bucket", "index"]
+                  "bucket", "index", "conv3", "thin"]
 
 
 def ds_profile_enable(on: bool):
@@ -398,3 +398,14 @@ def ds_profile_read() -> dict:
         _chk(lib.ds_profile_read(k, ctypes.byref(ms), ctypes.byref(n)))
         out[name] = (ms.value, n.value)
     return out
+
+
+def ds_profile_launches() -> list:
+    """[(kernel class, milliseconds)] of the recorded launches, in launch order."""
+    lib = load()
+    n = ctypes.c_int64(0)
+    _chk(lib.ds_profile_launches(None, None, ctypes.c_int64(0), ctypes.byref(n)))
+    kinds = (ctypes.c_int32 * max(n.value, 1))()
+    ms = (ctypes.c_float * max(n.value, 1))()
+    _chk(lib.ds_profile_launches(kinds, ms, ctypes.c_int64(n.value), ctypes.byref(n)))
+    return [(KERNEL_CLASSES[kinds[i]], float(ms[i])) for i in range(n.value)]

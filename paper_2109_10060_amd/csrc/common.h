@@ -243,6 +243,8 @@ enum {
     DS_K_GATE,
     DS_K_BUCKET,
     DS_K_MISC,
+    DS_K_CONV3,      // conv3_kernel (3x3 stride-1 layers with the input patch staged once)
+    DS_K_THIN,       // thin_kernel (short reductions, one workgroup per row tile; with or without a chained second layer)
     DS_K_COUNT
 };
 struct ProfScope {

@@ -64,20 +64,6 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
     const int W = a.W, H = a.H, rows = a.rows;
     const int halo = W + 1, R = BM + 2 * halo;
 
-    if (tid < BM) {
-        const int m = grow0 + tid;
-        long long rc = -1, rr = 0;
-        if (m < rows_g) {
-            const int sl = m / rows;
-            const int p = m - sl * rows;
-            const int slot = slot0 + sl;
-            const int cs = a.c_index ? a.c_index[slot] : slot;
-            rc = (long long)cs * a.c_sample_stride + (long long)(p + a.c_row0) * c_ld;
-            rr = (long long)(a.r_use_index ? cs : 0) * a.r_sample_stride + (long long)(p + a.c_row0) * r_ld;
-        }
-        rowC[tid] = rc;
-        rowR[tid] = rr;
-    }
     if (tid < 4) *(uint4*)(As + ZROW * 64 + tid * 16) = make_uint4(0, 0, 0, 0);
 
     // ---- patch loader: item e = tid + 256 i is chunk (e & 3) of patch row (e >> 2) --------------
@@ -131,6 +117,24 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
         for (int v = 0; v < TPP; ++v) *(uint4*)(Bs + (v * BN + wn_row) * 64 + ((lchunk ^ sw(wn_row)) * 16)) = rb[v];
     };
 
+    // the first patch and filter-row loads are requested as soon as their addresses are known: everything below (output
+    // row table, tap mask, epilogue constants) is worked out while they travel
+    load_phase(0, 0);
+
+    if (tid < BM) {
+        const int m = grow0 + tid;
+        long long rc = -1, rr = 0;
+        if (m < rows_g) {
+            const int sl = m / rows;
+            const int p = m - sl * rows;
+            const int slot = slot0 + sl;
+            const int cs = a.c_index ? a.c_index[slot] : slot;
+            rc = (long long)cs * a.c_sample_stride + (long long)(p + a.c_row0) * c_ld;
+            rr = (long long)(a.r_use_index ? cs : 0) * a.r_sample_stride + (long long)(p + a.c_row0) * r_ld;
+        }
+        rowC[tid] = rc;
+        rowR[tid] = rr;
+    }
     const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     // ---- this lane's output pixel: which taps are inside the image ---------------------------
     const int trow = wave * 32 + l32;
@@ -188,7 +192,6 @@ __global__ __launch_bounds__(NT) void conv3_kernel(const GemmArgs a, const int n
     }
 
     const int nph = ((k_in + 31) / 32) * PPC;
-    load_phase(0, 0);
     store_phase(0);
     __syncthreads();
     int c = 0, u = 0;
@@ -295,7 +298,7 @@ int32_t launch(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, hipStrea
     }
     const int ny = (max_kout + BN - 1) / BN;
     const unsigned grid = (unsigned)(((max_mtiles + 7) / 8) * ny * 8);
-    ProfScope prof(DS_K_GEMM_TAPS, s);
+    ProfScope prof(DS_K_CONV3, s);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), SMEM, s, a, ny, max_mtiles);
     DS_CHECK_LAUNCH("sliced 3x3 conv");
     return DS_OK;

@@ -63,3 +63,16 @@ extern "C" int32_t ds_profile_read(int32_t kind, double* total_ms, int64_t* laun
     *launches = n;
     return DS_OK;
 }
+
+extern "C" int32_t ds_profile_launches(int32_t* kinds, float* ms, int64_t capacity, int64_t* count) {
+    if (!count || capacity < 0 || (capacity > 0 && (!kinds || !ms))) DS_FAIL(DS_EINVAL, "ds_profile_launches: bad argument");
+    *count = (int64_t)g_used;
+    for (size_t i = 0; i < g_used && (int64_t)i < capacity; ++i) {
+        if (hipEventSynchronize(g_pool[i].b) != hipSuccess) DS_FAIL(DS_EHIP, "ds_profile_launches: event sync failed");
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, g_pool[i].a, g_pool[i].b) != hipSuccess) DS_FAIL(DS_EHIP, "ds_profile_launches: elapsed time failed");
+        kinds[i] = g_pool[i].kind;
+        ms[i] = t;
+    }
+    return DS_OK;
+}

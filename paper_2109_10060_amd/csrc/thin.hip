@@ -329,7 +329,7 @@ int32_t ds_launch_thin(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     if (thin_supported(a, max_mtiles, max_kout, &kmax) != DS_OK) return DS_EUNSUPPORTED;
     const int32_t rc = thin_configure();
     if (rc != DS_OK) return rc;
-    ProfScope prof(DS_K_GEMM, s);
+    ProfScope prof(DS_K_THIN, s);
     const dim3 grid((unsigned)max_mtiles), block(NT);
     ThinChain none;
     memset(&none, 0, sizeof(none));
@@ -361,7 +361,7 @@ int32_t ds_launch_thin_chain(const GemmArgs& a, const ThinChain& ch, int32_t max
         if (ch.k_out[t] > 64 || (ch.k_out[t] > 0 && ch.k_out[t] % 8)) return DS_EUNSUPPORTED;
     const int32_t rc = thin_configure();
     if (rc != DS_OK) return rc;
-    ProfScope prof(DS_K_GEMM, s);
+    ProfScope prof(DS_K_THIN, s);
     hipLaunchKernelGGL((thin_kernel<true, 2, true>), dim3((unsigned)max_mtiles), dim3(NT), smem_bytes_chain(), s, a, max_mtiles, ch);
     DS_CHECK_LAUNCH("chained thin layers");
     return DS_OK;

@@ -5,6 +5,12 @@
          <copy_bytes> <out.json> "<commands>"
   python -m paper_2109_10060_amd.profiling layers <kernel_trace.csv> <layers.json> <out.txt> "<title>" "<command>"
 
+  python -m paper_2109_10060_amd.profiling counters <counter_collection.csv> [more.csv ...] <out.txt> "<title>" "<command>"
+
+`counters` averages the hardware counters of one or more rocprofv3 --pmc runs per kernel (over that kernel's dispatches)
+and derives, where the raw counters are present: the share of time the matrix pipes were busy (SQ_VALU_MFMA_BUSY_CYCLES
+over GRBM_GUI_ACTIVE x 1024 SIMDs), the LDS busy and bank-conflict shares, the L2 hit rate and the bytes the L2 served.
+
 `layers` joins a rocprofv3 kernel trace of the benchmark with the per-launch work list the benchmark writes
 (`bench.py --layers-json`): one row per kernel launch of a forward pass with its algorithmic flops and bytes, its
 duration averaged over the traced passes, the rates these give, the roof its arithmetic intensity selects
@@ -142,8 +148,48 @@ def layers(trace_csv, layers_json, out_path, title, command):
     open(out_path, "w").write("\n".join(lines) + "\n")
 
 
+def counters(csv_paths, out_path, title, command, top=12):
+    agg = {}     # kernel -> counter -> [sum, dispatches]
+    for path in csv_paths:
+        per_dispatch = {}
+        for r in csv.DictReader(open(path)):
+            key = (r["Dispatch_Id"], _short(r["Kernel_Name"]))
+            c, v = r["Counter_Name"], float(r["Counter_Value"])
+            d = per_dispatch.setdefault(key, {})
+            d[c] = d.get(c, 0.0) + v
+        for (_, k), vals in per_dispatch.items():
+            for c, v in vals.items():
+                e = agg.setdefault(k, {}).setdefault(c, [0.0, 0])
+                e[0] += v
+                e[1] += 1
+    mean = {k: {c: v[0] / v[1] for c, v in cs.items()} for k, cs in agg.items()}
+    order = sorted(mean, key=lambda k: -mean[k].get("GRBM_GUI_ACTIVE", 0.0) * max(v[1] for v in agg[k].values()))[:top]
+    names = sorted({c for k in order for c in mean[k]})
+    lines = [f"# {title}", f"# command: {command}",
+             "# per kernel: mean over its dispatches; derived figures first (clocks = GRBM_GUI_ACTIVE / 8 XCDs; mfma_busy: SQ_VALU_MFMA_BUSY_CYCLES / (clocks x 1024 SIMDs);",
+             "# lds_busy: SQ_LDS_IDX_ACTIVE / (clocks x 256 compute units); waves_per_simd: SQ_WAVE_CYCLES / (clocks x 1024); wave_wait: share of resident wave cycles spent waiting)",
+             "kernel | dispatches | " + " | ".join(["mfma_busy_pct", "lds_busy_pct", "lds_conflict_pct_of_lds", "wave_wait_pct", "waves_per_simd", "l2_hit_pct"] + names)]
+    for k in order:
+        m = mean[k]
+        # the tool reports every counter summed over its hardware instances: GRBM_GUI_ACTIVE is the busy clock of
+        # each of the 8 XCDs added up, so one eighth of it is the kernel's duration in clocks
+        act = m.get("GRBM_GUI_ACTIVE", 0.0) / 8.0
+        d = []
+        d.append(f"{100 * m['SQ_VALU_MFMA_BUSY_CYCLES'] / (act * 1024):.1f}" if act and "SQ_VALU_MFMA_BUSY_CYCLES" in m else "-")
+        d.append(f"{100 * m['SQ_LDS_IDX_ACTIVE'] / (act * 256):.1f}" if act and "SQ_LDS_IDX_ACTIVE" in m else "-")
+        d.append(f"{100 * m['SQ_LDS_BANK_CONFLICT'] / m['SQ_LDS_IDX_ACTIVE']:.1f}" if m.get("SQ_LDS_IDX_ACTIVE") and "SQ_LDS_BANK_CONFLICT" in m else "-")
+        d.append(f"{100 * m['TCC_HIT_sum'] / (m['TCC_HIT_sum'] + m['TCC_MISS_sum']):.1f}" if m.get("TCC_HIT_sum") is not None and (m.get("TCC_HIT_sum", 0) + m.get("TCC_MISS_sum", 0)) > 0 else "-")
+        d.insert(3, f"{100 * m['SQ_WAIT_ANY'] / m['SQ_WAVE_CYCLES']:.1f}" if m.get("SQ_WAVE_CYCLES") and "SQ_WAIT_ANY" in m else "-")
+        d.insert(4, f"{m['SQ_WAVE_CYCLES'] / (act * 1024):.2f}" if act and "SQ_WAVE_CYCLES" in m else "-")
+        n = max(v[1] for v in agg[k].values())
+        lines.append(f"{k} | {n} | " + " | ".join(d + [f"{m[c]:.0f}" if c in m else "-" for c in names]))
+    open(out_path, "w").write("\n".join(lines) + "\n")
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "layers":
+    if sys.argv[1] == "counters":
+        counters(sys.argv[2:-3], *sys.argv[-3:])
+    elif sys.argv[1] == "layers":
         layers(*sys.argv[2:7])
     elif sys.argv[1] == "stats":
         stats(*sys.argv[2:6])
