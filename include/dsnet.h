@@ -210,6 +210,19 @@ int32_t ds_sliced_dwconv_spatial(const void* x, int32_t B, int32_t C, int32_t H,
                                  int32_t act, void* y, int64_t y_sample_stride, void* ws,
                                  size_t ws_bytes, void* stream);
 
+/* Global average pool and classifier with sliced input width (the "Pool + FC" row of the routing-space tables,
+ * Section 5.2): logits[b, :] = W[:, :k_in[t]] . mean over the HW pixels of x[b, :, :k_in[t]] + bias for every sample b of
+ * group t.  x: device bf16 [B, HW, C] (channels-last, original sample order, C = stored width); w: device bf16
+ * [n_out, C]; bias: device fp32 [n_out] or NULL; logits: device fp32 [B, n_out]; the mean and the products are
+ * accumulated in fp32.  ws: ds_pool_head_workspace(B, C) bytes. */
+size_t ds_pool_head_workspace(int32_t B, int32_t C);
+int32_t ds_pool_head(const void* x, int32_t B, int32_t HW, int32_t C, const void* w, const float* bias,
+                     int32_t n_out, const ds_groups* g, float* logits, void* ws, size_t ws_bytes, void* stream);
+
+/* 3x3 stride-2 padding-1 max-pool of the ResNet-shaped stem (Section 5.2, DS-ResNet): x device bf16 [B, H, W, C],
+ * y device bf16 [B, (H - 1) / 2 + 1, (W - 1) / 2 + 1, C]; padding never wins (it counts as minus infinity). */
+int32_t ds_maxpool(const void* x, int32_t B, int32_t H, int32_t W, int32_t C, void* y, void* stream);
+
 /* LayerNorm over the k_in[t] valid features of each row with gamma[:k], beta[:k]
  * (the statistics use the valid features only).  x, y: device bf16 [B, rows, ld]. */
 int32_t ds_sliced_layernorm(const void* x, int64_t x_ld, const float* gamma, const float* beta,

@@ -32,7 +32,7 @@ EXPORTS = [
     "ds_last_error", "ds_version", "ds_bn_fold", "ds_bn_stats_workspace", "ds_bn_stats_accumulate", "ds_bn_stats_finish", "ds_gate_workspace", "ds_gate", "ds_gate_double_workspace",
     "ds_gate_double", "ds_route_bucket",
     "ds_sliced_linear_workspace", "ds_sliced_linear", "ds_sliced_linear_noalloc", "ds_sliced_conv_workspace", "ds_sliced_conv",
-    "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_dwconv_spatial", "ds_sliced_layernorm", "ds_sliced_mhsa_workspace",
+    "ds_slot_workspace", "ds_sliced_dwconv", "ds_sliced_dwconv_spatial", "ds_sliced_layernorm", "ds_pool_head_workspace", "ds_pool_head", "ds_maxpool", "ds_sliced_mhsa_workspace",
     "ds_sliced_mhsa", "ds_forward_workspace", "ds_forward", "ds_forward_taps", "ds_forward_parts_workspace", "ds_forward_parts", "ds_profile_enable", "ds_profile_reset", "ds_profile_read", "ds_profile_launches",
 ]
 
@@ -75,7 +75,7 @@ def load(path: Optional[str] = None):
     lib.ds_last_error.restype = ctypes.c_char_p
     for name in ("ds_gate_workspace", "ds_sliced_linear_workspace", "ds_sliced_conv_workspace",
                  "ds_slot_workspace", "ds_sliced_mhsa_workspace", "ds_forward_workspace", "ds_forward_parts_workspace", "ds_gate_double_workspace",
-                 "ds_bn_stats_workspace"):
+                 "ds_bn_stats_workspace", "ds_pool_head_workspace"):
         getattr(lib, name).restype = ctypes.c_size_t
     _lib = lib
     return lib
@@ -311,6 +311,26 @@ def ds_sliced_layernorm(x, gamma, beta, eps: float, groups: ds_groups, y=None):
     _chk(lib.ds_sliced_layernorm(_ptr(x, torch.bfloat16), ctypes.c_int64(ld), _ptr(gamma, torch.float32),
                                  _ptr(beta, torch.float32), ctypes.c_float(eps), ctypes.byref(groups), B, rows,
                                  _ptr(y), ctypes.c_int64(y.shape[-1]), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return y
+
+
+def ds_pool_head(x, w, bias, groups: ds_groups):
+    """x: [B, HW, C] bf16; w: [n_out, C] bf16.  Returns logits [B, n_out] fp32."""
+    lib = load()
+    B, HW, C = x.shape
+    n_out = w.shape[0]
+    logits = torch.empty((B, n_out), dtype=torch.float32, device=x.device)
+    ws = _ws(lib.ds_pool_head_workspace(B, C), x)
+    _chk(lib.ds_pool_head(_ptr(x, torch.bfloat16), B, HW, C, _ptr(w, torch.bfloat16), _ptr(bias), n_out, ctypes.byref(groups),
+                          _ptr(logits), _ptr(ws), ctypes.c_size_t(ws.numel()), _stream()))
+    return logits
+
+
+def ds_maxpool(x):
+    """x: [B, H, W, C] bf16 -> [B, Ho, Wo, C], 3x3 stride 2 padding 1."""
+    B, H, W, C = x.shape
+    y = torch.empty((B, (H - 1) // 2 + 1, (W - 1) // 2 + 1, C), dtype=x.dtype, device=x.device)
+    _chk(load().ds_maxpool(_ptr(x, torch.bfloat16), B, H, W, C, _ptr(y), _stream()))
     return y
 
 

@@ -354,3 +354,42 @@ extern "C" int32_t ds_sliced_mhsa(const void* x, int32_t B, int32_t N, int32_t D
     b.act = DS_ACT_NONE; b.out_f32 = 0; b.gt = gp;
     return ds_launch_gemm(b, cap, mi, s);
 }
+
+// ---- pool + classifier and max-pool as calls of their own ("Pool + FC" rows of the routing-space tables, Section 5.2) ----
+extern "C" size_t ds_pool_head_workspace(int32_t B, int32_t C) {
+    if (B <= 0 || C <= 0) return 0;
+    return 2 * ds_slot_workspace(B) + ds_align_up(ds_gate_partial_bytes(B, C), 256);
+}
+
+extern "C" int32_t ds_pool_head(const void* x, int32_t B, int32_t HW, int32_t C, const void* w, const float* bias,
+                                int32_t n_out, const ds_groups* g, float* logits, void* ws, size_t ws_bytes, void* stream) {
+    const char* who = "ds_pool_head";
+    if (B < 0 || HW < 1 || C < 1 || n_out < 1) DS_FAIL(DS_EINVAL, "%s: bad size", who);
+    GroupTable gt;
+    int mi, mo;
+    int32_t rc = check_groups(who, g, C, INT32_MAX, true, &gt, &mi, &mo);
+    if (rc) return rc;
+    if (B == 0) return DS_OK;
+    if (!x || !w || !logits) DS_FAIL(DS_EINVAL, "%s: null tensor", who);
+    if ((C % 8) || !ds_aligned16(x) || !ds_aligned16(w)) DS_FAIL(DS_EALIGN, "%s: needs 16-byte aligned pointers and C %% 8 == 0", who);
+    if (!ws || ws_bytes < ds_pool_head_workspace(B, C)) DS_FAIL(DS_EWORKSPACE, "%s: workspace needs %zu bytes", who, ds_pool_head_workspace(B, C));
+    hipStream_t s = (hipStream_t)stream;
+    int32_t* slot_group = (int32_t*)ws;
+    int32_t* slot_c = (int32_t*)((char*)ws + ds_slot_workspace(B));
+    float* partial = (float*)((char*)ws + 2 * ds_slot_workspace(B));
+    rc = ds_launch_expand_groups(g->offsets, g->T, slot_group, s);
+    if (rc) return rc;
+    rc = ds_launch_lookup(slot_group, gt, 0, slot_c, B, s);
+    if (rc) return rc;
+    ActView xv = {(void*)x, g->perm, (int64_t)HW * C, C};
+    return ds_launch_head(xv, HW, (const bf16_t*)w, C, bias, n_out, slot_c, g->perm, logits, partial, B, C, s);
+}
+
+extern "C" int32_t ds_maxpool(const void* x, int32_t B, int32_t H, int32_t W, int32_t C, void* y, void* stream) {
+    const char* who = "ds_maxpool";
+    if (B < 0 || H < 1 || W < 1 || C < 1) DS_FAIL(DS_EINVAL, "%s: bad size", who);
+    if (B == 0) return DS_OK;
+    if (!x || !y) DS_FAIL(DS_EINVAL, "%s: null tensor", who);
+    if ((C % 8) || !ds_aligned16(x) || !ds_aligned16(y)) DS_FAIL(DS_EALIGN, "%s: needs 16-byte aligned pointers and C %% 8 == 0", who);
+    return ds_launch_maxpool((const bf16_t*)x, (bf16_t*)y, B, H, W, C, (hipStream_t)stream);
+}

@@ -162,6 +162,13 @@ bool parse_mb(const ds_net* net, MbDesc* d) {
         d->kfull = d->cout + d->T * d->nb;
         d->ksize = d->kfull + d->nb;
     }
+    if (d->image < 1 || d->stem_out < 1 || d->gate_hidden < 1 || d->classes < 1) return false;
+    for (int i = 0; i < d->nb; ++i) {
+        const int st = d->blk[3 * i + 2];
+        if (d->blk[3 * i] < 1 || d->blk[3 * i + 1] < 1 || (st != 1 && st != 2)) return false;
+    }
+    for (int i = 0; i < 2 * d->T * d->nb; ++i)
+        if (d->cin[i] < 1) return false;                     // cin and cout are adjacent: every valid width is positive
     return d->gate_after >= 1 && d->gate_after < d->nb;
 }
 
@@ -170,7 +177,7 @@ struct MbPlan {
     float *gate_logits, *gate_partial;
     float* head_partial;
     int32_t *off1, *offs, *perm, *inv, *slot_group, *route, *slot_c;
-    void* lists[8];
+    void* lists[2 * 64 + 2];      // one tile list per (resolution, before / after the gate): at most one per block and phase
     int n_lists;
 };
 
@@ -360,6 +367,11 @@ bool parse_rn(const ds_net* net, RnDesc* d) {
     d->nblk = net->n_ints >= deep ? d->out + 4 * d->T : nullptr;
     d->single_gate = net->n_ints == deep + 1 ? (v[deep] & 1) : 0;
     if (rn_groups(*d) > DS_MAX_GROUPS) return false;
+    if (d->image < 1 || d->stem_out < 1 || d->classes < 1) return false;
+    for (int st = 0; st < 4; ++st)
+        if (d->widths[st] < 1 || d->blocks[st] < 1 || d->blocks[st] > 64 || d->hidden[st] < 1) return false;
+    for (int i = 0; i < 8 * d->T; ++i)
+        if (d->mid[i] < 1) return false;                     // mid and out are adjacent: every valid width is positive
     if (d->nblk)
         for (int st = 0; st < 4; ++st)
             for (int q = 0; q < d->T; ++q)

@@ -95,6 +95,20 @@ def test_host_validation_of_the_spatial_statistics_and_forward_entry_points():
     assert lib.ds_forward(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
     assert lib.ds_forward(ctypes.byref(net), None, -1, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_EINVAL
     assert lib.ds_forward(ctypes.byref(net), None, 0, None, None, None, None, None, ctypes.c_size_t(0), None) == ds.DS_OK
+    # a MobileNet-shaped description with a block stride of 0, then with a non-positive width: refused on the host
+    # (no workspace size, DS_ESHAPE from the forward call) instead of dividing by zero
+    def mb(stride, width):
+        nb, T = 2, 1
+        v = [32, 8, nb, 1, 4, T, 10] + [8, 16, 1, 16, width, stride] + [8, 16] + [16, width]
+        arr = (ctypes.c_int32 * len(v))(*v)
+        pp = (ctypes.c_void_p * (3 + 6 * nb + 6))(*([256] * (3 + 6 * nb + 6)))      # aligned, never dereferenced
+        return ds.ds_net(ds.DS_ARCH_MBNET, len(v), arr, len(pp), pp), arr, pp
+    good = mb(2, 16)
+    assert lib.ds_forward_workspace(ctypes.byref(good[0]), 4) > 0
+    for bad in (mb(0, 16), mb(3, 16), mb(1, 0), mb(1, -8)):
+        assert lib.ds_forward_workspace(ctypes.byref(bad[0]), 4) == 0
+        assert lib.ds_forward(ctypes.byref(bad[0]), ctypes.c_void_p(256), 4, None, None, ctypes.c_void_p(256), None, None,
+                              ctypes.c_size_t(0), None) == ds.DS_ESHAPE
     assert lib.ds_forward_parts_workspace(ctypes.byref(net), 4, 2) == 0 and lib.ds_forward_parts_workspace(ctypes.byref(net), 4, 5) == 0
     assert lib.ds_forward_parts(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), 0, None) == ds.DS_EINVAL
     assert lib.ds_forward_parts(ctypes.byref(net), None, 4, None, None, None, None, None, ctypes.c_size_t(0), 5, None) == ds.DS_EINVAL

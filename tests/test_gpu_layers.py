@@ -585,3 +585,34 @@ def test_bn_stats_streaming_recalibration(gpu_lib, HW, C):
     # the new tables go straight into the fold used by every sliced layer
     scale, shift = gpu_lib.ds_bn_fold(torch.ones(C, device=DEV), torch.zeros(C, device=DEV), mean, var, 1e-5)
     assert torch.isfinite(scale).all() and torch.isfinite(shift).all()
+
+
+# ------------------------------------------------------------------ pool + classifier, max-pool
+@pytest.mark.parametrize("B,HW,C,n_out,T", [(37, 49, 256, 1000, 4), (9, 196, 1024, 100, 14), (3, 1, 64, 10, 2)])
+def test_pool_head_sliced_input_width(gpu_lib, B, HW, C, n_out, T):
+    d = WL.nets.Draw(900 + C)
+    x = WL.nets.as_bf16_values(d.normal((B, HW, C)))
+    w = WL.nets.as_bf16_values(d.normal((n_out, C), std=C ** -0.5))
+    bias = d.normal((n_out,), std=0.1)
+    route = d.randint(B, T)
+    widths = [8 * max(1, (C // 8) * (t + 1) // T) for t in range(T)]
+    perm, inv, off = gpu_lib.ds_route_bucket(dev(route, torch.int32), T)
+    g = gpu_lib.make_groups(off, perm, widths, widths)
+    logits = gpu_lib.ds_pool_head(dev(x, torch.bfloat16), dev(w, torch.bfloat16), dev(bias), g)
+    lg = host(logits)
+    for b in range(B):
+        c = widths[route[b]]
+        pooled = O.gate_encoder(x[b, :, :c].T.reshape(c, HW, 1))
+        want = O.sliced_linear(pooled, w[:, :c], bias, n_out)
+        assert relerr(lg[b], want) < 1e-4, b          # fp32 accumulation of bf16 values over up to 196 x 1024 terms
+
+
+@pytest.mark.parametrize("B,H,W,C", [(5, 112, 112, 64), (3, 7, 9, 24), (2, 1, 1, 8)])
+def test_maxpool_3x3_stride2(gpu_lib, B, H, W, C):
+    d = WL.nets.Draw(950 + H)
+    x = WL.nets.as_bf16_values(d.normal((B, H, W, C)))
+    y = gpu_lib.ds_maxpool(dev(x, torch.bfloat16))
+    yh = host(y)
+    for b in range(B):
+        want = O.maxpool3x3s2(x[b].transpose(2, 0, 1))          # oracle layout [C, H, W]
+        assert np.array_equal(yh[b].transpose(2, 0, 1), want), b   # a maximum of bf16 values is one of them: bit-exact
