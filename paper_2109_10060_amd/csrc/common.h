@@ -254,7 +254,7 @@ struct ProfScope {
     ~ProfScope();
 };
 
-struct ProfPause {   // no launch inside its scope is recorded (and no event is created)
+struct ProfPause {   // no launch made by this thread inside its scope is recorded (and no event is created)
     bool was;
     ProfPause();
     ~ProfPause();

@@ -14,6 +14,7 @@
 // bytes are touched.  The first sliced layer gathers whole samples through the
 // permutation; the classifier scatters logits back to the original order.
 #include <string.h>
+#include <mutex>
 
 #include "common.h"
 
@@ -962,19 +963,24 @@ int32_t run_part(const ds_net* net, const bf16_t* images, int b0, int Bp, int Bs
 }
 
 // side streams and fork / join events of ds_forward_parts, made on first use, one set per device, kept until the
-// process ends (default priority, no device memory)
+// process ends (default priority, no device memory).  A device's set is shared by every call on that device, so
+// the caller of part_streams holds the set's mutex while it enqueues: calls from several host threads then
+// fork and join one after the other instead of recording over each other's events.
 constexpr int MAX_PARTS = 4, MAX_DEVICES = 16;
 struct PartStreams {
-    bool ready;
+    std::mutex mu;
+    bool ready = false;
     hipStream_t side[MAX_PARTS - 1];
     hipEvent_t fork, join[MAX_PARTS - 1];
 };
 PartStreams g_part_streams[MAX_DEVICES];
 
-int32_t part_streams(PartStreams** out) {
+// call with ps.mu of the current device's set held by the returned lock
+int32_t part_streams(PartStreams** out, std::unique_lock<std::mutex>* lock) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) DS_FAIL(DS_EHIP, "ds_forward_parts: no current device");
     PartStreams& ps = g_part_streams[dev];
+    *lock = std::unique_lock<std::mutex>(ps.mu);
     if (!ps.ready) {
         if (hipEventCreateWithFlags(&ps.fork, hipEventDisableTiming) != hipSuccess) DS_FAIL(DS_EHIP, "ds_forward_parts: event creation failed");
         for (int i = 0; i < MAX_PARTS - 1; ++i)
@@ -1040,7 +1046,8 @@ extern "C" int32_t ds_forward_parts(const ds_net* net, const void* images, int32
     hipStream_t s = (hipStream_t)stream;
     if (n == 1) return run_part(net, (const bf16_t*)images, 0, B, B, route_override, logit_bias, logits, routes_out, ws, s);
     PartStreams* ps = nullptr;
-    RC(part_streams(&ps));
+    std::unique_lock<std::mutex> enqueue_lock;
+    RC(part_streams(&ps, &enqueue_lock));
     // the side streams start after everything already queued on the caller's stream and the caller's stream continues
     // after them: to the caller the call is one piece of work on its stream
     if (hipEventRecord(ps->fork, s) != hipSuccess) DS_FAIL(DS_EHIP, "%s: event record failed", who);

@@ -2,6 +2,10 @@
 // with a pair of HIP events on the launch stream; ds_profile_read sums the elapsed
 // times per kernel class.  Off by default; costs nothing when off.  Recording can be
 // paused and resumed (records accumulate) so that a caller samples some of its steps.
+// The record list is guarded by one mutex, so launchers on several host threads may record at once; the
+// records then interleave in the order the threads took the lock.
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -11,13 +15,16 @@ struct Rec {
     hipEvent_t a, b;
     int kind;
 };
-bool g_on = false;
-std::vector<Rec> g_pool;  // events are created once and reused
+std::atomic<bool> g_on{false};
+thread_local int t_paused = 0;   // entry points that must not allocate pause recording on their own thread only
+std::mutex g_mu;                 // guards g_pool and g_used
+std::vector<Rec> g_pool;         // events are created once and reused
 size_t g_used = 0;
 }  // namespace
 
 ProfScope::ProfScope(int kind, hipStream_t stream) : rec(-1), s(stream) {
-    if (!g_on) return;
+    if (!g_on.load(std::memory_order_relaxed) || t_paused) return;
+    std::lock_guard<std::mutex> lock(g_mu);
     if (g_used == g_pool.size()) {
         Rec r;
         if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
@@ -30,19 +37,22 @@ ProfScope::ProfScope(int kind, hipStream_t stream) : rec(-1), s(stream) {
 }
 
 ProfScope::~ProfScope() {
-    if (rec >= 0) (void)hipEventRecord(g_pool[rec].b, s);
+    if (rec < 0) return;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if ((size_t)rec < g_pool.size()) (void)hipEventRecord(g_pool[rec].b, s);
 }
 
 // recording creates HIP events on first use; entry points that must not allocate switch it off for their duration
-ProfPause::ProfPause() : was(g_on) { g_on = false; }
-ProfPause::~ProfPause() { g_on = was; }
+ProfPause::ProfPause() : was(t_paused != 0) { ++t_paused; }
+ProfPause::~ProfPause() { --t_paused; }
 
 extern "C" int32_t ds_profile_enable(int32_t on) {
-    g_on = on != 0;
+    g_on.store(on != 0);
     return DS_OK;
 }
 
 extern "C" int32_t ds_profile_reset(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
     g_used = 0;
     return DS_OK;
 }
@@ -51,6 +61,7 @@ extern "C" int32_t ds_profile_read(int32_t kind, double* total_ms, int64_t* laun
     if (kind < 0 || kind >= DS_K_COUNT || !total_ms || !launches) DS_FAIL(DS_EINVAL, "ds_profile_read: bad argument");
     double t = 0.0;
     int64_t n = 0;
+    std::lock_guard<std::mutex> lock(g_mu);
     for (size_t i = 0; i < g_used; ++i) {
         if (g_pool[i].kind != kind) continue;
         if (hipEventSynchronize(g_pool[i].b) != hipSuccess) DS_FAIL(DS_EHIP, "ds_profile_read: event sync failed");
@@ -66,6 +77,7 @@ extern "C" int32_t ds_profile_read(int32_t kind, double* total_ms, int64_t* laun
 
 extern "C" int32_t ds_profile_launches(int32_t* kinds, float* ms, int64_t capacity, int64_t* count) {
     if (!count || capacity < 0 || (capacity > 0 && (!kinds || !ms))) DS_FAIL(DS_EINVAL, "ds_profile_launches: bad argument");
+    std::lock_guard<std::mutex> lock(g_mu);
     *count = (int64_t)g_used;
     for (size_t i = 0; i < g_used && (int64_t)i < capacity; ++i) {
         if (hipEventSynchronize(g_pool[i].b) != hipSuccess) DS_FAIL(DS_EHIP, "ds_profile_launches: event sync failed");

@@ -96,7 +96,7 @@ PEAK_TFLOPS, PEAK_GBS = 2500.0, 8000.0
 
 def layers(trace_csv, layers_json, out_path, title, command):
     work = json.load(open(layers_json))
-    rows = list(csv.DictReader(open(trace_csv)))
+    rows = sorted(csv.DictReader(open(trace_csv)), key=lambda r: int(r["Start_Timestamp"]))   # launch order
     per_class = {}
     for r in rows:
         name = r["Kernel_Name"]
@@ -167,8 +167,8 @@ def counters(csv_paths, out_path, title, command, top=12):
     names = sorted({c for k in order for c in mean[k]})
     lines = [f"# {title}", f"# command: {command}",
              "# per kernel: mean over its dispatches; derived figures first (clocks = GRBM_GUI_ACTIVE / 8 XCDs; mfma_busy: SQ_VALU_MFMA_BUSY_CYCLES / (clocks x 1024 SIMDs);",
-             "# lds_busy: SQ_LDS_IDX_ACTIVE / (clocks x 256 compute units); waves_per_simd: SQ_WAVE_CYCLES / (clocks x 1024); wave_wait: share of resident wave cycles spent waiting)",
-             "kernel | dispatches | " + " | ".join(["mfma_busy_pct", "lds_busy_pct", "lds_conflict_pct_of_lds", "wave_wait_pct", "waves_per_simd", "l2_hit_pct"] + names)]
+             "# lds_busy: SQ_LDS_IDX_ACTIVE / (clocks x 256 compute units); wave_wait: SQ_WAIT_ANY / SQ_WAVE_CYCLES, the share of resident wave cycles spent waiting)",
+             "kernel | dispatches | " + " | ".join(["mfma_busy_pct", "lds_busy_pct", "lds_conflict_pct_of_lds", "wave_wait_pct", "l2_hit_pct"] + names)]
     for k in order:
         m = mean[k]
         # the tool reports every counter summed over its hardware instances: GRBM_GUI_ACTIVE is the busy clock of
@@ -180,7 +180,6 @@ def counters(csv_paths, out_path, title, command, top=12):
         d.append(f"{100 * m['SQ_LDS_BANK_CONFLICT'] / m['SQ_LDS_IDX_ACTIVE']:.1f}" if m.get("SQ_LDS_IDX_ACTIVE") and "SQ_LDS_BANK_CONFLICT" in m else "-")
         d.append(f"{100 * m['TCC_HIT_sum'] / (m['TCC_HIT_sum'] + m['TCC_MISS_sum']):.1f}" if m.get("TCC_HIT_sum") is not None and (m.get("TCC_HIT_sum", 0) + m.get("TCC_MISS_sum", 0)) > 0 else "-")
         d.insert(3, f"{100 * m['SQ_WAIT_ANY'] / m['SQ_WAVE_CYCLES']:.1f}" if m.get("SQ_WAVE_CYCLES") and "SQ_WAIT_ANY" in m else "-")
-        d.insert(4, f"{m['SQ_WAVE_CYCLES'] / (act * 1024):.2f}" if act and "SQ_WAVE_CYCLES" in m else "-")
         n = max(v[1] for v in agg[k].values())
         lines.append(f"{k} | {n} | " + " | ".join(d + [f"{m[c]:.0f}" if c in m else "-" for c in names]))
     open(out_path, "w").write("\n".join(lines) + "\n")

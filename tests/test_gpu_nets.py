@@ -544,3 +544,45 @@ def test_forward_parts_equals_forward(gpu_lib, kind):
     # too small a workspace is refused before anything is launched
     with pytest.raises(gpu_lib.DsError):
         gpu_lib.ds_forward_parts(net, xg, 2, logit_bias=lbg, ws=torch.empty(256, dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.gpu
+def test_forward_parts_from_two_host_threads(gpu_lib):
+    """The side streams and fork / join events of ds_forward_parts are one set per device; calls from two host
+    threads, each on a stream and workspace of its own, take turns enqueueing and both equal ds_forward."""
+    import threading
+    B = 29
+    arch = WL.vit_arch(image=64, patch=16, depth=2, routes="diag")
+    net = gpu_lib.build_vit(arch, WL.vit_params(arch, S + 50), DEV)
+    xs, lbs, wants, outs, wss, streams = [], [], [], [], [], []
+    for t in range(2):
+        xg = torch.from_numpy(WL.images(S + 60 + t, B, 64)).to(DEV).to(torch.bfloat16).contiguous()
+        lb = WL.seeded_logit_bias(S + 62 + t, B, arch["T"])[None]
+        lbs.append(torch.from_numpy(np.ascontiguousarray(lb, dtype=np.float32)).to(DEV))
+        xs.append(xg)
+        wants.append(gpu_lib.ds_forward(net, xg, logit_bias=lbs[t]))
+        outs.append((torch.empty((B, net.num_classes), dtype=torch.float32, device=DEV),
+                     torch.empty((net.n_gates, B), dtype=torch.int32, device=DEV)))
+        wss.append(net.workspace(B, 3))
+        streams.append(torch.cuda.Stream())
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(t):
+        try:
+            with torch.cuda.stream(streams[t]):
+                for _ in range(8):
+                    gpu_lib.ds_forward_parts(net, xs[t], 3, logit_bias=lbs[t], logits=outs[t][0], routes=outs[t][1], ws=wss[t])
+        except Exception as e:  # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for t in range(2):
+        assert torch.equal(outs[t][1], wants[t][1]), t
+        assert relerr(outs[t][0].cpu().numpy(), wants[t][0].cpu().numpy()) < 1e-5, t
