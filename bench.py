@@ -429,6 +429,15 @@ def main():
                                            "roofline", "kernels")}
         args.layers_json = layers_json
         out["other_workloads"] = others
+        if args.parts == 1:
+            # the same batch through ds_forward_parts: four shares on streams of the library fill each other's launch ramps
+            # and tails; reported beside the headline, which stays on ds_forward because overlapping kernels have no
+            # duration of their own to hold against a roofline
+            a4 = argparse.Namespace(**vars(args))
+            a4.parts, a4.no_kernel_events, a4.layers_json = 4, True, ""
+            r = run_net("resnet", a4, max(10, args.steps // 2), max(3, args.warmup // 2), False)
+            out["concurrent_shares"] = {"entry_point": "ds_forward_parts", "parts": 4,
+                                        **{k: r[k] for k in ("value", "unit", "ms_per_step", "ms_per_step_median", "steps", "warmup")}}
     print(json.dumps(out))
 
 
