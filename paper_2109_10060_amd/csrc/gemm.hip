@@ -13,8 +13,10 @@
 // v_mfma_f32_32x32x16_bf16 accumulators (the dispatcher uses this shape for every layer: with ragged route
 // groups and slices as narrow as 64 channels the wider 128 x 128 / 128 x 256 instantiations lose more to
 // quantisation and residency than their lower operand traffic gains).  Operands go through one LDS tile in
-// 32-deep slabs, or 64-deep ones for reductions of 256 steps and more (64- or 128-byte rows, 16-byte chunks
-// XOR-swizzled by row so stores and reads are bank-conflict free); the next slab's global loads are issued into
+// 32-deep slabs, 64-deep ones for reductions of 256 steps and more, or 128-deep ones where a launch is about one
+// generation of workgroups and a filter tap has 512 channels or more (the last ResNet stage: half as many dependent
+// load -> LDS -> barrier rounds per workgroup; 64-, 128- or 256-byte rows, 16-byte chunks XOR-swizzled by row so
+// stores and reads are bank-conflict free); the next slab's global loads are issued into
 // registers before the current slab's matrix instructions and stored to LDS after them, and 5-6 resident
 // workgroups per compute unit hide each other's round trips.  The epilogue (split batch-norm scale and
 // shift or bias, residual, ReLU/GELU, bf16 rounding) re-reads the accumulators through LDS so that every lane
@@ -35,7 +37,7 @@ constexpr int BM = DS_GEMM_BM, NT = 256;
 // bank-conflict free for 8- and 16-lane access groups alike
 template <int BK>
 __device__ __forceinline__ int swz(int r) {
-    return BK == 64 ? ((r ^ (r >> 3)) & 7) : (((r >> 1) ^ (r >> 2)) & 3);
+    return BK == 128 ? (r & 15) : BK == 64 ? ((r ^ (r >> 3)) & 7) : (((r >> 1) ^ (r >> 2)) & 3);
 }
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
@@ -55,7 +57,7 @@ struct Tile {
 };
 
 template <int WROWS, int WCOLS, int WMT, int WNT, int BK, bool CONV, bool HASR>
-__global__ __launch_bounds__(NT, (WMT * WNT == 2 && !CONV) ? (BK == 32 ? (HASR ? 5 : 6) : 5) : 1) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
+__global__ __launch_bounds__(NT, BK == 128 ? 3 : (WMT * WNT == 2 && !CONV) ? (BK == 32 ? (HASR ? 5 : 6) : 5) : 1) void gemm_kernel(const GemmArgs a, const int ny, const int max_mtiles) {
     using TL = Tile<WROWS, WCOLS, WMT, WNT, BK>;
     constexpr int BN = TL::BN, LDS_LD = BK, CPR = BK / 8, RPT = NT / CPR;   // chunks per row, rows per pass
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(NT, (WMT * WNT == 2 && !CONV) ? (BK == 32 ? (HASR ?
     const bf16_t* as = As + (wm * WMT * 32 + l32) * LDS_LD;
     const bf16_t* bs = Bs + (wn * WNT * 32 + l32) * LDS_LD;
     const int fa = swz<BK>(wm * WMT * 32 + l32), fb = swz<BK>(wn * WNT * 32 + l32);
-    constexpr int TK = BK == 64 ? 4 : 0;
+    constexpr int TK = BK == 64 ? 4 : 0;   // 256-byte rows: the key is the row's low four bits, the same 32 rows on
 
     const int kchunks = (k_in + BK - 1) / BK;
     const int nk = a.K * (a.Kw > 0 ? a.Kw : a.K) * kchunks;
@@ -428,6 +430,9 @@ int32_t ds_launch_gemm(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
           : (a.R ? launch<__VA_ARGS__, false, true>(a, max_mtiles, max_kout, s)                        \
                  : launch<__VA_ARGS__, false, false>(a, max_mtiles, max_kout, s)))
     if (!deep) return DS_GEMM_DISPATCH(4, 1, 1, 2, 32);   // 64-wide tile, 32-deep slabs
+    // launches of about one generation with long reductions: 128-deep slabs halve the number of dependent rounds
+    const long long wgs = (long long)max_mtiles * a.n_seg * ((max_kout + 63) / 64);
+    if (kmax >= 512 && wgs <= 256 * 6) return DS_GEMM_DISPATCH(4, 1, 1, 2, 128);
     return DS_GEMM_DISPATCH(4, 1, 1, 2, 64);
 #undef DS_GEMM_DISPATCH
 }

@@ -274,7 +274,11 @@ def test_config1_forced_routes_cover_all_ratios(gpu_lib):
                                                        # 3x3 stride 1 on wide maps: the patch-staged kernel up to 59 pixels,
                                                        # the tap-walking kernel beyond
                                                        (3, 1, 1, 56, 32, 72, False), (3, 1, 1, 59, 32, 16, True),
-                                                       (3, 1, 1, 60, 32, 16, False)])
+                                                       (3, 1, 1, 60, 32, 16, False),
+                                                       # few workgroups and 512+ channels per tap: the 128-deep slabs, with
+                                                       # slices that end 8 channels into a slab
+                                                       (1, 1, 0, 7, 1040, 72, True), (1, 1, 0, 7, 1040, 136, False),
+                                                       (3, 2, 1, 9, 528, 40, False)])
 def test_sliced_conv_bf16_nhwc(gpu_lib, K, stride, pad, H, CI, CO, res):
     B, T = 11, 4
     d = WL.nets.Draw(1000 + K * 10 + stride + CI)
