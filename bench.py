@@ -151,6 +151,20 @@ def run_linear(args):
     torch.cuda.synchronize()
     ms_per_step = max((time.perf_counter() - t0) * 1e3, e0.elapsed_time(e1)) / args.steps
     prof = ds.ds_profile_read() if sampled else {}
+    # the same step with cold caches: a 1 GiB device fill between steps evicts L2 and the memory-side cache, so the
+    # operands and the weight come from HBM; each step is timed on its own
+    scratch = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cold = []
+    for i in range(min(20, args.steps)):
+        scratch.fill_(i & 1)
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        step()
+        a1.record()
+        torch.cuda.synchronize()
+        cold.append(a0.elapsed_time(a1))
+    cold.sort()
+    del scratch
     k_in = c["k_in"][c["route"]].astype(np.float64)
     k_out = c["k_out"][c["route"]].astype(np.float64)
     flops = 2.0 * c["N"] * float(np.sum(k_in * k_out))
@@ -175,6 +189,8 @@ def run_linear(args):
                                "bucket + one grouped GEMM, operands warm in the caches", "batch": B,
                    "route_histogram": [np.bincount(c["route"], minlength=4).tolist()]},
         "roofline": roofline,
+        "cold_caches": {"ms_per_step_median": cold[len(cold) // 2], "ms_per_step_min": cold[0], "steps": len(cold),
+                        "flush": "1 GiB device fill before every step"},
     }
     if not args.no_cpu_baseline:
         from oracle import ds_oracle as O
