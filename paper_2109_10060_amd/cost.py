@@ -98,10 +98,10 @@ def resnet_cost(arch, routes) -> Cost:
         out = arch["out"][s][routes[s]].astype(np.float64)
         if s == 0 or not arch.get("single_gate"):
             c.add("gate", 2.0 * r * r * cprev.sum(), 2.0 * r * r * cprev.sum(), name=f"s{s} gate pool + MLP")
-        # stages with slices of at most 64 channels run a block's last convolution and the next block's first one
+        # stages with slices of at most 128 channels run a block's last convolution and the next block's first one
         # as one launch (the wide map is written once and not read back)
         mids, outs = arch["mid"][s], arch["out"][s]
-        chain = bool(mids.max() <= 64 and outs.max() >= 128 and not (mids % 8).any() and not (outs % 8).any())
+        chain = bool(mids.max() <= 128 and outs.max() >= 128 and not (mids % 8).any() and not (outs % 8).any())
         for b in range(nb):
             # dynamic depth: samples whose route has run its blocks of this stage contribute nothing
             on = (arch["nblk"][s][routes[s]] > b).astype(np.float64) if arch.get("nblk") is not None else np.ones(B)

@@ -29,15 +29,22 @@ __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ (r >> 2)) & 3; }
 // CHAIN: the rows' results feed a second 1x1 layer of at most 64 output channels before they leave the workgroup
 // (the next bottleneck's first convolution): each pass's 64 result columns are one reduction slab of that layer, whose
 // accumulators stay in registers over the passes, so the wide map is written once and not read back.
-template <bool HASR, int KCH, bool CHAIN>
-__global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs a, const int max_mtiles, const ThinChain ch) {
+// N2B: 32-column blocks of the second layer's output (2: up to 64 channels, 4: up to 128).  With 128-channel input slices
+// (KCH = 4) the second layer's slab takes the place of the first layer's weights once the pass's own matrix
+// instructions are done (one more barrier per pass), so that two workgroups per compute unit still fit.
+template <bool HASR, int KCH, bool CHAIN, int N2B = 2>
+__global__ __launch_bounds__(NT, CHAIN ? (KCH == 4 ? 2 : 3) : 1) void thin_kernel(const GemmArgs a, const int max_mtiles, const ThinChain ch) {
     constexpr int A_BYTES = KCH * BM * 64, B_BYTES = KCH * 64 * 64, CP = KCH * 4;   // CP 16-byte pieces per operand row
     constexpr int NAP = BM * CP / NT, NWP = 64 * CP / NT;                            // pieces per lane: activations, weights
+    constexpr bool W2_ALIAS = CHAIN && KCH == 4;
+    constexpr int N2R = 32 * N2B;                      // rows (output channels) of the second layer's slab
+    static_assert(!W2_ALIAS || 2 * N2R * 64 <= B_BYTES, "the second layer's slab fits the first layer's weight tile");
+    static_assert(W2_ALIAS || N2B == 2, "the separate slab holds 64 output channels");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* As = smem;                                   // [KCH][128][32] bf16
     char* Bs = smem + A_BYTES;                         // [KCH][64][32] bf16
-    char* W2s = smem + A_BYTES + B_BYTES;              // CHAIN only: [2][64][32] bf16, the second layer's slab of the pass
-    constexpr int T_OFF = A_BYTES + B_BYTES + (CHAIN ? W2_BYTES : 0);
+    char* W2s = W2_ALIAS ? Bs : smem + A_BYTES + B_BYTES;   // CHAIN only: [2][N2R][32] bf16, the second layer's slab of the pass
+    constexpr int T_OFF = A_BYTES + B_BYTES + (CHAIN && !W2_ALIAS ? W2_BYTES : 0);
     bf16_t* tile = (bf16_t*)(smem + T_OFF);            // [128][T_LD]: residual in, result out
     long long* rowC = (long long*)(smem + T_OFF + TILE_BYTES);
     long long* rowR = rowC + BM;                       // CHAIN: rows of the second output (the residual is addressed like C)
@@ -137,21 +144,28 @@ __global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs 
     const int kch = (k_in + 31) >> 5;                  // chunks of this group's reduction, at most KCH
     // second layer: its weights for the 64 channels of a pass, 2 pieces per lane (row tid / 8 + 32 i, channels 8 (tid % 8) ..)
     const __amdgpu_buffer_rsrc_t rsrc_w2 = __builtin_amdgcn_make_buffer_rsrc((void*)(CHAIN ? ch.Wt : a.Wt), 0, 0x7fffffff, 0x00020000);
-    uint4 w2reg[2];
-    f32x16_t acc2[2];
+    uint4 w2reg[N2B];
+    f32x16_t acc2[N2B];
     auto fetch_w2 = [&](int n0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < N2B; ++i) {
             const int nl = (tid >> 3) + 32 * i, c0 = n0 + (tid & 7) * 8;
             const bool ok = nl < k_out2 && c0 < k_out;
             const auto t = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w2, (int)(ok ? (uint32_t)(((long long)nl * ch.w_ld + c0) * 2) : OOB), 0, 0);
             w2reg[i] = make_uint4(t[0], t[1], t[2], t[3]);
         }
     };
+    auto store_w2 = [&]() {
+#pragma unroll
+        for (int i = 0; i < N2B; ++i) {
+            const int nl = (tid >> 3) + 32 * i, pc = tid & 7;
+            *(uint4*)(W2s + ((pc >> 2) * N2R + nl) * 64 + (((pc & 3) ^ swz(nl)) * 16)) = w2reg[i];
+        }
+    };
     if constexpr (CHAIN) {
         if (k_out2 > 0) fetch_w2(0);
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < N2B; ++t)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc2[t][e] = 0.f;
     }
@@ -163,14 +177,8 @@ __global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs 
             *(uint4*)(Bs + ((oc8 >> 2) * 64 + nl) * 64 + (((oc8 & 3) ^ swz(nl)) * 16)) = wreg[i];
         }
         if (tid < 128) cst[tid] = creg;
-        if constexpr (CHAIN) {
-            if (k_out2 > 0) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int nl = (tid >> 3) + 32 * i, pc = tid & 7;
-                    *(uint4*)(W2s + ((pc >> 2) * 64 + nl) * 64 + (((pc & 3) ^ swz(nl)) * 16)) = w2reg[i];
-                }
-            }
+        if constexpr (CHAIN && !W2_ALIAS) {
+            if (k_out2 > 0) store_w2();
         }
         if constexpr (HASR) {
 #pragma unroll
@@ -179,7 +187,7 @@ __global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs 
         __syncthreads();
         if (n0 + 64 < k_out) {                         // in flight during this pass
             fetch_pass(n0 + 64);
-            if constexpr (CHAIN) {
+            if constexpr (CHAIN && !W2_ALIAS) {
                 if (k_out2 > 0) fetch_w2(n0 + 64);
             }
         }
@@ -229,6 +237,15 @@ __global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs 
                 *tp = o;
             }
         __syncthreads();
+        if constexpr (W2_ALIAS) {
+            // every wavefront is done with the first layer's weights of this pass: the second layer's slab takes their
+            // place, and the slab of the next pass is requested (a whole pass ahead of its use)
+            if (k_out2 > 0) {                          // uniform over the workgroup
+                store_w2();
+                if (n0 + 64 < k_out) fetch_w2(n0 + 64);
+                __syncthreads();
+            }
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = prow8 + 32 * i;
@@ -243,9 +260,9 @@ __global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs 
                     const bf16x8_t pf = *(const bf16x8_t*)(tile + prow * T_LD + kk * 16 + lhi * 8);
                     const int c = (kk & 1) * 2 + lhi;
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
+                    for (int t = 0; t < N2B; ++t) {
                         const int nr = t * 32 + l32;
-                        const bf16x8_t wf = *(const bf16x8_t*)(W2s + ((kk >> 1) * 64 + nr) * 64 + ((c ^ swz(nr)) * 16));
+                        const bf16x8_t wf = *(const bf16x8_t*)(W2s + ((kk >> 1) * N2R + nr) * 64 + ((c ^ swz(nr)) * 16));
                         acc2[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, pf, acc2[t], 0, 0, 0);
                     }
                 }
@@ -254,34 +271,41 @@ __global__ __launch_bounds__(NT, CHAIN ? 3 : 1) void thin_kernel(const GemmArgs 
     }
     if constexpr (CHAIN) {
         if (k_out2 <= 0) return;
-        __syncthreads();                               // the last pass's tile has been read
         const long long trow2 = (long long)a.gt.row[g] * ch.tab_ld;
+        // the second layer's results leave through the same tile, 64 columns at a time
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int hb = 0; hb < N2B / 2; ++hb) {
+            if (hb * 64 >= k_out2) break;              // uniform over the workgroup
+            __syncthreads();                           // the last pass's tile (or the previous 64 columns) has been read
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = t * 32 + q * 8 + lhi * 4;
-                float4 s4 = make_float4(1.f, 1.f, 1.f, 1.f), h4 = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (col < k_out2) {
-                    if (ch.scale) s4 = *(const float4*)(ch.scale + trow2 + col);
-                    if (ch.shift) h4 = *(const float4*)(ch.shift + trow2 + col);
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = t * 32 + q * 8 + lhi * 4, gcol = hb * 64 + col;
+                    float4 s4 = make_float4(1.f, 1.f, 1.f, 1.f), h4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (gcol < k_out2) {
+                        if (ch.scale) s4 = *(const float4*)(ch.scale + trow2 + gcol);
+                        if (ch.shift) h4 = *(const float4*)(ch.shift + trow2 + gcol);
+                    }
+                    const f32x16_t& av = acc2[2 * hb + t];
+                    float v[4] = {av[4 * q] * s4.x + h4.x, av[4 * q + 1] * s4.y + h4.y, av[4 * q + 2] * s4.z + h4.z,
+                                  av[4 * q + 3] * s4.w + h4.w};
+                    if (ch.act == DS_ACT_RELU) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
+                    }
+                    uint2 o;
+                    o.x = f2bf2(v[0], v[1]);
+                    o.y = f2bf2(v[2], v[3]);
+                    *(uint2*)(tile + prow * T_LD + col) = o;
                 }
-                float v[4] = {acc2[t][4 * q] * s4.x + h4.x, acc2[t][4 * q + 1] * s4.y + h4.y, acc2[t][4 * q + 2] * s4.z + h4.z,
-                              acc2[t][4 * q + 3] * s4.w + h4.w};
-                if (ch.act == DS_ACT_RELU) {
+            __syncthreads();
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-                }
-                uint2 o;
-                o.x = f2bf2(v[0], v[1]);
-                o.y = f2bf2(v[2], v[3]);
-                *(uint2*)(tile + prow * T_LD + col) = o;
+            for (int i = 0; i < 4; ++i) {
+                const int row = prow8 + 32 * i;
+                if (rowC[row] >= 0 && hb * 64 + pc8 < k_out2)
+                    *(uint4*)(ch.C + rowR[row] + hb * 64 + pc8) = *(const uint4*)(tile + row * T_LD + pc8);
             }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = prow8 + 32 * i;
-            if (rowC[row] >= 0 && pc8 < k_out2) *(uint4*)(ch.C + rowR[row] + pc8) = *(const uint4*)(tile + row * T_LD + pc8);
         }
     }
 }
@@ -309,12 +333,13 @@ int32_t thin_supported(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
 }
 
 int32_t thin_configure() {
-    const int32_t rc[5] = {ds_reserve_lds((const void*)thin_kernel<true, 2, false>, smem_bytes(2), "thin layer"),
+    const int32_t rc[6] = {ds_reserve_lds((const void*)thin_kernel<true, 4, true, 4>, smem_bytes(4), "thin layer"),
+                           ds_reserve_lds((const void*)thin_kernel<true, 2, false>, smem_bytes(2), "thin layer"),
                            ds_reserve_lds((const void*)thin_kernel<false, 2, false>, smem_bytes(2), "thin layer"),
                            ds_reserve_lds((const void*)thin_kernel<true, 4, false>, smem_bytes(4), "thin layer"),
                            ds_reserve_lds((const void*)thin_kernel<false, 4, false>, smem_bytes(4), "thin layer"),
                            ds_reserve_lds((const void*)thin_kernel<true, 2, true>, smem_bytes_chain(), "thin layer")};
-    for (int i = 0; i < 5; ++i)
+    for (int i = 0; i < 6; ++i)
         if (rc[i]) return rc[i];
     return DS_OK;
 }
@@ -344,25 +369,32 @@ int32_t ds_launch_thin(const GemmArgs& a, int32_t max_mtiles, int32_t max_kout, 
     return DS_OK;
 }
 
-// The same layer (input slices up to 64 channels, residual addressed like the output) followed, inside the workgroup, by a
-// second 1x1 layer over the result rows with at most 64 output channels per group; DS_EUNSUPPORTED otherwise (the
-// caller then launches the two layers one after the other)
+// The same layer (input slices up to 128 channels, residual addressed like the output) followed, inside the workgroup, by
+// a second 1x1 layer over the result rows with at most 128 output channels per group (64 / 64: three workgroups per
+// compute unit; beyond: two); DS_EUNSUPPORTED otherwise (the caller then launches the two layers one after the other)
 int32_t ds_launch_thin_chain(const GemmArgs& a, const ThinChain& ch, int32_t max_mtiles, int32_t max_kout, hipStream_t s) {
     if (max_mtiles <= 0 || max_kout <= 0) return DS_EUNSUPPORTED;
     int kmax = 0;
-    if (thin_supported(a, max_mtiles, max_kout, &kmax) != DS_OK || kmax > 64) return DS_EUNSUPPORTED;
+    if (thin_supported(a, max_mtiles, max_kout, &kmax) != DS_OK) return DS_EUNSUPPORTED;
     if (!a.R || !a.r_use_index || a.r_sample_stride != a.c_sample_stride || a.r_ld != a.c_ld) return DS_EUNSUPPORTED;
     if (!ch.Wt || !ch.C || (ch.act != DS_ACT_NONE && ch.act != DS_ACT_RELU) || (ch.tab_ld % 4)) return DS_EUNSUPPORTED;
     // 16-byte pieces of the second output and of its weights, float4 reads of its batch-norm constants
     if ((ch.c_sample_stride % 8) || (ch.c_ld > 0 && ch.c_ld % 8) || (ch.w_ld % 8) ||
         (((uintptr_t)ch.scale | (uintptr_t)ch.shift | (uintptr_t)ch.C | (uintptr_t)ch.Wt) & 15))
         return DS_EUNSUPPORTED;
-    for (int t = 0; t < a.gt.T; ++t)
-        if (ch.k_out[t] > 64 || (ch.k_out[t] > 0 && ch.k_out[t] % 8)) return DS_EUNSUPPORTED;
+    int k2max = 0;
+    for (int t = 0; t < a.gt.T; ++t) {
+        if (ch.k_out[t] > 128 || (ch.k_out[t] > 0 && ch.k_out[t] % 8)) return DS_EUNSUPPORTED;
+        k2max = ch.k_out[t] > k2max ? ch.k_out[t] : k2max;
+    }
+    if (((long long)k2max * ch.w_ld + max_kout) * 2 >= 0x7fffffffLL) return DS_EUNSUPPORTED;   // 32-bit weight offsets
     const int32_t rc = thin_configure();
     if (rc != DS_OK) return rc;
     ProfScope prof(DS_K_THIN, s);
-    hipLaunchKernelGGL((thin_kernel<true, 2, true>), dim3((unsigned)max_mtiles), dim3(NT), smem_bytes_chain(), s, a, max_mtiles, ch);
+    if (kmax <= 64 && k2max <= 64)
+        hipLaunchKernelGGL((thin_kernel<true, 2, true>), dim3((unsigned)max_mtiles), dim3(NT), smem_bytes_chain(), s, a, max_mtiles, ch);
+    else
+        hipLaunchKernelGGL((thin_kernel<true, 4, true, 4>), dim3((unsigned)max_mtiles), dim3(NT), smem_bytes(4), s, a, max_mtiles, ch);
     DS_CHECK_LAUNCH("chained thin layers");
     return DS_OK;
 }
