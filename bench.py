@@ -354,6 +354,17 @@ def run_net(workload, args, steps, warmup, with_cpu_baseline):
                                                            "frac": rr["frac_mfma"] if roof == "mfma" else rr["frac_hbm"]}
                 per_kernel[kern] = entry
             roofline["per_kernel"] = per_kernel
+            # the class as a whole under each roof: the launches above the ridge against the matrix peak, the rest against HBM
+            by_roof = {}
+            for roof in ("mfma", "hbm"):
+                part = [r for r in gsel if ("mfma" if r["flops"] / max(r["bytes"], 1.0) >= RIDGE else "hbm") == roof]
+                if part:
+                    t_ms = sum(r["us"] for r in part) * 1e-3
+                    rr = rates(sum(r["flops"] for r in part), sum(r["bytes"] for r in part), t_ms, True)
+                    by_roof[roof] = {"launches": len(part), "ms_per_step": t_ms, "tflops": rr["tflops"],
+                                     "algorithmic_gbs": rr["algorithmic_gbs"],
+                                     "frac": rr["frac_mfma"] if roof == "mfma" else rr["frac_hbm"]}
+            roofline["by_roof"] = by_roof
         # every kernel class with its algorithmic rates (same events, same sampled steps)
         merged = dict(prof)
         for k, (t, cnt) in merged.items():
